@@ -1,0 +1,296 @@
+"""Pins for oracle/transformer.py against things other than itself: PyTorch's own
+LayerNorm / multi-head attention / pre-LN encoder and decoder layers (library
+routines), closed forms with most weights zeroed, causality, and the residual
+structure of the proposal heads (Section 6, Figure 3).  Then the decoding-level
+guarantees of Sections 3-4 on real (tiny, random) Transformers, including the
+brute-force definition of k-hat on a tiny vocabulary."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import (CombinedModel, blockwise_decode, blockwise_decode_two_calls, feed_forward,
+                    greedy_decode, layer_norm, multi_head_attention, scorers, softmax_rows)
+
+torch.set_grad_enabled(False)
+
+
+def tiny_cfg(**kw):
+    base = dict(name="T", index=7, n_enc=2, n_dec=2, d_model=16, n_heads=2, d_ff=32, vocab=11,
+                k=3, batch=1, max_src=6, max_out=8, dtype="f32", eos_id=-1, src_kind="uniform3")
+    base.update(kw)
+    return workloads.Config(**base)
+
+
+def build(cfg, seed=0, std=0.3):
+    w = workloads.make_weights(cfg, seed=seed, std=std)
+    return CombinedModel(w, cfg.n_enc, cfg.n_dec, cfg.n_heads, cfg.k, cfg.ln_eps), w
+
+
+def t64(a):
+    return torch.tensor(np.asarray(a), dtype=torch.float64)
+
+
+# ----------------------------------------------------------------------------- sub-blocks
+
+def test_layer_norm_against_torch_and_moments():
+    rng = np.random.default_rng(0)
+    x, g, b = rng.normal(size=(5, 12)), rng.normal(size=12), rng.normal(size=12)
+    ref = torch.nn.functional.layer_norm(t64(x), (12,), t64(g), t64(b), eps=1e-6).numpy()
+    np.testing.assert_allclose(layer_norm(x, g, b, 1e-6), ref, atol=1e-12)
+    y = layer_norm(x, np.ones(12), np.zeros(12), 0.0)
+    np.testing.assert_allclose(y.mean(-1), 0, atol=1e-12)
+    np.testing.assert_allclose(y.var(-1), 1, atol=1e-12)
+
+
+def test_softmax_rows():
+    rng = np.random.default_rng(1)
+    s = rng.normal(size=(4, 7)) * 30
+    vis = rng.random((4, 7)) < 0.6
+    vis[:, 0] = True
+    p = softmax_rows(s, vis)
+    np.testing.assert_allclose(p.sum(-1), 1, atol=1e-12)
+    assert np.all(p[~vis] == 0)
+    ref = torch.softmax(t64(s).masked_fill(~torch.tensor(vis), -math.inf), -1).numpy()
+    np.testing.assert_allclose(p, ref, atol=1e-12)
+
+
+@pytest.mark.parametrize("mask_kind", ["causal", "full", "random"])
+def test_attention_against_torch(mask_kind):
+    rng = np.random.default_rng(2)
+    d, h, tq = 12, 3, 5
+    tk = tq if mask_kind == "causal" else 7
+    xq, xkv = rng.normal(size=(tq, d)), rng.normal(size=(tk, d))
+    if mask_kind == "causal":
+        xkv = xq
+    wq, wk, wv, wo = (rng.normal(size=(d, d)) * 0.4 for _ in range(4))
+    vis = {"causal": np.tril(np.ones((tq, tk), bool)), "full": np.ones((tq, tk), bool),
+           "random": rng.random((tq, tk)) < 0.5}[mask_kind]
+    vis[:, 0] = True
+    mine = multi_head_attention(xq, xkv, wq, wk, wv, wo, h, vis)
+    # torch's routine takes [T, batch, d] and out x in weights
+    ref, _ = torch.nn.functional.multi_head_attention_forward(
+        t64(xq)[:, None], t64(xkv)[:, None], t64(xkv)[:, None], d, h,
+        in_proj_weight=None, in_proj_bias=None, bias_k=None, bias_v=None, add_zero_attn=False,
+        dropout_p=0.0, out_proj_weight=t64(wo.T), out_proj_bias=None, training=False,
+        attn_mask=~torch.tensor(vis), use_separate_proj_weight=True,
+        q_proj_weight=t64(wq.T), k_proj_weight=t64(wk.T), v_proj_weight=t64(wv.T), need_weights=False)
+    np.testing.assert_allclose(mine, ref[:, 0].numpy(), atol=1e-10)
+
+
+def test_attention_single_key_returns_value():
+    rng = np.random.default_rng(3)
+    d = 8
+    xq, xkv = rng.normal(size=(3, d)), rng.normal(size=(1, d))
+    wq, wk, wv, wo = (rng.normal(size=(d, d)) for _ in range(4))
+    out = multi_head_attention(xq, xkv, wq, wk, wv, wo, 2, np.ones((3, 1), bool))
+    np.testing.assert_allclose(out, np.repeat(xkv @ wv @ wo, 3, 0), atol=1e-12)
+
+
+def _load_attn(mha, w, prefix):
+    d = w[prefix + ".wq"].shape[0]
+    mha.in_proj_weight.copy_(t64(np.concatenate([w[prefix + ".wq"].T, w[prefix + ".wk"].T, w[prefix + ".wv"].T])))
+    mha.in_proj_bias.zero_()
+    mha.out_proj.weight.copy_(t64(w[prefix + ".wo"].T))
+    mha.out_proj.bias.zero_()
+    assert mha.in_proj_weight.shape == (3 * d, d)
+
+
+def _load_common(layer, w, p, ffn, norms):
+    layer.linear1.weight.copy_(t64(w[ffn + ".w1"].T)); layer.linear1.bias.copy_(t64(w[ffn + ".b1"]))
+    layer.linear2.weight.copy_(t64(w[ffn + ".w2"].T)); layer.linear2.bias.copy_(t64(w[ffn + ".b2"]))
+    for mod, name in norms:
+        mod.weight.copy_(t64(w[name + ".g"])); mod.bias.copy_(t64(w[name + ".b"]))
+
+
+def test_encoder_and_decoder_stacks_against_torch_layers():
+    """One whole pre-LN encoder stack and decoder stack vs torch.nn.Transformer*Layer
+    (norm_first=True, ReLU) loaded with the same numbers."""
+    cfg = tiny_cfg()
+    model, w = build(cfg, seed=5)
+    d, h, f = cfg.d_model, cfg.n_heads, cfg.d_ff
+    src = [3, 9, 4, 10, 5]
+    prefix = [6, 3, 8, 7]
+
+    x = t64(math.sqrt(d) * model.w["emb"][src] + model.w["pos_src"][:len(src)])[None]
+    for l in range(cfg.n_enc):
+        layer = torch.nn.TransformerEncoderLayer(d, h, f, dropout=0.0, activation="relu",
+                                                 layer_norm_eps=cfg.ln_eps, batch_first=True,
+                                                 norm_first=True).double()
+        _load_attn(layer.self_attn, model.w, f"enc.{l}.self")
+        _load_common(layer, model.w, None, f"enc.{l}.ffn", [(layer.norm1, f"enc.{l}.ln1"), (layer.norm2, f"enc.{l}.ln2")])
+        x = layer(x)
+    mem_ref = torch.nn.functional.layer_norm(x, (d,), t64(model.w["enc.lnf.g"]), t64(model.w["enc.lnf.b"]), cfg.ln_eps)
+    memory = model.encode(src)
+    np.testing.assert_allclose(memory, mem_ref[0].numpy(), atol=1e-10)
+
+    t1 = len(prefix) + 1
+    u = np.zeros((t1, d)); u[1:] = math.sqrt(d) * model.w["emb"][prefix]
+    y = t64(u + model.w["pos_tgt"][:t1])[None]
+    causal = torch.triu(torch.ones(t1, t1, dtype=torch.bool), 1)
+    for l in range(cfg.n_dec):
+        layer = torch.nn.TransformerDecoderLayer(d, h, f, dropout=0.0, activation="relu",
+                                                 layer_norm_eps=cfg.ln_eps, batch_first=True,
+                                                 norm_first=True).double()
+        _load_attn(layer.self_attn, model.w, f"dec.{l}.self")
+        _load_attn(layer.multihead_attn, model.w, f"dec.{l}.cross")
+        _load_common(layer, model.w, None, f"dec.{l}.ffn",
+                     [(layer.norm1, f"dec.{l}.ln1"), (layer.norm2, f"dec.{l}.ln2"), (layer.norm3, f"dec.{l}.ln3")])
+        y = layer(y, mem_ref, tgt_mask=causal)
+    h_ref = torch.nn.functional.layer_norm(y, (d,), t64(model.w["dec.lnf.g"]), t64(model.w["dec.lnf.b"]), cfg.ln_eps)
+    np.testing.assert_allclose(model.decoder_states(memory, prefix), h_ref[0].numpy(), atol=1e-10)
+
+
+def test_embedding_scale_positions_and_tied_projection_closed_form():
+    """With every sublayer matrix zeroed the network collapses to
+    h_t = LN_f(sqrt(d) E[y_t] + pos_t)  (zero vector at t = 0) and
+    z_i = (h_t + b2_i) . E[v]; computed here with explicit loops."""
+    cfg = tiny_cfg(n_enc=1, n_dec=1)
+    _, w = build(cfg, seed=9)
+    for n in w:
+        if any(n.endswith(s) for s in (".wo", ".w2", ".b2")) and not n.startswith("head"):
+            w[n] = np.zeros_like(w[n])
+    w["head.w2"] = np.zeros_like(w["head.w2"])
+    model = CombinedModel(w, 1, 1, cfg.n_heads, cfg.k, cfg.ln_eps)
+    mem = model.encode([3, 4])
+    prefix = [5, 9]
+    z = model.all_position_logits(mem, prefix)
+    d = cfg.d_model
+    for t in range(3):
+        v = [(0.0 if t == 0 else math.sqrt(d) * float(w["emb"][prefix[t - 1], c])) + float(w["pos_tgt"][t, c])
+             for c in range(d)]
+        mu = sum(v) / d
+        var = sum((a - mu) ** 2 for a in v) / d
+        hvec = [(a - mu) / math.sqrt(var + cfg.ln_eps) * float(w["dec.lnf.g"][c]) + float(w["dec.lnf.b"][c])
+                for c, a in enumerate(v)]
+        for i in range(cfg.k):
+            for tok in range(cfg.vocab):
+                ref = sum((hvec[c] + float(w["head.b2"][i, c])) * float(w["emb"][tok, c]) for c in range(d))
+                assert abs(z[t, i, tok] - ref) < 1e-10
+
+
+def test_heads_are_residual_ffns_with_shared_projection():
+    cfg = tiny_cfg()
+    model, w = build(cfg, seed=11)
+    rng = np.random.default_rng(0)
+    h = rng.normal(size=(4, cfg.d_model))
+    o = model.head_outputs(h)
+    assert o.shape == (4, cfg.k, cfg.d_model)
+    for i in range(cfg.k):
+        ref = h + np.maximum(h @ model.w["head.w1"][i] + model.w["head.b1"][i], 0) @ model.w["head.w2"][i] \
+            + model.w["head.b2"][i]
+        np.testing.assert_allclose(o[:, i], ref, atol=1e-12)
+        # same thing through torch's linear layers
+        lin1 = torch.nn.functional.linear(t64(h), t64(model.w["head.w1"][i].T), t64(model.w["head.b1"][i]))
+        lin2 = torch.nn.functional.linear(torch.relu(lin1), t64(model.w["head.w2"][i].T), t64(model.w["head.b2"][i]))
+        np.testing.assert_allclose(o[:, i], (t64(h) + lin2).numpy(), atol=1e-12)
+    # zero second layers: every head scores exactly like the bare decoder output
+    w0 = dict(w); w0["head.w2"] = np.zeros_like(w["head.w2"]); w0["head.b2"] = np.zeros_like(w["head.b2"])
+    m0 = CombinedModel(w0, cfg.n_enc, cfg.n_dec, cfg.n_heads, cfg.k)
+    z = m0.logits(h)
+    for i in range(cfg.k):
+        np.testing.assert_allclose(z[:, i], h @ m0.w["emb"].T, atol=1e-12)
+    # heads differ from each other otherwise, and k' < k uses the first k' heads
+    z = model.logits(h)
+    assert not np.allclose(z[:, 0], z[:, 1])
+    np.testing.assert_array_equal(model.logits(h, 2), z[:, :2])
+
+
+def test_causality_and_parallel_scoring():
+    """h_s depends on y_{<=s} only, so one pass over prefix+block gives the same rows
+    as one full evaluation per row (the property Section 3 relies on)."""
+    cfg = tiny_cfg()
+    model, _ = build(cfg, seed=13)
+    mem = model.encode([3, 4, 5, 6])
+    a = [4, 7, 9, 3, 5]
+    b = [4, 7, 9, 10, 8]
+    ha, hb = model.decoder_states(mem, a), model.decoder_states(mem, b)
+    np.testing.assert_allclose(ha[:4], hb[:4], atol=1e-12)
+    assert not np.allclose(ha[4], hb[4])
+    allz = model.all_position_logits(mem, a)
+    for s in range(len(a) + 1):
+        np.testing.assert_allclose(allz[s], model.next_logits(mem, a[:s]), atol=1e-10)
+    score, block = scorers(model, [3, 4, 5, 6])
+    rows = block(a[:2], a[2:])
+    for r in range(1, 4):
+        np.testing.assert_allclose(rows[r - 1], score(a[:2 + r]), atol=1e-10)
+    # the source matters
+    assert not np.allclose(model.encode([3, 4, 5, 6]), model.encode([3, 4, 6, 5]))
+
+
+def test_gemm_against_triple_loop():
+    rng = np.random.default_rng(17)
+    x, w1, b1 = rng.normal(size=(3, 4)), rng.normal(size=(4, 5)), rng.normal(size=5)
+    w2, b2 = rng.normal(size=(5, 4)), rng.normal(size=4)
+    out = feed_forward(x, w1, b1, w2, b2)
+    for r in range(3):
+        hid = [max(0.0, sum(x[r, c] * w1[c, j] for c in range(4)) + b1[j]) for j in range(5)]
+        for c in range(4):
+            assert abs(out[r, c] - (sum(hid[j] * w2[j, c] for j in range(5)) + b2[c])) < 1e-12
+
+
+# ----------------------------------------------------------------------------- decoding on real models
+
+@pytest.mark.parametrize("seed,k", [(0, 1), (1, 2), (2, 3), (3, 4)])
+def test_blockwise_equals_greedy_tiny_transformers(seed, k):
+    cfg = tiny_cfg(k=4, vocab=5, eos_id=2, max_out=10)
+    model, _ = build(cfg, seed=seed, std=0.6)
+    score, block = scorers(model, [3, 4, 3, 4], k=k)
+    gr = greedy_decode(score, cfg.max_out, cfg.eos_id)
+    seq = blockwise_decode(score, k, cfg.max_out, cfg.eos_id)                 # row by row
+    par = blockwise_decode(score, k, cfg.max_out, cfg.eos_id, block_score=block)  # one pass per step
+    two = blockwise_decode_two_calls(score, k, cfg.max_out, cfg.eos_id)
+    assert seq.tokens == gr.tokens == par.tokens == two.tokens
+    assert seq.block_sizes == par.block_sizes == two.block_sizes
+    assert all(1 <= s <= k for s in seq.block_sizes) and sum(seq.block_sizes) == len(gr.tokens)
+    assert seq.invocations == len(seq.steps) + 1 and two.invocations == 2 * len(two.steps)
+    ones = blockwise_decode(score, k, cfg.max_out, cfg.eos_id, schedule=[1] * 64)
+    assert ones.tokens == gr.tokens
+    if k == 1:
+        assert seq.block_sizes == [1] * len(gr.tokens)
+
+
+def test_khat_brute_force_tiny_vocab():
+    """V = 4: k-hat from its definition (k sequential greedy calls) and by enumerating
+    all V^k candidate blocks: exactly one block of each length is greedy-consistent."""
+    found_long = False
+    for seed in range(6):
+        cfg = tiny_cfg(k=3, vocab=4, d_model=8, n_heads=2, d_ff=16, max_out=6, n_enc=1, n_dec=1)
+        model, _ = build(cfg, seed=100 + seed, std=0.8)
+        score, _ = scorers(model, [1, 2, 3])
+        dec = blockwise_decode(score, 3, 6)
+        gr = greedy_decode(score, 6)
+        assert dec.tokens == gr.tokens
+        for st in dec.steps:
+            pfx = dec.tokens[:st.j]
+            consistent = {n: [] for n in (1, 2, 3)}
+            for cand in itertools.product(range(4), repeat=3):
+                for n in (1, 2, 3):
+                    if all(cand[i] == int(np.argmax(score(pfx + list(cand[:i]))[0])) for i in range(n)):
+                        consistent[n].append(cand[:n])
+            for n in (1, 2, 3):
+                assert len(set(consistent[n])) == 1
+            greedy3 = list(consistent[3][0])
+            lcp = 0
+            while lcp < 3 and st.proposals[lcp] == greedy3[lcp]:
+                lcp += 1
+            assert st.k_verified == lcp >= 1
+            found_long |= lcp > 1
+    assert found_long            # the cases above do exercise k-hat > 1
+
+
+def test_c0_blockwise_equals_greedy():
+    """Workload C0 (tiny fp32 config): exact-match blockwise decoding reproduces greedy."""
+    cfg = workloads.C0
+    w = workloads.make_weights(cfg)
+    model = CombinedModel(w, cfg.n_enc, cfg.n_dec, cfg.n_heads, cfg.k, cfg.ln_eps)
+    src, src_len = workloads.make_sources(cfg)
+    score, block = scorers(model, src[0, :src_len[0]])
+    gr = greedy_decode(score, cfg.max_out, cfg.eos_id)
+    dec = blockwise_decode(score, cfg.k, cfg.max_out, cfg.eos_id, block_score=block)
+    assert dec.tokens == gr.tokens
+    assert 1 <= len(gr.tokens) <= cfg.max_out
+    assert dec.invocations == len(dec.steps) + 1
