@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the blockwise-parallel-decoding step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+Workload: Transformer-big, k = 10, bf16 (benchmark configs[2], batch 1: the paper decodes
+single sentences) with an imposed acceptance schedule of mean 5 (the paper's trained k = 10
+model reaches 4.95, Table 1); the batch-32 ragged workload (configs[3], mean 3) is measured in
+the same run and reported under "batch32".  A "step" is one bpd_step: decoder forward over the
+k proposed positions, k heads, vocabulary projection + argmax of the k x k outputs, verify /
+accept / KV commit.  Inputs are seeded and synthetic (workloads.py) and already resident in
+HBM when the timed region starts; encoder runs and the first invocation of each sentence are
+outside the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads as wl  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def step_bytes(cfg) -> dict:
+    """Algorithmic HBM bytes of one step at batch 1: every weight read once (bf16)."""
+    d, F, V, k, nl = cfg.d_model, cfg.d_ff, cfg.vocab, cfg.k, cfg.n_dec
+    return {
+        "layers": nl * (6 * d * d + 2 * d * F) * 2,
+        "head_hidden": k * d * F * 2,
+        "head_out": k * F * d * 2,
+        "vocab": V * d * 2,
+    }
+
+
+def step_flops(cfg, B: int, L_mean: float, S_mean: float) -> dict:
+    d, F, V, k, nl = cfg.d_model, cfg.d_ff, cfg.vocab, cfg.k, cfg.n_dec
+    M = B * k
+    return {
+        "layers": 2 * M * nl * (6 * d * d + 2 * d * F) + nl * B * 4 * k * d * (L_mean + k + S_mean),
+        "head_hidden": 2 * M * d * k * F,
+        "head_out": 2 * M * k * F * d,
+        "vocab": 2 * M * k * V * d,
+    }
+
+
+def steps_needed(sched_col: np.ndarray, max_len: int) -> int:
+    c = np.cumsum(sched_col)
+    return int(np.argmax(c >= max_len)) + 1 if (c >= max_len).any() else len(sched_col)
+
+
+def run_sessions(ctx, cfg, src, n, max_len, sched, k, total_steps, torch):
+    """Time `total_steps` bpd_step calls spread over as many decode sessions as needed.
+    Returns (seconds, accepted tokens, steps)."""
+    B = src.shape[0]
+    per_session = max(steps_needed(sched[:, b], int(max_len[b])) for b in range(B))
+    sched_dev = torch.from_numpy(np.ascontiguousarray(sched[:per_session])).cuda()
+    elapsed, accepted, done = 0.0, 0, 0
+    while done < total_steps:
+        ctx.bpd_encode(src, n, max_len)               # untimed: encoder + first invocation
+        todo = min(per_session, total_steps - done)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(todo):
+            ctx.bpd_step(k, sched_dev[s])
+        torch.cuda.synchronize()
+        elapsed += time.perf_counter() - t0
+        accepted += int(ctx.bpd_get_stats().accepted_total)
+        done += todo
+    return elapsed, accepted, done
+
+
+def profile_phase(ctx, phase, cfg, src, n, max_len, sched, k, steps, torch):
+    ctx.bpd_profile_enable(phase)
+    run_sessions(ctx, cfg, src, n, max_len, sched, k, steps, torch)
+    ms, launches = ctx.bpd_profile_read()
+    ctx.bpd_profile_enable(0)
+    return ms / max(1, launches)
+
+
+def cpu_baseline(cfg, weights, src, n, sched_col, tokens_target=40):
+    """The oracle as it stands, on the host cores: blockwise decoding of the first
+    `tokens_target` tokens of the batch-1 sentence under the same imposed schedule."""
+    from oracle import CombinedModel, blockwise_decode, scorers
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    model = CombinedModel(weights, cfg.n_enc, cfg.n_dec, cfg.n_heads, cfg.k, cfg.ln_eps)
+    score, block = scorers(model, src[0, :n[0]])
+    t0 = time.perf_counter()
+    dec = blockwise_decode(score, cfg.k, tokens_target, -1, schedule=list(sched_col), block_score=block)
+    dt = time.perf_counter() - t0
+    return {"value": len(dec.tokens) / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"oracle/ blockwise_decode (fp64 numpy, full recomputation per step) of the first "
+                      f"{len(dec.tokens)} tokens of the batch-1 sentence, {len(dec.steps)} steps, same schedule",
+            "ms_per_step": 1e3 * dt / max(1, len(dec.steps))}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-batch32", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (every box here has one); "
+              "use --gpus 1.  How the path would shard is described in DESIGN.md.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1811_03115_amd import binding
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+
+    cfg1, cfg32 = wl.C2, wl.C3
+    weights = wl.make_weights(cfg1)
+    ctx = binding.Context(binding.config_from_workload(cfg32))
+    ctx.bpd_load_weights(weights)
+    k = cfg1.k
+
+    # ---------------------------------------------------------------- batch 1 (headline)
+    src, n = wl.make_sources(cfg1)
+    max_len = wl.make_max_len(cfg1, n)
+    sched = wl.make_schedule(cfg1, 5, cfg1.max_out)
+    run_sessions(ctx, cfg1, src, n, max_len, sched, k, args.warmup, torch)
+    sec, accepted, steps = run_sessions(ctx, cfg1, src, n, max_len, sched, k, args.steps, torch)
+    ms_step = 1e3 * sec / steps
+    nbytes = step_bytes(cfg1)
+    total_bytes = sum(nbytes.values())
+    kern = {}
+    for name, phase in (("head_hidden", binding.PHASE_HEAD_HIDDEN), ("head_out", binding.PHASE_HEAD_OUT),
+                        ("vocab", binding.PHASE_VOCAB), ("layers", binding.PHASE_LAYERS)):
+        ms = profile_phase(ctx, phase, cfg1, src, n, max_len, sched, k, min(args.steps, 60), torch)
+        kern[name] = {"ms": ms, "GBps": nbytes[name] / ms / 1e6}
+    dom = max(("head_hidden", "head_out", "vocab"), key=lambda q: kern[q]["ms"])
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": kern[dom]["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": kern[dom]["GBps"] / HBM_PEAK_GBS, "traffic": None,
+                "step_achieved": total_bytes / (ms_step * 1e6), "step_frac": total_bytes / (ms_step * 1e6) / HBM_PEAK_GBS,
+                "kernels": kern}
+
+    out = {
+        "metric": "accepted tokens/s (bpd_step, Transformer-big k=10, batch 1)",
+        "value": accepted / sec, "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "C2: Transformer-big 6+6 layers d=1024 F=4096 V=32768, k=10, batch 1, "
+                               "imposed acceptance schedule mean 5", "batch": 1, "k": k,
+                   "scored_positions_per_s": k / (ms_step * 1e-3), "mean_accepted": accepted / steps},
+        "roofline": roofline,
+    }
+
+    # ---------------------------------------------------------------- batch 32
+    if not args.no_batch32:
+        src32, n32 = wl.make_sources(cfg32)
+        max32 = wl.make_max_len(cfg32, n32)
+        sched32 = wl.make_schedule(cfg32, 3, cfg32.max_out)
+        steps32 = max(20, args.steps // 4)
+        run_sessions(ctx, cfg32, src32, n32, max32, sched32, k, max(4, args.warmup // 4), torch)
+        sec32, acc32, st32 = run_sessions(ctx, cfg32, src32, n32, max32, sched32, k, steps32, torch)
+        ms32 = 1e3 * sec32 / st32
+        fl = step_flops(cfg32, cfg32.batch, 32.0, float(n32.mean()))
+        vocab_ms = profile_phase(ctx, binding.PHASE_VOCAB, cfg32, src32, n32, max32, sched32, k, min(steps32, 30), torch)
+        out["batch32"] = {
+            "workload": "C3: same model, batch 32, ragged source lengths and budgets, imposed schedule mean 3",
+            "value": acc32 / sec32, "unit": "tokens/s", "ms_per_step": ms32, "steps": st32,
+            "scored_positions_per_s": cfg32.batch * k / (ms32 * 1e-3),
+            "roofline": {"bound": "mfma", "kernel": "vocab", "achieved": fl["vocab"] / (vocab_ms * 1e9),
+                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": fl["vocab"] / (vocab_ms * 1e9) / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                         "kernel_ms": vocab_ms,
+                         "step_achieved": sum(fl.values()) / (ms32 * 1e9),
+                         "step_frac": sum(fl.values()) / (ms32 * 1e9) / MFMA_BF16_PEAK_TFLOPS},
+        }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg1, weights, src, n, sched[:, 0])
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

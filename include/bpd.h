@@ -1,0 +1,182 @@
+/*
+ * libbpd — blockwise parallel decoding (Stern, Shazeer, Uszkoreit, NeurIPS 2018) on one
+ * MI355X (gfx950).  C ABI: plain pointers and sizes, no C++ or torch types.
+ *
+ * The library implements the decoding loop of the paper's Sections 3 and 4 for the combined
+ * scoring-and-proposal model of Section 6:
+ *
+ *   given a source x, keep a hypothesis y-hat of length j and k proposals P_1..P_k for the
+ *   next k tokens; one model invocation scores the k proposed positions against the cached
+ *   prefix and yields, at every block row i' and for every head i, the argmax
+ *   A[i'][i] of p_i(y_{j+i'+i} | y-hat_{<=j}, P_1..P_i', x); the longest prefix of P that the
+ *   base model p_1 would have produced greedily is appended (k-hat tokens, 1 <= k-hat <= k)
+ *   and row k-hat of A becomes the next block of proposals.
+ *
+ * All device work is enqueued on the HIP stream given at creation; unless stated otherwise a
+ * call does not synchronise.  Every function returns 0 (BPD_OK) or a negative error code and
+ * never throws or aborts; bpd_last_error() gives a message.  On an argument error the decode
+ * state is left unchanged.
+ *
+ * Pointer arguments marked [host|device] may be either (they are copied with
+ * hipMemcpyDefault); arguments marked [device] are dereferenced by kernels.
+ */
+#ifndef BPD_H
+#define BPD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BPD_OK           0
+#define BPD_E_ARG       (-1)  /* null pointer, size out of range, k > k_max, ...            */
+#define BPD_E_STATE     (-2)  /* call out of order: step before encode, encode before load  */
+#define BPD_E_CAPACITY  (-3)  /* workspace too small, batch / source length over the limits */
+#define BPD_E_WEIGHTS   (-4)  /* unknown tensor name, wrong shape, tensors missing           */
+#define BPD_E_HIP       (-5)  /* a HIP runtime call or kernel launch failed                  */
+
+#define BPD_F32  0
+#define BPD_BF16 1
+
+typedef struct bpd_ctx bpd_ctx;   /* opaque; owns small host structs only */
+
+/* Model and capacity description.  k_max counts all heads p_1..p_k (Section 3: p_1 is the
+ * base model, p_2..p_k the proposal models; Section 6: p_1 passes through a head as well). */
+typedef struct {
+  int32_t n_enc_layers, n_dec_layers;
+  int32_t d_model, n_heads, d_ff, vocab;
+  int32_t k_max;                      /* number of heads = largest block size, <= 16        */
+  int32_t max_batch, max_src_len, max_out_len;
+  int32_t dtype;                      /* BPD_F32: fp32 everywhere.  BPD_BF16: bf16 weights,
+                                         bf16 K/V caches and GEMM inputs, fp32 accumulation,
+                                         fp32 residual stream / LayerNorm / softmax          */
+  int32_t eos_id;                     /* < 0: fixed-length decoding (Section 2, images)      */
+  int32_t pad_id;                     /* fills out_ids beyond out_len                        */
+  float   ln_eps;
+} bpd_config;
+
+/* One named weight tensor handed to bpd_load_weights.  Row-major, shape[0..ndim).  Matrices
+ * are input-major (y = x W, W[in][out]).  Names (l = layer index):
+ *   emb [V,d]   pos_src [max_src_len,d]   pos_tgt [max_out_len+k_max+1,d]
+ *   enc.l.ln1.g/.b [d]  enc.l.self.wq/.wk/.wv/.wo [d,d]  enc.l.ln2.g/.b  enc.l.ffn.w1 [d,F] .b1 [F] .w2 [F,d] .b2 [d]
+ *   enc.lnf.g/.b
+ *   dec.l.ln1.g/.b  dec.l.self.wq/.wk/.wv/.wo  dec.l.ln2.g/.b  dec.l.cross.wq/.wk/.wv/.wo
+ *   dec.l.ln3.g/.b  dec.l.ffn.w1/.b1/.w2/.b2      dec.lnf.g/.b
+ *   head.w1 [k_max,d,F]  head.b1 [k_max,F]  head.w2 [k_max,F,d]  head.b2 [k_max,d]   (Section 6) */
+typedef struct {
+  const char* name;
+  const void* data;        /* [host|device], see on_device                                  */
+  int32_t dtype;           /* BPD_F32 (float) or BPD_BF16 (uint16 bit patterns)             */
+  int32_t ndim;
+  int64_t shape[4];
+  int32_t on_device;       /* 0: host memory, 1: device memory                              */
+} bpd_tensor;
+
+/* Counters since the last bpd_encode.  mean accepted block size (Section 7.1) =
+ * accepted_total / (steps summed over live sequences) = accepted_total / seq_steps.        */
+typedef struct {
+  int64_t steps;           /* steps in which at least one sequence was still decoding       */
+  int64_t invocations;     /* model invocations = steps + 1 (Section 4)                     */
+  int64_t seq_steps;       /* sum over steps of sequences still decoding                    */
+  int64_t accepted_total;  /* sum of k-hat over sequences and steps                         */
+  int64_t hist[17];        /* hist[a] = number of (sequence, step) pairs with k-hat = a     */
+  int32_t finished;        /* sequences that have ended                                     */
+} bpd_stats;
+
+/* Bytes of device workspace bpd_create needs for this configuration (weights in kernel
+ * layout, K/V caches, activations, decode state, a staging area for host weights).
+ * Returns 0 if the configuration is invalid. */
+size_t bpd_workspace_bytes(const bpd_config* cfg);
+
+/* Create a context on the current device.  workspace [device] is caller-owned, 256-byte
+ * aligned, at least bpd_workspace_bytes(cfg) bytes, and must outlive the context; the
+ * library allocates no device memory itself.  hip_stream is a hipStream_t (NULL = the
+ * default stream).  Errors: BPD_E_ARG, BPD_E_CAPACITY. */
+int bpd_create(const bpd_config* cfg, void* workspace, size_t workspace_bytes,
+               void* hip_stream, bpd_ctx** out);
+int bpd_destroy(bpd_ctx* ctx);
+
+/* Copy n named tensors into the workspace, converting to the kernel layout (bf16 MFMA tiles
+ * in BPD_BF16 mode).  The caller's buffers are not referenced after the call returns
+ * (the call synchronises the stream).  May be called several times; every tensor must have
+ * been loaded before bpd_encode.  Errors: BPD_E_WEIGHTS (unknown name / shape), BPD_E_ARG. */
+int bpd_load_weights(bpd_ctx* ctx, const bpd_tensor* tensors, int n);
+
+/* Condition on a batch of sources (Section 2: the input x) and start decoding:
+ * runs the encoder, fills the cross-attention K/V, resets the hypotheses (j = 0), and makes
+ * the first model invocation on the empty prefix, whose k_max argmaxes become the first
+ * proposals (the "+1" invocation of Section 4).
+ *   src_ids [host|device]  int32 [B, S] row-major, rows padded beyond src_len[b]
+ *   src_len [host|device]  int32 [B], 1 <= src_len[b] <= S
+ *   max_len [host|device]  int32 [B] output budget per sequence (1..max_out_len), or NULL
+ * Errors: BPD_E_STATE (weights missing), BPD_E_CAPACITY (B, S over the limits), BPD_E_ARG. */
+int bpd_encode(bpd_ctx* ctx, const int32_t* src_ids, const int32_t* src_len,
+               const int32_t* max_len, int B, int S);
+
+/* One combined verify + predict step with block size k (Sections 3 and 4), 1 <= k <= k_max,
+ * the same k on every step of a decode.
+ *   imposed_accept [host|device] int32 [B] or NULL.  NULL: exact-match verification
+ *       (k-hat = longest prefix of P equal to p_1's argmaxes).  Otherwise the verify outcome
+ *       is replaced by imposed_accept[b] (clamped to 1..k); the accepted tokens are still
+ *       P_1..P_k-hat and the next proposals still row k-hat of A.  Not in the paper: it lets
+ *       untrained heads exercise every accepted length.
+ *   accepted_len [host|device] int32 [B] or NULL: k-hat per sequence after the cut at the
+ *       first EOS (inclusive, cf. Section 7.4) and at max_len; 0 for sequences that had
+ *       already ended.  With a pageable host pointer the call waits for the copy.
+ * Errors: BPD_E_STATE (no bpd_encode yet), BPD_E_ARG. */
+int bpd_step(bpd_ctx* ctx, int k, const int32_t* imposed_accept, int32_t* accepted_len);
+
+/* Relaxed verification (Section 5), applies to later bpd_step / bpd_decode calls with
+ * imposed_accept == NULL:  a proposal is accepted if |P - argmax p_1| <= distance_eps
+ * (Section 5.2; 0 = exact match) and at least min_block tokens are taken (Section 5.3;
+ * 1 = no minimum).  Errors: BPD_E_ARG. */
+int bpd_set_acceptance(bpd_ctx* ctx, int distance_eps, int min_block);
+
+/* Repeat bpd_step until every sequence has ended (EOS accepted or max_len reached) or
+ * max_steps steps were made; synchronises.
+ *   schedule [host|device] int32 [max_steps, B] imposed accepted lengths, or NULL
+ *   out_ids  [host|device] int32 [B, max_out_len], pad_id beyond out_len[b]
+ *   out_len  [host|device] int32 [B]
+ *   stats    host pointer or NULL
+ * Errors: as bpd_step. */
+int bpd_decode(bpd_ctx* ctx, int k, const int32_t* schedule, int max_steps,
+               int32_t* out_ids, int32_t* out_len, bpd_stats* stats);
+
+/* Copy out the decode state (synchronises).  Any pointer may be NULL.  [host|device].
+ *   P [B,k_max] current proposals; A [B,k_max,k_max] argmax table of the last invocation
+ *   (A[b][i'][i] = head i+1 at block row i'+1); j [B] accepted lengths; finished [B] flags. */
+int bpd_get_state(bpd_ctx* ctx, int32_t* P, int32_t* A, int32_t* j, int32_t* finished);
+int bpd_get_output(bpd_ctx* ctx, int32_t* out_ids, int32_t* out_len);
+int bpd_get_stats(bpd_ctx* ctx, bpd_stats* stats);
+
+/* Overwrite the current proposals P [host|device] int32 [B, k_max] (teacher forcing: lets a
+ * test drive the cache along a given token sequence). */
+int bpd_set_proposals(bpd_ctx* ctx, const int32_t* P);
+
+/* Run the model invocation of the next step with block size k WITHOUT verifying or
+ * committing, and write all logits: logits [device] float [B, k, k, vocab],
+ * logits[b][i'][i][v] = score of head i+1 at block row i'+1.  The argmax table A is
+ * refreshed as by bpd_step; j, P and the caches' committed part are unchanged. */
+int bpd_debug_step_logits(bpd_ctx* ctx, int k, float* logits);
+
+/* Timing hook for benchmarks: when enabled, bpd_step brackets the kernels of one phase
+ * (BPD_PHASE_*) with HIP events on the context's stream; bpd_profile_read synchronises and
+ * returns the accumulated milliseconds and the number of launches since it was enabled. */
+#define BPD_PHASE_NONE         0
+#define BPD_PHASE_LAYERS       1   /* decoder layers (embedding .. final LayerNorm), many kernels */
+#define BPD_PHASE_HEAD_HIDDEN  2   /* heads, hidden layers: one GEMM kernel                       */
+#define BPD_PHASE_HEAD_OUT     3   /* heads, k output layers + residual: one grouped GEMM kernel  */
+#define BPD_PHASE_VOCAB        4   /* vocabulary projection + argmax: one kernel                  */
+#define BPD_PHASE_ACCEPT       5   /* verify / accept / commit                                    */
+#define BPD_PHASE_STEP         6   /* the whole step                                              */
+int bpd_profile_enable(bpd_ctx* ctx, int phase);
+int bpd_profile_read(bpd_ctx* ctx, double* total_ms, int64_t* launches);
+
+const char* bpd_last_error(const bpd_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BPD_H */

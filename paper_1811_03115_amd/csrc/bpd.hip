@@ -1,0 +1,762 @@
+// Host side of libbpd: workspace layout, weight loading, and the launch sequences behind
+// the C ABI declared in include/bpd.h.  Every step of the method runs in the kernels of
+// bpd_kernels.h; this file only orders them on the caller's stream.
+#include "../../include/bpd.h"
+#include "bpd_kernels.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <string>
+#include <vector>
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+
+struct Arena {
+  char* base;
+  size_t off = 0;
+  explicit Arena(char* b) : base(b) {}
+  void* take(size_t bytes) {
+    off = (off + ALIGN - 1) / ALIGN * ALIGN;
+    void* p = base + off;
+    off += bytes;
+    return p;
+  }
+};
+
+struct LnW { float *g, *b; };
+struct EncL { LnW ln1, ln2; void *wqkv, *wo, *w1, *w2; float *b1, *b2; };
+struct DecL { LnW ln1, ln2, ln3; void *wqkv, *wo, *cq, *co, *ckv, *w1, *w2; float *b1, *b2; };
+
+struct Layout {
+  // weights
+  void* emb; float *pos_src, *pos_tgt;
+  std::vector<EncL> enc; LnW enc_lnf;
+  std::vector<DecL> dec; LnW dec_lnf;
+  void *hw1, *hw2; float *hb1, *hb2;
+  // caches
+  void *selfK, *selfV, *crossK, *crossV;        // [n_dec][B][slots|max_src][d]
+  // decoder activations (M = max_batch * k_max rows)
+  float *x, *q, *h; void *xn, *attn, *ffh, *hn, *H, *O;
+  unsigned long long* keys;
+  // encoder activations (max_batch * max_src rows)
+  float *xe, *qe; void *xen, *ke, *ve, *attne, *ffhe, *mem;
+  // state
+  int *L, *j, *finished, *max_len, *src_len, *src_ids, *P, *A, *accepted, *out_ids, *step_counter, *imposed1, *sched;
+  long long* stats;
+  void* staging; size_t staging_bytes;
+  size_t total;
+};
+
+size_t act_size(const bpd_config& c) { return c.dtype == BPD_BF16 ? 2 : 4; }
+
+bool config_ok(const bpd_config& c) {
+  if (c.n_enc_layers < 1 || c.n_dec_layers < 1 || c.d_model < 32 || c.n_heads < 1) return false;
+  if (c.d_model % c.n_heads) return false;
+  const int dh = c.d_model / c.n_heads;
+  if (dh != 16 && dh != 64) return false;
+  if (c.d_model % 32 || c.d_ff % 32 || c.vocab % 16 || c.vocab < 16) return false;
+  if (c.k_max < 1 || c.k_max > 16) return false;
+  if (c.max_batch < 1 || c.max_src_len < 1 || c.max_out_len < 1) return false;
+  if (c.dtype != BPD_F32 && c.dtype != BPD_BF16) return false;
+  if (c.eos_id >= c.vocab || c.ln_eps <= 0.f) return false;
+  return true;
+}
+
+size_t build_layout(const bpd_config& c, char* base, Layout& L) {
+  Arena a(base);
+  const size_t d = c.d_model, F = c.d_ff, V = c.vocab, k = c.k_max, ws = act_size(c), as = act_size(c);
+  const size_t slots = (size_t)c.max_out_len + c.k_max + 1;
+  auto vec = [&](size_t n) { return (float*)a.take(n * 4); };
+  auto mat = [&](size_t kk, size_t nn) { return a.take(kk * nn * ws); };
+  auto ln = [&]() { LnW w; w.g = vec(d); w.b = vec(d); return w; };
+  L.emb = mat(V, d);
+  L.pos_src = vec((size_t)c.max_src_len * d);
+  L.pos_tgt = vec(slots * d);
+  L.enc.resize(c.n_enc_layers);
+  for (auto& e : L.enc) {
+    e.ln1 = ln(); e.wqkv = mat(d, 3 * d); e.wo = mat(d, d); e.ln2 = ln();
+    e.w1 = mat(d, F); e.b1 = vec(F); e.w2 = mat(F, d); e.b2 = vec(d);
+  }
+  L.enc_lnf = ln();
+  L.dec.resize(c.n_dec_layers);
+  for (auto& e : L.dec) {
+    e.ln1 = ln(); e.wqkv = mat(d, 3 * d); e.wo = mat(d, d);
+    e.ln2 = ln(); e.cq = mat(d, d); e.co = mat(d, d); e.ckv = mat(d, 2 * d);
+    e.ln3 = ln(); e.w1 = mat(d, F); e.b1 = vec(F); e.w2 = mat(F, d); e.b2 = vec(d);
+  }
+  L.dec_lnf = ln();
+  L.hw1 = mat(d, k * F); L.hb1 = vec(k * F); L.hw2 = mat(k * F, d); L.hb2 = vec(k * d);
+  const size_t B = c.max_batch, nd = c.n_dec_layers, S = c.max_src_len;
+  L.selfK = a.take(nd * B * slots * d * as); L.selfV = a.take(nd * B * slots * d * as);
+  L.crossK = a.take(nd * B * S * d * as);    L.crossV = a.take(nd * B * S * d * as);
+  const size_t M = B * k;
+  L.x = vec(M * d); L.q = vec(M * d); L.h = vec(M * d);
+  L.xn = a.take(M * d * as); L.attn = a.take(M * d * as); L.ffh = a.take(M * F * as);
+  L.hn = a.take(M * d * as); L.H = a.take(M * k * F * as); L.O = a.take(M * k * d * as);
+  L.keys = (unsigned long long*)a.take(M * k * 8);
+  const size_t Me = B * S;
+  L.xe = vec(Me * d); L.qe = vec(Me * d);
+  L.xen = a.take(Me * d * as); L.ke = a.take(Me * d * as); L.ve = a.take(Me * d * as);
+  L.attne = a.take(Me * d * as); L.ffhe = a.take(Me * F * as); L.mem = a.take(Me * d * as);
+  auto ints = [&](size_t n) { return (int*)a.take(n * 4); };
+  L.L = ints(B); L.j = ints(B); L.finished = ints(B); L.max_len = ints(B); L.src_len = ints(B);
+  L.src_ids = ints(Me); L.P = ints(B * k); L.A = ints(B * k * k); L.accepted = ints(B);
+  L.out_ids = ints(B * (size_t)c.max_out_len); L.step_counter = ints(1); L.imposed1 = ints(B);
+  L.sched = ints(B * (size_t)c.max_out_len);
+  L.stats = (long long*)a.take(32 * 8);
+  size_t biggest = V * d;
+  if (k * d * F > biggest) biggest = k * d * F;
+  L.staging_bytes = biggest * 4;
+  L.staging = a.take(L.staging_bytes);
+  L.total = (a.off + ALIGN - 1) / ALIGN * ALIGN;
+  return L.total;
+}
+
+enum Kind { MAT, MATK_CAT, MATK_SEP, EMB, VEC };
+struct WEntry {
+  Kind kind;
+  int nd; int64_t shape[4];
+  void* dst;
+  int K, N, ldw, n_off;      // matrices: source K x N, destination row length, column offset
+  bool loaded;
+};
+
+}  // namespace
+
+struct bpd_ctx {
+  bpd_config cfg;
+  hipStream_t stream;
+  Layout lay;
+  std::map<std::string, WEntry> table;
+  std::string err;
+  int B = 0, S = 0;
+  bool encoded = false;
+  int64_t steps = 0;
+  int distance_eps = 0, min_block = 1;
+  int* pinned = nullptr;       // small pinned host scratch
+  int prof_phase = 0;
+  std::vector<hipEvent_t> prof_ev;
+  size_t prof_used = 0;
+  int64_t prof_launches = 0;
+};
+
+namespace {
+
+int fail(bpd_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg;
+  return code;
+}
+#define HIPCHK(expr)                                                                   \
+  do {                                                                                 \
+    hipError_t _e = (expr);                                                            \
+    if (_e != hipSuccess)                                                              \
+      return fail(ctx, BPD_E_HIP, std::string(#expr) + ": " + hipGetErrorString(_e)); \
+  } while (0)
+#define LAUNCHCHK() HIPCHK(hipGetLastError())
+
+void add_entry(bpd_ctx* ctx, const std::string& name, Kind kind, std::vector<int64_t> shape, void* dst,
+               int K = 0, int N = 0, int ldw = 0, int n_off = 0) {
+  WEntry e{};
+  e.kind = kind; e.nd = (int)shape.size();
+  for (int i = 0; i < e.nd; ++i) e.shape[i] = shape[i];
+  e.dst = dst; e.K = K; e.N = N; e.ldw = ldw; e.n_off = n_off; e.loaded = false;
+  ctx->table[name] = e;
+}
+
+void build_table(bpd_ctx* ctx) {
+  const bpd_config& c = ctx->cfg;
+  Layout& L = ctx->lay;
+  const int d = c.d_model, F = c.d_ff, V = c.vocab, k = c.k_max;
+  const int slots = c.max_out_len + c.k_max + 1;
+  auto ln = [&](const std::string& p, LnW w) {
+    add_entry(ctx, p + ".g", VEC, {d}, w.g);
+    add_entry(ctx, p + ".b", VEC, {d}, w.b);
+  };
+  add_entry(ctx, "emb", EMB, {V, d}, L.emb, d, V, V, 0);
+  add_entry(ctx, "pos_src", VEC, {c.max_src_len, d}, L.pos_src);
+  add_entry(ctx, "pos_tgt", VEC, {slots, d}, L.pos_tgt);
+  for (int l = 0; l < c.n_enc_layers; ++l) {
+    const std::string p = "enc." + std::to_string(l);
+    EncL& e = L.enc[l];
+    ln(p + ".ln1", e.ln1); ln(p + ".ln2", e.ln2);
+    add_entry(ctx, p + ".self.wq", MAT, {d, d}, e.wqkv, d, d, 3 * d, 0);
+    add_entry(ctx, p + ".self.wk", MAT, {d, d}, e.wqkv, d, d, 3 * d, d);
+    add_entry(ctx, p + ".self.wv", MAT, {d, d}, e.wqkv, d, d, 3 * d, 2 * d);
+    add_entry(ctx, p + ".self.wo", MAT, {d, d}, e.wo, d, d, d, 0);
+    add_entry(ctx, p + ".ffn.w1", MAT, {d, F}, e.w1, d, F, F, 0);
+    add_entry(ctx, p + ".ffn.b1", VEC, {F}, e.b1);
+    add_entry(ctx, p + ".ffn.w2", MAT, {F, d}, e.w2, F, d, d, 0);
+    add_entry(ctx, p + ".ffn.b2", VEC, {d}, e.b2);
+  }
+  ln("enc.lnf", L.enc_lnf);
+  for (int l = 0; l < c.n_dec_layers; ++l) {
+    const std::string p = "dec." + std::to_string(l);
+    DecL& e = L.dec[l];
+    ln(p + ".ln1", e.ln1); ln(p + ".ln2", e.ln2); ln(p + ".ln3", e.ln3);
+    add_entry(ctx, p + ".self.wq", MAT, {d, d}, e.wqkv, d, d, 3 * d, 0);
+    add_entry(ctx, p + ".self.wk", MAT, {d, d}, e.wqkv, d, d, 3 * d, d);
+    add_entry(ctx, p + ".self.wv", MAT, {d, d}, e.wqkv, d, d, 3 * d, 2 * d);
+    add_entry(ctx, p + ".self.wo", MAT, {d, d}, e.wo, d, d, d, 0);
+    add_entry(ctx, p + ".cross.wq", MAT, {d, d}, e.cq, d, d, d, 0);
+    add_entry(ctx, p + ".cross.wk", MAT, {d, d}, e.ckv, d, d, 2 * d, 0);
+    add_entry(ctx, p + ".cross.wv", MAT, {d, d}, e.ckv, d, d, 2 * d, d);
+    add_entry(ctx, p + ".cross.wo", MAT, {d, d}, e.co, d, d, d, 0);
+    add_entry(ctx, p + ".ffn.w1", MAT, {d, F}, e.w1, d, F, F, 0);
+    add_entry(ctx, p + ".ffn.b1", VEC, {F}, e.b1);
+    add_entry(ctx, p + ".ffn.w2", MAT, {F, d}, e.w2, F, d, d, 0);
+    add_entry(ctx, p + ".ffn.b2", VEC, {d}, e.b2);
+  }
+  ln("dec.lnf", L.dec_lnf);
+  add_entry(ctx, "head.w1", MATK_CAT, {k, d, F}, L.hw1, d, F, k * F, 0);
+  add_entry(ctx, "head.b1", VEC, {k, F}, L.hb1);
+  add_entry(ctx, "head.w2", MATK_SEP, {k, F, d}, L.hw2, F, d, d, 0);
+  add_entry(ctx, "head.b2", VEC, {k, d}, L.hb2);
+}
+
+// ------------------------------------------------------------------------------- launches
+
+template <int MT, int NT, int KS>
+void launch_gemm_bf16(const GemmP& p, const Epi& e, int groups, hipStream_t s) {
+  const int ntiles = p.N / 16;
+  dim3 grid(KS == 4 ? (ntiles + NT - 1) / NT : (ntiles + 4 * NT - 1) / (4 * NT), (p.M + 16 * MT - 1) / (16 * MT), groups);
+  hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, KS>), grid, dim3(256), 0, s, p, e);
+}
+template <int MT, int NT, int KS>
+void launch_vocab_bf16(const GemmP& p, unsigned long long* keys, float* logits, hipStream_t s) {
+  const int ntiles = p.N / 16;
+  dim3 grid(KS == 4 ? (ntiles + NT - 1) / NT : (ntiles + 4 * NT - 1) / (4 * NT), (p.M + 16 * MT - 1) / (16 * MT), 1);
+  hipLaunchKernelGGL((vocab_argmax_bf16_kernel<MT, NT, KS>), grid, dim3(256), 0, s, p, keys, logits);
+}
+
+// Tile shape by problem shape: few rows -> one workgroup per 16 columns with the 4 waves
+// splitting K (many small workgroups keep every CU streaming weights); many columns -> each
+// wave its own column tile; many rows -> 64x256 output tiles per workgroup.
+#define DISPATCH_TILES(LAUNCH, ...)                                          \
+  do {                                                                       \
+    const bool wide = (p.N / 16) >= 1024;                                    \
+    if (p.M > 128) { LAUNCH<4, 4, 1>(__VA_ARGS__); }                         \
+    else if (p.M > 64) { if (wide) LAUNCH<8, 1, 1>(__VA_ARGS__); else LAUNCH<8, 1, 4>(__VA_ARGS__); } \
+    else if (p.M > 32) { if (wide) LAUNCH<4, 1, 1>(__VA_ARGS__); else LAUNCH<4, 1, 4>(__VA_ARGS__); } \
+    else if (p.M > 16) { if (wide) LAUNCH<2, 1, 1>(__VA_ARGS__); else LAUNCH<2, 1, 4>(__VA_ARGS__); } \
+    else { if (wide) LAUNCH<1, 1, 1>(__VA_ARGS__); else LAUNCH<1, 1, 4>(__VA_ARGS__); }               \
+  } while (0)
+
+void gemm(bpd_ctx* ctx, const GemmP& p, const Epi& e, int groups = 1) {
+  if (ctx->cfg.dtype == BPD_BF16) {
+    DISPATCH_TILES(launch_gemm_bf16, p, e, groups, ctx->stream);
+  } else {
+    dim3 grid((p.N + 127) / 128, p.M, groups);
+    hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(128), 0, ctx->stream, p, e);
+  }
+}
+
+GemmP gp(const void* X, int ldx, const void* W, int ldw, int M, int N, int K) {
+  GemmP p{};
+  p.X = X; p.ldx = ldx; p.W = W; p.ldw = ldw; p.M = M; p.N = N; p.K = K;
+  return p;
+}
+Epi plain(const float* bias, int relu, const float* R, int ldr, float* Yf, int ldyf, void* Ya, int ldya) {
+  Epi e{};
+  e.mode = 0; e.bias = bias; e.relu = relu; e.R = R; e.ldr = ldr; e.Yf = Yf; e.ldyf = ldyf; e.Ya = Ya; e.ldya = ldya;
+  return e;
+}
+Epi split(float* Qf, void* Ka, void* Va, int dsplit, int chunk0, int rows_per_seq, int cap, const int* base) {
+  Epi e{};
+  e.mode = 1; e.Qf = Qf; e.Ka = Ka; e.Va = Va; e.dsplit = dsplit; e.chunk0 = chunk0;
+  e.rows_per_seq = rows_per_seq; e.cap = cap; e.base = base;
+  return e;
+}
+
+void layernorm(bpd_ctx* ctx, const float* x, LnW w, int M, void* ya, float* yf) {
+  const int d = ctx->cfg.d_model;
+  dim3 grid((M + 3) / 4);
+  if (ctx->cfg.dtype == BPD_BF16)
+    hipLaunchKernelGGL(layernorm_kernel<bf16_t>, grid, dim3(256), 0, ctx->stream, x, w.g, w.b, M, d, ctx->cfg.ln_eps, (bf16_t*)ya, yf);
+  else
+    hipLaunchKernelGGL(layernorm_kernel<float>, grid, dim3(256), 0, ctx->stream, x, w.g, w.b, M, d, ctx->cfg.ln_eps, (float*)ya, yf);
+}
+
+void attention(bpd_ctx* ctx, const float* Q, const void* Kc, const void* Vc, void* out, long kv_seq_stride,
+               int B, int R, const int* limit, int causal) {
+  const bpd_config& c = ctx->cfg;
+  const int dh = c.d_model / c.n_heads;
+  AttnP p{};
+  p.Q = Q; p.Kc = Kc; p.Vc = Vc; p.out = out; p.kv_seq_stride = kv_seq_stride; p.d = c.d_model; p.R = R;
+  p.limit = limit; p.causal = causal; p.scale = 1.0f / sqrtf((float)dh);
+  dim3 grid(c.n_heads, B, (R + 15) / 16);
+  if (c.dtype == BPD_BF16) {
+    if (dh == 64) hipLaunchKernelGGL((attention_kernel<bf16_t, 64>), grid, dim3(256), 0, ctx->stream, p);
+    else hipLaunchKernelGGL((attention_kernel<bf16_t, 16>), grid, dim3(256), 0, ctx->stream, p);
+  } else {
+    if (dh == 64) hipLaunchKernelGGL((attention_kernel<float, 64>), grid, dim3(256), 0, ctx->stream, p);
+    else hipLaunchKernelGGL((attention_kernel<float, 16>), grid, dim3(256), 0, ctx->stream, p);
+  }
+}
+
+void embed(bpd_ctx* ctx, const int* tok, int tok_ld, const int* base, int rows_per_seq, int M, const float* pos,
+           float* x, int zero_input) {
+  const bpd_config& c = ctx->cfg;
+  const long n = (long)M * c.d_model;
+  dim3 grid((unsigned)((n + 255) / 256));
+  const float scale = sqrtf((float)c.d_model);
+  if (c.dtype == BPD_BF16)
+    hipLaunchKernelGGL(embed_kernel<true>, grid, dim3(256), 0, ctx->stream, tok, tok_ld, base, rows_per_seq, M, c.d_model,
+                       ctx->lay.emb, c.vocab, pos, scale, x, zero_input);
+  else
+    hipLaunchKernelGGL(embed_kernel<false>, grid, dim3(256), 0, ctx->stream, tok, tok_ld, base, rows_per_seq, M, c.d_model,
+                       ctx->lay.emb, c.vocab, pos, scale, x, zero_input);
+}
+
+void fill_i32(bpd_ctx* ctx, int* p, long n, int v) {
+  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, p, n, v);
+}
+
+// ------------------------------------------------------------------------------- profiling
+
+hipEvent_t prof_event(bpd_ctx* ctx) {
+  if (ctx->prof_used == ctx->prof_ev.size()) {
+    hipEvent_t e;
+    (void)hipEventCreate(&e);
+    ctx->prof_ev.push_back(e);
+  }
+  return ctx->prof_ev[ctx->prof_used++];
+}
+struct PhaseTimer {
+  bpd_ctx* ctx; bool on;
+  PhaseTimer(bpd_ctx* c, int phase) : ctx(c), on(c->prof_phase == phase) {
+    if (on) (void)hipEventRecord(prof_event(ctx), ctx->stream);
+  }
+  ~PhaseTimer() {
+    if (on) { (void)hipEventRecord(prof_event(ctx), ctx->stream); ctx->prof_launches++; }
+  }
+};
+
+// ------------------------------------------------------------------------------- the model invocation
+
+// One invocation of the combined model on R new rows per sequence (R = 1 for the first call
+// on the empty prefix, R = k afterwards) with the first k heads; fills keys[B*R*k].
+int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
+  const bpd_config& c = ctx->cfg;
+  Layout& L = ctx->lay;
+  const int B = ctx->B, d = c.d_model, F = c.d_ff, M = B * R;
+  const int slots = c.max_out_len + c.k_max + 1;
+  const size_t as = act_size(c);
+  {
+    PhaseTimer t(ctx, BPD_PHASE_LAYERS);
+    embed(ctx, L.P, c.k_max, L.L, R, M, L.pos_tgt, L.x, zero_input);
+    for (int l = 0; l < c.n_dec_layers; ++l) {
+      DecL& w = L.dec[l];
+      char* Kl = (char*)L.selfK + (size_t)l * c.max_batch * slots * d * as;
+      char* Vl = (char*)L.selfV + (size_t)l * c.max_batch * slots * d * as;
+      char* cK = (char*)L.crossK + (size_t)l * c.max_batch * c.max_src_len * d * as;
+      char* cV = (char*)L.crossV + (size_t)l * c.max_batch * c.max_src_len * d * as;
+      // self-attention sublayer: K/V of the block rows go straight into the cache at L_b + i'
+      layernorm(ctx, L.x, w.ln1, M, L.xn, nullptr);
+      gemm(ctx, gp(L.xn, d, w.wqkv, 3 * d, M, 3 * d, d), split(L.q, Kl, Vl, d, 0, R, slots, L.L));
+      attention(ctx, L.q, Kl, Vl, L.attn, (long)slots * d, B, R, L.L, 1);
+      gemm(ctx, gp(L.attn, d, w.wo, d, M, d, d), plain(nullptr, 0, L.x, d, L.x, d, nullptr, 0));
+      // cross-attention sublayer over the encoder memory
+      layernorm(ctx, L.x, w.ln2, M, L.xn, nullptr);
+      gemm(ctx, gp(L.xn, d, w.cq, d, M, d, d), plain(nullptr, 0, nullptr, 0, L.q, d, nullptr, 0));
+      attention(ctx, L.q, cK, cV, L.attn, (long)c.max_src_len * d, B, R, L.src_len, 0);
+      gemm(ctx, gp(L.attn, d, w.co, d, M, d, d), plain(nullptr, 0, L.x, d, L.x, d, nullptr, 0));
+      // feed-forward sublayer
+      layernorm(ctx, L.x, w.ln3, M, L.xn, nullptr);
+      gemm(ctx, gp(L.xn, d, w.w1, F, M, F, d), plain(w.b1, 1, nullptr, 0, nullptr, 0, L.ffh, F));
+      gemm(ctx, gp(L.ffh, F, w.w2, d, M, d, F), plain(w.b2, 0, L.x, d, L.x, d, nullptr, 0));
+    }
+    layernorm(ctx, L.x, L.dec_lnf, M, L.hn, L.h);
+  }
+  // the k residual FFN heads: hidden layers side by side, then one output layer per head
+  {
+    PhaseTimer t(ctx, BPD_PHASE_HEAD_HIDDEN);
+    gemm(ctx, gp(L.hn, d, L.hw1, c.k_max * F, M, k * F, d), plain(L.hb1, 1, nullptr, 0, nullptr, 0, L.H, k * F));
+  }
+  {
+    PhaseTimer t(ctx, BPD_PHASE_HEAD_OUT);
+    GemmP p = gp(L.H, k * F, L.hw2, d, M, d, F);
+    p.x_g = F; p.w_g = (long)F * d;
+    Epi e = plain(L.hb2, 0, L.h, d, nullptr, 0, L.O, k * d);
+    e.bias_g = d; e.r_g = 0; e.ya_g = d;
+    gemm(ctx, p, e, k);
+  }
+  const long nk = (long)M * k;
+  hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, ctx->stream, L.keys, nk, 0ull);
+  {
+    PhaseTimer t(ctx, BPD_PHASE_VOCAB);
+    if (c.dtype == BPD_BF16) {
+      GemmP p = gp(L.O, d, L.emb, c.vocab, (int)nk, c.vocab, d);
+      DISPATCH_TILES(launch_vocab_bf16, p, L.keys, logits, ctx->stream);
+    } else {
+      hipLaunchKernelGGL(vocab_argmax_f32_kernel, dim3((unsigned)nk), dim3(256), 0, ctx->stream, (const float*)L.O,
+                         (const float*)L.emb, (int)nk, c.vocab, d, L.keys, logits);
+    }
+  }
+  LAUNCHCHK();
+  return BPD_OK;
+}
+
+StateP state_params(bpd_ctx* ctx) {
+  Layout& L = ctx->lay;
+  StateP s{};
+  s.L = L.L; s.j = L.j; s.finished = L.finished; s.max_len = L.max_len; s.P = L.P; s.A = L.A;
+  s.accepted = L.accepted; s.out_ids = L.out_ids; s.stats = L.stats; s.imposed = nullptr; s.imposed_stride = 0;
+  s.step_counter = L.step_counter; s.kmax = ctx->cfg.k_max; s.max_out = ctx->cfg.max_out_len;
+  s.eos_id = ctx->cfg.eos_id; s.distance_eps = ctx->distance_eps; s.min_block = ctx->min_block;
+  return s;
+}
+
+int encoder(bpd_ctx* ctx) {
+  const bpd_config& c = ctx->cfg;
+  Layout& L = ctx->lay;
+  const int B = ctx->B, S = ctx->S, d = c.d_model, F = c.d_ff, M = B * S;
+  const size_t as = act_size(c);
+  embed(ctx, L.src_ids, S, nullptr, S, M, L.pos_src, L.xe, 0);
+  for (int l = 0; l < c.n_enc_layers; ++l) {
+    EncL& w = L.enc[l];
+    layernorm(ctx, L.xe, w.ln1, M, L.xen, nullptr);
+    gemm(ctx, gp(L.xen, d, w.wqkv, 3 * d, M, 3 * d, d), split(L.qe, L.ke, L.ve, d, 0, S, S, nullptr));
+    attention(ctx, L.qe, L.ke, L.ve, L.attne, (long)S * d, B, S, L.src_len, 0);
+    gemm(ctx, gp(L.attne, d, w.wo, d, M, d, d), plain(nullptr, 0, L.xe, d, L.xe, d, nullptr, 0));
+    layernorm(ctx, L.xe, w.ln2, M, L.xen, nullptr);
+    gemm(ctx, gp(L.xen, d, w.w1, F, M, F, d), plain(w.b1, 1, nullptr, 0, nullptr, 0, L.ffhe, F));
+    gemm(ctx, gp(L.ffhe, F, w.w2, d, M, d, F), plain(w.b2, 0, L.xe, d, L.xe, d, nullptr, 0));
+  }
+  layernorm(ctx, L.xe, L.enc_lnf, M, L.mem, nullptr);
+  for (int l = 0; l < c.n_dec_layers; ++l) {
+    char* cK = (char*)L.crossK + (size_t)l * c.max_batch * c.max_src_len * d * as;
+    char* cV = (char*)L.crossV + (size_t)l * c.max_batch * c.max_src_len * d * as;
+    gemm(ctx, gp(L.mem, d, L.dec[l].ckv, 2 * d, M, 2 * d, d), split(nullptr, cK, cV, d, 1, S, c.max_src_len, nullptr));
+  }
+  LAUNCHCHK();
+  return BPD_OK;
+}
+
+__global__ void sanitize_kernel(int* src_len, int* max_len, int* src_ids, int B, int S, int max_out, int V) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < B) {
+    int s = src_len[i]; src_len[i] = s < 1 ? 1 : (s > S ? S : s);
+    int m = max_len[i]; max_len[i] = m < 1 ? 1 : (m > max_out ? max_out : m);
+  }
+  if (i < B * S) { int t = src_ids[i]; src_ids[i] = t < 0 ? 0 : (t >= V ? V - 1 : t); }
+}
+
+bool is_host_ptr(const void* p) {
+  hipPointerAttribute_t a;
+  if (hipPointerGetAttributes(&a, p) != hipSuccess) { (void)hipGetLastError(); return true; }
+  return a.type != hipMemoryTypeDevice && a.type != hipMemoryTypeManaged;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------- C ABI
+
+extern "C" {
+
+size_t bpd_workspace_bytes(const bpd_config* cfg) {
+  if (!cfg || !config_ok(*cfg)) return 0;
+  Layout L;
+  return build_layout(*cfg, nullptr, L);
+}
+
+int bpd_create(const bpd_config* cfg, void* workspace, size_t workspace_bytes, void* hip_stream, bpd_ctx** out) {
+  if (!cfg || !workspace || !out) return BPD_E_ARG;
+  if (!config_ok(*cfg)) return BPD_E_ARG;
+  if (((uintptr_t)workspace) % ALIGN) return BPD_E_ARG;
+  Layout probe;
+  if (workspace_bytes < build_layout(*cfg, nullptr, probe)) return BPD_E_CAPACITY;
+  bpd_ctx* ctx = new bpd_ctx();
+  ctx->cfg = *cfg;
+  ctx->stream = (hipStream_t)hip_stream;
+  build_layout(*cfg, (char*)workspace, ctx->lay);
+  build_table(ctx);
+  if (hipHostMalloc((void**)&ctx->pinned, 64 * sizeof(int), hipHostMallocDefault) != hipSuccess) {
+    delete ctx;
+    return BPD_E_HIP;
+  }
+  *out = ctx;
+  return BPD_OK;
+}
+
+int bpd_destroy(bpd_ctx* ctx) {
+  if (!ctx) return BPD_E_ARG;
+  (void)hipStreamSynchronize(ctx->stream);
+  for (auto e : ctx->prof_ev) (void)hipEventDestroy(e);
+  if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+  delete ctx;
+  return BPD_OK;
+}
+
+const char* bpd_last_error(const bpd_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int bpd_load_weights(bpd_ctx* ctx, const bpd_tensor* tensors, int n) {
+  if (!ctx || !tensors || n < 0) return fail(ctx, BPD_E_ARG, "bpd_load_weights: null argument");
+  const bool bf = ctx->cfg.dtype == BPD_BF16;
+  // validate everything first so that a bad tensor leaves the loaded set unchanged
+  for (int t = 0; t < n; ++t) {
+    const bpd_tensor& T = tensors[t];
+    if (!T.name || !T.data) return fail(ctx, BPD_E_ARG, "bpd_load_weights: tensor without name or data");
+    auto it = ctx->table.find(T.name);
+    if (it == ctx->table.end()) return fail(ctx, BPD_E_WEIGHTS, std::string("unknown tensor ") + T.name);
+    const WEntry& e = it->second;
+    if (T.dtype != BPD_F32 && T.dtype != BPD_BF16) return fail(ctx, BPD_E_WEIGHTS, std::string("bad dtype for ") + T.name);
+    bool ok = T.ndim == e.nd;
+    for (int i = 0; ok && i < e.nd; ++i) ok = T.shape[i] == e.shape[i];
+    if (!ok) return fail(ctx, BPD_E_WEIGHTS, std::string("wrong shape for ") + T.name);
+  }
+  for (int t = 0; t < n; ++t) {
+    const bpd_tensor& T = tensors[t];
+    WEntry& e = ctx->table[T.name];
+    size_t count = 1;
+    for (int i = 0; i < e.nd; ++i) count *= (size_t)e.shape[i];
+    const size_t esz = T.dtype == BPD_F32 ? 4 : 2;
+    const void* src = T.data;
+    if (!T.on_device) {
+      if (count * esz > ctx->lay.staging_bytes) return fail(ctx, BPD_E_CAPACITY, "staging area too small");
+      HIPCHK(hipMemcpyAsync(ctx->lay.staging, T.data, count * esz, hipMemcpyHostToDevice, ctx->stream));
+      src = ctx->lay.staging;
+    }
+    const dim3 blk(256);
+    auto conv_mat = [&](const void* s, void* dst, int K, int N, int transposed, int ldw, int n_off) {
+      const long tot = (long)K * N;
+      dim3 grid((unsigned)((tot + 255) / 256));
+      if (T.dtype == BPD_F32) {
+        if (bf) hipLaunchKernelGGL((convert_matrix_kernel<float, true>), grid, blk, 0, ctx->stream, (const float*)s, dst, K, N, transposed, ldw, n_off);
+        else hipLaunchKernelGGL((convert_matrix_kernel<float, false>), grid, blk, 0, ctx->stream, (const float*)s, dst, K, N, transposed, ldw, n_off);
+      } else {
+        if (bf) hipLaunchKernelGGL((convert_matrix_kernel<bf16_t, true>), grid, blk, 0, ctx->stream, (const bf16_t*)s, dst, K, N, transposed, ldw, n_off);
+        else hipLaunchKernelGGL((convert_matrix_kernel<bf16_t, false>), grid, blk, 0, ctx->stream, (const bf16_t*)s, dst, K, N, transposed, ldw, n_off);
+      }
+    };
+    auto conv_vec = [&](const void* s, float* dst, size_t cnt) {
+      dim3 grid((unsigned)((cnt + 255) / 256));
+      if (T.dtype == BPD_F32) hipLaunchKernelGGL(convert_vector_kernel<float>, grid, blk, 0, ctx->stream, (const float*)s, dst, (long)cnt);
+      else hipLaunchKernelGGL(convert_vector_kernel<bf16_t>, grid, blk, 0, ctx->stream, (const bf16_t*)s, dst, (long)cnt);
+    };
+    const size_t wsz = bf ? 2 : 4;
+    switch (e.kind) {
+      case VEC: conv_vec(src, (float*)e.dst, count); break;
+      case MAT: conv_mat(src, e.dst, e.K, e.N, 0, e.ldw, e.n_off); break;
+      case EMB:
+        if (bf) conv_mat(src, e.dst, e.K, e.N, 1, e.ldw, 0);      // as the projection matrix W[d][V] = E^T
+        else conv_vec(src, (float*)e.dst, count);                  // fp32 kernels read E[V][d] directly
+        break;
+      case MATK_CAT:
+        for (int i = 0; i < (int)e.shape[0]; ++i)
+          conv_mat((const char*)src + (size_t)i * e.K * e.N * esz, e.dst, e.K, e.N, 0, e.ldw, i * e.N);
+        break;
+      case MATK_SEP:
+        for (int i = 0; i < (int)e.shape[0]; ++i)
+          conv_mat((const char*)src + (size_t)i * e.K * e.N * esz, (char*)e.dst + (size_t)i * e.K * e.N * wsz, e.K, e.N, 0, e.ldw, 0);
+        break;
+    }
+    LAUNCHCHK();
+    HIPCHK(hipStreamSynchronize(ctx->stream));   // the staging area and the caller's buffer are free again
+    e.loaded = true;
+  }
+  ctx->encoded = false;
+  return BPD_OK;
+}
+
+int bpd_encode(bpd_ctx* ctx, const int32_t* src_ids, const int32_t* src_len, const int32_t* max_len, int B, int S) {
+  if (!ctx || !src_ids || !src_len) return fail(ctx, BPD_E_ARG, "bpd_encode: null argument");
+  const bpd_config& c = ctx->cfg;
+  if (B < 1 || S < 1) return fail(ctx, BPD_E_ARG, "bpd_encode: B and S must be positive");
+  if (B > c.max_batch || S > c.max_src_len) return fail(ctx, BPD_E_CAPACITY, "bpd_encode: batch or source length over the configured maximum");
+  for (auto& kv : ctx->table)
+    if (!kv.second.loaded) return fail(ctx, BPD_E_STATE, "bpd_encode: tensor not loaded: " + kv.first);
+  // host-side validation when the caller's arrays are host memory
+  if (is_host_ptr(src_len)) {
+    for (int b = 0; b < B; ++b)
+      if (src_len[b] < 1 || src_len[b] > S) return fail(ctx, BPD_E_ARG, "bpd_encode: src_len out of range");
+  }
+  if (is_host_ptr(src_ids)) {
+    for (long i = 0; i < (long)B * S; ++i)
+      if (src_ids[i] < 0 || src_ids[i] >= c.vocab) return fail(ctx, BPD_E_ARG, "bpd_encode: source id out of range");
+  }
+  if (max_len && is_host_ptr(max_len)) {
+    for (int b = 0; b < B; ++b)
+      if (max_len[b] < 1 || max_len[b] > c.max_out_len) return fail(ctx, BPD_E_ARG, "bpd_encode: max_len out of range");
+  }
+  Layout& L = ctx->lay;
+  ctx->B = B; ctx->S = S; ctx->encoded = false;
+  HIPCHK(hipMemcpyAsync(L.src_ids, src_ids, (size_t)B * S * 4, hipMemcpyDefault, ctx->stream));
+  HIPCHK(hipMemcpyAsync(L.src_len, src_len, (size_t)B * 4, hipMemcpyDefault, ctx->stream));
+  if (max_len) HIPCHK(hipMemcpyAsync(L.max_len, max_len, (size_t)B * 4, hipMemcpyDefault, ctx->stream));
+  else fill_i32(ctx, L.max_len, B, c.max_out_len);
+  hipLaunchKernelGGL(sanitize_kernel, dim3((B * S + 255) / 256), dim3(256), 0, ctx->stream, L.src_len, L.max_len, L.src_ids, B, S,
+                     c.max_out_len, c.vocab);
+  int rc = encoder(ctx);
+  if (rc) return rc;
+  // empty hypotheses
+  fill_i32(ctx, L.L, B, 0);
+  fill_i32(ctx, L.j, B, 0);
+  fill_i32(ctx, L.finished, B, 0);
+  fill_i32(ctx, L.accepted, B, 0);
+  fill_i32(ctx, L.out_ids, (long)B * c.max_out_len, c.pad_id);
+  fill_i32(ctx, L.step_counter, 1, 0);
+  fill_i32(ctx, (int*)L.stats, 64, 0);
+  fill_i32(ctx, L.P, (long)B * c.k_max, 0);
+  fill_i32(ctx, L.A, (long)B * c.k_max * c.k_max, 0);
+  // first invocation: position 0 only, all heads -> first proposals
+  rc = forward(ctx, 1, c.k_max, 1, nullptr);
+  if (rc) return rc;
+  hipLaunchKernelGGL(prime_kernel, dim3(B), dim3(64), 0, ctx->stream, state_params(ctx), L.keys, B);
+  LAUNCHCHK();
+  ctx->steps = 0;
+  ctx->encoded = true;
+  return BPD_OK;
+}
+
+static int step_impl(bpd_ctx* ctx, int k, const int* imposed_dev, int imposed_stride) {
+  Layout& L = ctx->lay;
+  PhaseTimer whole(ctx, BPD_PHASE_STEP);
+  int rc = forward(ctx, k, k, 0, nullptr);
+  if (rc) return rc;
+  {
+    PhaseTimer t(ctx, BPD_PHASE_ACCEPT);
+    StateP s = state_params(ctx);
+    s.imposed = imposed_dev; s.imposed_stride = imposed_stride;
+    hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(64), 0, ctx->stream, s, L.keys, k, ctx->B, 1);
+    hipLaunchKernelGGL(bump_step_kernel, dim3(1), dim3(1), 0, ctx->stream, L.step_counter);
+  }
+  LAUNCHCHK();
+  ctx->steps++;
+  return BPD_OK;
+}
+
+int bpd_step(bpd_ctx* ctx, int k, const int32_t* imposed_accept, int32_t* accepted_len) {
+  if (!ctx) return BPD_E_ARG;
+  if (!ctx->encoded) return fail(ctx, BPD_E_STATE, "bpd_step: call bpd_encode first");
+  if (k < 1 || k > ctx->cfg.k_max) return fail(ctx, BPD_E_ARG, "bpd_step: k outside 1..k_max");
+  Layout& L = ctx->lay;
+  const int* imp = nullptr;
+  if (imposed_accept) {
+    HIPCHK(hipMemcpyAsync(L.imposed1, imposed_accept, (size_t)ctx->B * 4, hipMemcpyDefault, ctx->stream));
+    imp = L.imposed1;
+  }
+  int rc = step_impl(ctx, k, imp, 0);
+  if (rc) return rc;
+  if (accepted_len) HIPCHK(hipMemcpyAsync(accepted_len, L.accepted, (size_t)ctx->B * 4, hipMemcpyDefault, ctx->stream));
+  return BPD_OK;
+}
+
+int bpd_set_acceptance(bpd_ctx* ctx, int distance_eps, int min_block) {
+  if (!ctx) return BPD_E_ARG;
+  if (distance_eps < 0 || min_block < 1 || min_block > ctx->cfg.k_max) return fail(ctx, BPD_E_ARG, "bpd_set_acceptance: out of range");
+  ctx->distance_eps = distance_eps; ctx->min_block = min_block;
+  return BPD_OK;
+}
+
+int bpd_get_stats(bpd_ctx* ctx, bpd_stats* st) {
+  if (!ctx || !st) return BPD_E_ARG;
+  long long raw[32];
+  HIPCHK(hipMemcpyAsync(raw, ctx->lay.stats, sizeof(raw), hipMemcpyDeviceToHost, ctx->stream));
+  HIPCHK(hipStreamSynchronize(ctx->stream));
+  st->steps = raw[20]; st->invocations = ctx->encoded ? raw[20] + 1 : 0;
+  st->seq_steps = raw[0]; st->accepted_total = raw[1]; st->finished = (int32_t)raw[2];
+  for (int i = 0; i < 17; ++i) st->hist[i] = raw[3 + i];
+  return BPD_OK;
+}
+
+int bpd_get_output(bpd_ctx* ctx, int32_t* out_ids, int32_t* out_len) {
+  if (!ctx) return BPD_E_ARG;
+  if (!ctx->encoded) return fail(ctx, BPD_E_STATE, "bpd_get_output: nothing decoded");
+  Layout& L = ctx->lay;
+  if (out_ids) HIPCHK(hipMemcpyAsync(out_ids, L.out_ids, (size_t)ctx->B * ctx->cfg.max_out_len * 4, hipMemcpyDefault, ctx->stream));
+  if (out_len) HIPCHK(hipMemcpyAsync(out_len, L.j, (size_t)ctx->B * 4, hipMemcpyDefault, ctx->stream));
+  HIPCHK(hipStreamSynchronize(ctx->stream));
+  return BPD_OK;
+}
+
+int bpd_decode(bpd_ctx* ctx, int k, const int32_t* schedule, int max_steps, int32_t* out_ids, int32_t* out_len, bpd_stats* stats) {
+  if (!ctx) return BPD_E_ARG;
+  if (!ctx->encoded) return fail(ctx, BPD_E_STATE, "bpd_decode: call bpd_encode first");
+  if (k < 1 || k > ctx->cfg.k_max || max_steps < 0) return fail(ctx, BPD_E_ARG, "bpd_decode: bad k or max_steps");
+  Layout& L = ctx->lay;
+  const int B = ctx->B;
+  const int* imp = nullptr;
+  if (schedule) {
+    // a live sequence takes at least one token per step, so max_out_len rows always suffice
+    const int rows = max_steps < ctx->cfg.max_out_len ? max_steps : ctx->cfg.max_out_len;
+    if (rows > 0) HIPCHK(hipMemcpyAsync(L.sched, schedule, (size_t)rows * B * 4, hipMemcpyDefault, ctx->stream));
+    if (max_steps > rows) max_steps = rows;
+    imp = L.sched - (long)ctx->steps * B;     // the kernel indexes by the global step counter
+  }
+  for (int s = 0; s < max_steps; ++s) {
+    int rc = step_impl(ctx, k, imp, B);
+    if (rc) return rc;
+    if ((s & 3) == 3 || s + 1 == max_steps) {
+      HIPCHK(hipMemcpyAsync(ctx->pinned, (int*)(L.stats + 2), 4, hipMemcpyDeviceToHost, ctx->stream));
+      HIPCHK(hipStreamSynchronize(ctx->stream));
+      if (ctx->pinned[0] >= B) break;
+    }
+  }
+  int rc = bpd_get_output(ctx, out_ids, out_len);
+  if (rc) return rc;
+  if (stats) return bpd_get_stats(ctx, stats);
+  return BPD_OK;
+}
+
+int bpd_get_state(bpd_ctx* ctx, int32_t* P, int32_t* A, int32_t* j, int32_t* finished) {
+  if (!ctx) return BPD_E_ARG;
+  if (!ctx->encoded) return fail(ctx, BPD_E_STATE, "bpd_get_state: call bpd_encode first");
+  Layout& L = ctx->lay;
+  const size_t B = ctx->B, k = ctx->cfg.k_max;
+  if (P) HIPCHK(hipMemcpyAsync(P, L.P, B * k * 4, hipMemcpyDefault, ctx->stream));
+  if (A) HIPCHK(hipMemcpyAsync(A, L.A, B * k * k * 4, hipMemcpyDefault, ctx->stream));
+  if (j) HIPCHK(hipMemcpyAsync(j, L.j, B * 4, hipMemcpyDefault, ctx->stream));
+  if (finished) HIPCHK(hipMemcpyAsync(finished, L.finished, B * 4, hipMemcpyDefault, ctx->stream));
+  HIPCHK(hipStreamSynchronize(ctx->stream));
+  return BPD_OK;
+}
+
+int bpd_set_proposals(bpd_ctx* ctx, const int32_t* P) {
+  if (!ctx || !P) return fail(ctx, BPD_E_ARG, "bpd_set_proposals: null argument");
+  if (!ctx->encoded) return fail(ctx, BPD_E_STATE, "bpd_set_proposals: call bpd_encode first");
+  const size_t n = (size_t)ctx->B * ctx->cfg.k_max;
+  if (is_host_ptr(P)) {
+    for (size_t i = 0; i < n; ++i)
+      if (P[i] < 0 || P[i] >= ctx->cfg.vocab) return fail(ctx, BPD_E_ARG, "bpd_set_proposals: token id out of range");
+  }
+  HIPCHK(hipMemcpyAsync(ctx->lay.P, P, n * 4, hipMemcpyDefault, ctx->stream));
+  return BPD_OK;
+}
+
+int bpd_debug_step_logits(bpd_ctx* ctx, int k, float* logits) {
+  if (!ctx || !logits) return fail(ctx, BPD_E_ARG, "bpd_debug_step_logits: null argument");
+  if (!ctx->encoded) return fail(ctx, BPD_E_STATE, "bpd_debug_step_logits: call bpd_encode first");
+  if (k < 1 || k > ctx->cfg.k_max) return fail(ctx, BPD_E_ARG, "bpd_debug_step_logits: k outside 1..k_max");
+  int rc = forward(ctx, k, k, 0, logits);
+  if (rc) return rc;
+  hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(64), 0, ctx->stream, state_params(ctx), ctx->lay.keys, k, ctx->B, 0);
+  LAUNCHCHK();
+  return BPD_OK;
+}
+
+int bpd_profile_enable(bpd_ctx* ctx, int phase) {
+  if (!ctx || phase < 0 || phase > BPD_PHASE_STEP) return BPD_E_ARG;
+  (void)hipStreamSynchronize(ctx->stream);
+  ctx->prof_phase = phase; ctx->prof_used = 0; ctx->prof_launches = 0;
+  return BPD_OK;
+}
+
+int bpd_profile_read(bpd_ctx* ctx, double* total_ms, int64_t* launches) {
+  if (!ctx || !total_ms || !launches) return BPD_E_ARG;
+  HIPCHK(hipStreamSynchronize(ctx->stream));
+  double tot = 0;
+  for (size_t i = 0; i + 1 < ctx->prof_used; i += 2) {
+    float ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&ms, ctx->prof_ev[i], ctx->prof_ev[i + 1]));
+    tot += ms;
+  }
+  *total_ms = tot; *launches = ctx->prof_launches;
+  ctx->prof_used = 0; ctx->prof_launches = 0;
+  return BPD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,593 @@
+// Device code of libbpd: hand-written HIP kernels for gfx950 (CDNA4, 64-wide wavefronts).
+//
+// Number formats.  "act" tensors (GEMM inputs, K/V caches) are bf16 in BPD_BF16 mode and
+// fp32 in BPD_F32 mode; the residual stream, LayerNorm statistics, softmax and all GEMM
+// accumulators are fp32.  bf16 values are carried as uint16 bit patterns.
+//
+// Weight layout in bf16 mode.  A matrix W[K][N] (y = x W) is stored as MFMA operand tiles:
+//     Wp[n/16][k/32][lane][e],  lane = 16*((k%32)/8) + n%16,  e = k%8
+// so that the 64 lanes of a wavefront fetch one 16x32 tile (1 KiB) with a single fully
+// coalesced 16-byte load per lane, directly in the register layout that
+// v_mfma_f32_16x16x32_bf16 expects for its first operand.  The weights play the role of the
+// MFMA "A" operand (16 output features x 32 k) and the activations are the "B" operand
+// (32 k x 16 rows): a block of k <= 16 decoder rows then fills one MFMA tile exactly.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef unsigned short bf16_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+__device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((unsigned)v) << 16); }
+__device__ __forceinline__ bf16_t f2bf(float f) {          // round to nearest even
+  unsigned u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+template <typename T> __device__ __forceinline__ float to_f(T v);
+template <> __device__ __forceinline__ float to_f<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f<bf16_t>(bf16_t v) { return bf2f(v); }
+template <typename T> __device__ __forceinline__ T from_f(float v);
+template <> __device__ __forceinline__ float from_f<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f<bf16_t>(float v) { return f2bf(v); }
+
+__device__ __forceinline__ float wave_max(float v) {
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// ---------------------------------------------------------------------------------------
+// GEMM epilogue shared by the MFMA and the fp32 kernels.
+// mode 0:  v = acc (+bias[n]) (ReLU) (+R[m][n]);  Yf[m][n] = v (fp32)  and/or  Ya[m][n] = act(v)
+// mode 1:  the N axis is cut into chunks of `dsplit` columns; chunk c = n/dsplit + chunk0
+//          c == 0 -> Qf[m][n%dsplit] (fp32),  c == 1 -> Ka,  c == 2 -> Va  (act type) at row
+//          (m / rows_per_seq) * cap + (base ? base[m / rows_per_seq] : 0) + m % rows_per_seq
+//          (a K/V cache write at the sequence's current length).
+struct Epi {
+  int mode;
+  int relu;
+  const float* bias;
+  const float* R;  int ldr;
+  float* Yf;       int ldyf;
+  void* Ya;        int ldya;
+  long bias_g, r_g, yf_g, ya_g;      // per-group (blockIdx.z) element offsets
+  // mode 1
+  float* Qf; void* Ka; void* Va;
+  int dsplit, chunk0, rows_per_seq, cap;
+  const int* base;
+};
+
+template <typename ACT>
+__device__ __forceinline__ void epi_store(const Epi& e, int g, int m, int n, float v) {
+  if (e.mode == 0) {
+    if (e.bias) v += e.bias[g * e.bias_g + n];
+    if (e.relu) v = fmaxf(v, 0.f);
+    if (e.R) v += e.R[g * e.r_g + (long)m * e.ldr + n];
+    if (e.Yf) e.Yf[g * e.yf_g + (long)m * e.ldyf + n] = v;
+    if (e.Ya) ((ACT*)e.Ya)[g * e.ya_g + (long)m * e.ldya + n] = from_f<ACT>(v);
+  } else {
+    const int c = n / e.dsplit + e.chunk0;
+    const int col = n % e.dsplit;
+    if (c == 0) {
+      e.Qf[(long)m * e.dsplit + col] = v;
+    } else {
+      const int b = m / e.rows_per_seq, i = m % e.rows_per_seq;
+      const long row = (long)b * e.cap + (e.base ? e.base[b] : 0) + i;
+      ACT* dst = (ACT*)(c == 1 ? e.Ka : e.Va);
+      dst[row * e.dsplit + col] = from_f<ACT>(v);
+    }
+  }
+}
+
+struct GemmP {
+  const void* X; int ldx; long x_g;    // activations [M][K] (act type), per-group offset
+  const void* W; long w_g;             // bf16: packed tiles;  fp32: row-major [K][ldw]
+  int ldw;
+  int M, N, K;
+};
+
+// ---------------------------------------------------------------------------------------
+// bf16 MFMA GEMM.  One workgroup = 4 wavefronts.
+//   KS == 4: the 4 waves share NT feature tiles (16 columns each) and split K 4 ways
+//            (interleaved 32-wide steps, so neighbouring waves read neighbouring 1 KiB weight
+//            tiles); partial sums meet in LDS.  Used when N is small so that N/16 workgroups
+//            still spread the weight stream over many CUs.
+//   KS == 1: each wave owns NT feature tiles of its own; the workgroup covers 4*NT tiles.
+// MT = number of 16-row tiles of X handled by the workgroup (rows m0 .. m0+16*MT).
+template <int MT, int NT, int KS>
+struct GemmMain {
+  f32x4 acc[MT][NT];
+  int m0, nt0, lane, wave;
+  bool active;
+
+  __device__ __forceinline__ void run(const GemmP& p, f32x4* red /* LDS, KS==4 only */) {
+    lane = threadIdx.x & 63;
+    wave = threadIdx.x >> 6;
+    const int g = blockIdx.z;
+    const bf16_t* X = (const bf16_t*)p.X + g * p.x_g;
+    const bf16_t* W = (const bf16_t*)p.W + g * p.w_g;
+    m0 = blockIdx.y * (16 * MT);
+    nt0 = (KS == 4) ? blockIdx.x * NT : (blockIdx.x * 4 + wave) * NT;
+    const int ntiles = p.N >> 4, ksteps = p.K >> 5;
+    active = nt0 < ntiles;
+    const int lr = lane & 15, lk = (lane >> 4) * 8;
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+      for (int u = 0; u < NT; ++u) acc[t][u] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const bf16_t* xrow[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+      int r = m0 + t * 16 + lr;
+      r = r < p.M ? r : p.M - 1;
+      xrow[t] = X + (long)r * p.ldx + lk;
+    }
+    const uint4* wt[NT];
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+      int tile = nt0 + u;
+      tile = tile < ntiles ? tile : ntiles - 1;
+      wt[u] = (const uint4*)W + (long)tile * ksteps * 64 + lane;
+    }
+    if (active) {
+#pragma unroll 4
+      for (int ks = (KS == 4 ? wave : 0); ks < ksteps; ks += KS) {
+        uint4 a[NT], b[MT];
+#pragma unroll
+        for (int u = 0; u < NT; ++u) a[u] = wt[u][(long)ks * 64];
+#pragma unroll
+        for (int t = 0; t < MT; ++t) b[t] = *(const uint4*)(xrow[t] + ks * 32);
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+          for (int u = 0; u < NT; ++u)
+            acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                __builtin_bit_cast(bf16x8, a[u]), __builtin_bit_cast(bf16x8, b[t]), acc[t][u], 0, 0, 0);
+      }
+    }
+    if (KS == 4) {
+      if (wave > 0) {
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+          for (int u = 0; u < NT; ++u) red[((wave - 1) * MT * NT + t * NT + u) * 64 + lane] = acc[t][u];
+      }
+      __syncthreads();
+      if (wave == 0) {
+#pragma unroll
+        for (int w = 0; w < 3; ++w)
+#pragma unroll
+          for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int u = 0; u < NT; ++u) {
+              f32x4 v = red[(w * MT * NT + t * NT + u) * 64 + lane];
+              acc[t][u] += v;
+            }
+      }
+      active = active && wave == 0;
+    }
+  }
+  // after run(): for the owning wave, acc[t][u][r] is the value for
+  //   row  m = m0 + 16 t + lane%16,  column n = 16 (nt0+u) + 4 (lane/16) + r.
+};
+
+template <int MT, int NT, int KS>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmP p, Epi e) {
+  __shared__ f32x4 red[KS == 4 ? 3 * MT * NT * 64 : 1];
+  GemmMain<MT, NT, KS> g;
+  g.run(p, red);
+  if (!g.active) return;
+  const int ntiles = p.N >> 4;
+#pragma unroll
+  for (int t = 0; t < MT; ++t) {
+    const int m = g.m0 + t * 16 + (g.lane & 15);
+    if (m >= p.M) continue;
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+      if (g.nt0 + u >= ntiles) continue;
+      const int n = (g.nt0 + u) * 16 + (g.lane >> 4) * 4;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) epi_store<bf16_t>(e, blockIdx.z, m, n + r, g.acc[t][u][r]);
+    }
+  }
+}
+
+// Order-preserving map float -> uint32, then (value, lowest index wins) packed in 64 bits so
+// that an unsigned max over keys is the argmax regardless of the order of the updates.
+__device__ __forceinline__ unsigned long long argmax_key(float v, unsigned idx) {
+  unsigned u = __float_as_uint(v);
+  u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+  return ((unsigned long long)u << 32) | (unsigned long long)(0xFFFFFFFFu - idx);
+}
+__device__ __forceinline__ int key_index(unsigned long long key) {
+  return (int)(0xFFFFFFFFu - (unsigned)(key & 0xFFFFFFFFull));
+}
+
+// Vocabulary projection with the arg-max over the vocabulary fused into the epilogue: the
+// logits of the k x k outputs per sequence are never written unless `logits` is given.
+template <int MT, int NT, int KS>
+__global__ __launch_bounds__(256) void vocab_argmax_bf16_kernel(GemmP p, unsigned long long* keys,
+                                                                float* logits) {
+  __shared__ f32x4 red[KS == 4 ? 3 * MT * NT * 64 : 1];
+  GemmMain<MT, NT, KS> g;
+  g.run(p, red);
+  if (!g.active) return;
+  const int ntiles = p.N >> 4;
+#pragma unroll
+  for (int t = 0; t < MT; ++t) {
+    const int m = g.m0 + t * 16 + (g.lane & 15);
+    unsigned long long best = 0ull;
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+      if (g.nt0 + u >= ntiles) continue;
+      const int n = (g.nt0 + u) * 16 + (g.lane >> 4) * 4;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float v = g.acc[t][u][r];
+        const unsigned long long key = argmax_key(v, (unsigned)(n + r));
+        best = key > best ? key : best;
+        if (logits && m < p.M) logits[(long)m * p.N + n + r] = v;
+      }
+    }
+    // lanes l, l^16, l^32, l^48 hold the same row
+    unsigned long long o = __shfl_xor(best, 16, 64); best = o > best ? o : best;
+    o = __shfl_xor(best, 32, 64); best = o > best ? o : best;
+    if (g.lane < 16 && m < p.M) atomicMax(&keys[m], best);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// fp32 mode (small configurations): one thread per output element.
+__global__ void gemm_f32_kernel(GemmP p, Epi e) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  const int m = blockIdx.y, g = blockIdx.z;
+  if (n >= p.N || m >= p.M) return;
+  const float* X = (const float*)p.X + g * p.x_g + (long)m * p.ldx;
+  const float* W = (const float*)p.W + g * p.w_g + n;
+  float acc = 0.f;
+  for (int k = 0; k < p.K; ++k) acc = fmaf(X[k], W[(long)k * p.ldw], acc);
+  epi_store<float>(e, g, m, n, acc);
+}
+
+// fp32 vocabulary projection: E is [V][d] row-major; one workgroup per row of O.
+__global__ __launch_bounds__(256) void vocab_argmax_f32_kernel(const float* O, const float* E, int M, int V,
+                                                               int d, unsigned long long* keys, float* logits) {
+  const int m = blockIdx.x;
+  const float* o = O + (long)m * d;
+  unsigned long long best = 0ull;
+  for (int v = threadIdx.x; v < V; v += blockDim.x) {
+    const float* ev = E + (long)v * d;
+    float acc = 0.f;
+    for (int c = 0; c < d; ++c) acc = fmaf(o[c], ev[c], acc);
+    if (logits) logits[(long)m * V + v] = acc;
+    const unsigned long long key = argmax_key(acc, (unsigned)v);
+    best = key > best ? key : best;
+  }
+  for (int off = 32; off > 0; off >>= 1) {
+    unsigned long long o2 = __shfl_xor(best, off, 64);
+    best = o2 > best ? o2 : best;
+  }
+  if ((threadIdx.x & 63) == 0) atomicMax(&keys[m], best);
+}
+
+// ---------------------------------------------------------------------------------------
+// Weight conversion at load time.
+// src: [K][N_src] row-major (or, transposed, [N_src][K]) of float or bf16 bits.
+// bf16 mode: dst = packed tiles of a matrix with K rows; the tensor lands at columns n_off..
+// fp32 mode: dst = row-major [K][ldw] fp32, columns n_off..
+template <typename SRC, bool PACK>
+__global__ void convert_matrix_kernel(const SRC* src, void* dst, int K, int Nsrc, int transposed,
+                                      int ldw, int n_off) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long)K * Nsrc) return;
+  int k, n;
+  if (transposed) { n = (int)(idx / K); k = (int)(idx % K); } else { k = (int)(idx / Nsrc); n = (int)(idx % Nsrc); }
+  const float v = to_f<SRC>(src[idx]);
+  const int nn = n + n_off;
+  if (PACK) {
+    const int ksteps = K >> 5;
+    const long tile = (long)(nn >> 4) * ksteps + (k >> 5);
+    const int lane = 16 * ((k & 31) >> 3) + (nn & 15);
+    ((bf16_t*)dst)[(tile * 64 + lane) * 8 + (k & 7)] = f2bf(v);
+  } else {
+    ((float*)dst)[(long)k * ldw + nn] = v;
+  }
+}
+
+template <typename SRC>
+__global__ void convert_vector_kernel(const SRC* src, float* dst, long n) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < n) dst[idx] = to_f<SRC>(src[idx]);
+}
+
+// ---------------------------------------------------------------------------------------
+// Embedding of the k proposed tokens (decoder side) or of the source tokens.
+//   x[row][c] = sqrt(d) * E[tok][c] + pos[position][c];  tok < 0 -> zero vector (the shifted
+//   decoder input at position 0).  E is the packed vocabulary matrix in bf16 mode.
+template <bool BF16>
+__global__ void embed_kernel(const int* tok, int tok_ld, const int* base, int rows_per_seq, int M,
+                             int d, const void* E, int V, const float* pos, float scale, float* x,
+                             int zero_input) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long)M * d) return;
+  const int row = (int)(idx / d), c = (int)(idx % d);
+  const int b = row / rows_per_seq, i = row % rows_per_seq;
+  const int position = (base ? base[b] : 0) + i;
+  float v = pos[(long)position * d + c];
+  if (!zero_input) {
+    int t = tok[b * tok_ld + i];
+    t = t < 0 ? 0 : (t >= V ? V - 1 : t);      // ids are validated on the host; never index outside E
+    float ev;
+    if (BF16) {
+      const int ksteps = d >> 5;
+      const long tile = (long)(t >> 4) * ksteps + (c >> 5);
+      const int lane = 16 * ((c & 31) >> 3) + (t & 15);
+      ev = bf2f(((const bf16_t*)E)[(tile * 64 + lane) * 8 + (c & 7)]);
+    } else {
+      ev = ((const float*)E)[(long)t * d + c];
+    }
+    v += scale * ev;
+  }
+  x[idx] = v;
+}
+
+// LayerNorm over the last axis, one wavefront per row (biased variance, two passes).
+template <typename ACT>
+__global__ __launch_bounds__(256) void layernorm_kernel(const float* x, const float* g, const float* b, int M,
+                                                        int d, float eps, ACT* ya, float* yf) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= M) return;
+  const float* xr = x + (long)row * d;
+  float s = 0.f;
+  for (int c = lane; c < d; c += 64) s += xr[c];
+  const float mu = wave_sum(s) / d;
+  float q = 0.f;
+  for (int c = lane; c < d; c += 64) { const float t = xr[c] - mu; q += t * t; }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / d + eps);
+  for (int c = lane; c < d; c += 64) {
+    const float v = (xr[c] - mu) * rstd * g[c] + b[c];
+    if (ya) ya[(long)row * d + c] = from_f<ACT>(v);
+    if (yf) yf[(long)row * d + c] = v;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Attention of a tile of <= 16 query rows of one (sequence, head) over keys 0..n-1 held in a
+// K/V buffer: the decoder self-attention over the cache plus the block (block-causal: row i
+// sees keys < base[b] + i + 1), the cross attention (keys < len[b]) and the encoder's
+// self-attention.  Keys are visited in chunks of 256 with a running (max, sum) per row so
+// the LDS footprint does not depend on the cache length.
+//   Q    fp32 [B*R][d]                 out  act [B*R][d]
+//   Kc,Vc act, sequence b at Kc + b*kv_seq_stride, key s at + s*d, head h at + h*DH
+template <typename ACT, int DH> struct RowLoader;
+template <int DH> struct RowLoader<float, DH> {
+  static __device__ __forceinline__ void load(const float* p, float* out) {
+#pragma unroll
+    for (int x = 0; x < DH; x += 4) {
+      const float4 v = *(const float4*)(p + x);
+      out[x] = v.x; out[x + 1] = v.y; out[x + 2] = v.z; out[x + 3] = v.w;
+    }
+  }
+};
+template <int DH> struct RowLoader<bf16_t, DH> {
+  static __device__ __forceinline__ void load(const bf16_t* p, float* out) {
+#pragma unroll
+    for (int x = 0; x < DH; x += 8) {
+      const uint4 v = *(const uint4*)(p + x);
+      const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int y = 0; y < 4; ++y) {
+        out[x + 2 * y] = __uint_as_float(w[y] << 16);
+        out[x + 2 * y + 1] = __uint_as_float(w[y] & 0xFFFF0000u);
+      }
+    }
+  }
+};
+
+struct AttnP {
+  const float* Q;
+  const void* Kc; const void* Vc;
+  void* out;
+  long kv_seq_stride;
+  int d, R;
+  const int* limit;       // [B]: base (causal) or len (non-causal)
+  int causal;
+  float scale;
+};
+
+template <typename ACT, int DH>
+__global__ __launch_bounds__(256) void attention_kernel(AttnP p) {
+  constexpr int RT = 16, CH = 256, G = 256 / DH;
+  __shared__ float q_s[RT][DH];
+  __shared__ float sc[RT][CH];
+  __shared__ float red[G][RT][DH];
+  __shared__ float m_s[RT], l_s[RT], alpha_s[RT];
+  const int h = blockIdx.x, b = blockIdx.y, r0 = blockIdx.z * RT;
+  const int nrows = min(RT, p.R - r0);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lim = p.limit[b];
+  const ACT* Kb = (const ACT*)p.Kc + b * p.kv_seq_stride + h * DH;
+  const ACT* Vb = (const ACT*)p.Vc + b * p.kv_seq_stride + h * DH;
+  for (int idx = tid; idx < RT * DH; idx += 256) {
+    const int i = idx / DH, c = idx % DH;
+    q_s[i][c] = i < nrows ? p.Q[((long)b * p.R + r0 + i) * p.d + h * DH + c] * p.scale : 0.f;
+  }
+  if (tid < RT) { m_s[tid] = -INFINITY; l_s[tid] = 0.f; alpha_s[tid] = 1.f; }
+  const int nkeys = p.causal ? lim + r0 + nrows : lim;   // keys any row of the tile can see
+  float acc[RT];
+#pragma unroll
+  for (int i = 0; i < RT; ++i) acc[i] = 0.f;
+  const int g = tid / DH, c = tid % DH;
+  __syncthreads();
+  for (int c0 = 0; c0 < nkeys; c0 += CH) {
+    // scores of this chunk: one key per thread
+    const int key = c0 + tid;
+    if (key < nkeys) {
+      float kr[DH];
+      RowLoader<ACT, DH>::load(Kb + (long)key * p.d, kr);
+      for (int i = 0; i < nrows; ++i) {
+        float s = 0.f;
+#pragma unroll
+        for (int x = 0; x < DH; ++x) s = fmaf(q_s[i][x], kr[x], s);
+        const int nvis = p.causal ? lim + r0 + i + 1 : lim;
+        sc[i][tid] = key < nvis ? s : -INFINITY;
+      }
+    } else {
+      for (int i = 0; i < nrows; ++i) sc[i][tid] = -INFINITY;
+    }
+    __syncthreads();
+    // running max / sum per row; wave w owns rows w, w+4, ...
+    for (int i = wave; i < nrows; i += 4) {
+      float v[4], mx = -INFINITY;
+#pragma unroll
+      for (int x = 0; x < 4; ++x) { v[x] = sc[i][lane + 64 * x]; mx = fmaxf(mx, v[x]); }
+      mx = wave_max(mx);
+      const float m_old = m_s[i];
+      const float m_new = fmaxf(m_old, mx);
+      float sum = 0.f;
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        const float pv = (m_new == -INFINITY) ? 0.f : __expf(v[x] - m_new);
+        sc[i][lane + 64 * x] = pv;
+        sum += pv;
+      }
+      sum = wave_sum(sum);
+      if (lane == 0) {
+        const float a = (m_new == -INFINITY) ? 1.f : __expf(m_old - m_new);
+        alpha_s[i] = a;
+        l_s[i] = l_s[i] * a + sum;
+        m_s[i] = m_new;
+      }
+    }
+    __syncthreads();
+    // weighted values: thread (g, c) walks keys g, g+G, ... of the chunk for feature c
+#pragma unroll
+    for (int i = 0; i < RT; ++i) acc[i] *= alpha_s[i];
+    const int kend = min(CH, nkeys - c0);
+    for (int kk = g; kk < kend; kk += G) {
+      const float v = to_f<ACT>(Vb[(long)(c0 + kk) * p.d + c]);
+#pragma unroll
+      for (int i = 0; i < RT; ++i) acc[i] = fmaf(sc[i][kk], v, acc[i]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < RT; ++i) red[g][i][c] = acc[i];
+  __syncthreads();
+  for (int idx = tid; idx < nrows * DH; idx += 256) {
+    const int i = idx / DH, cc = idx % DH;
+    float s = 0.f;
+    for (int gg = 0; gg < G; ++gg) s += red[gg][i][cc];
+    ((ACT*)p.out)[((long)b * p.R + r0 + i) * p.d + h * DH + cc] = from_f<ACT>(s / l_s[i]);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Decode state (all arrays on the device, one entry per sequence).
+struct StateP {
+  int* L;            // committed decoder-cache rows = j + 1
+  int* j;            // accepted tokens so far
+  int* finished;
+  int* max_len;
+  int* P;            // [B][kmax]
+  int* A;            // [B][kmax][kmax]
+  int* accepted;     // [B] k-hat of the last step
+  int* out_ids;      // [B][max_out]
+  long long* stats;  // [0] seq_steps [1] accepted_total [2] finished [3..19] hist[0..16] [20] live steps
+  const int* imposed;  // k-hat to impose: imposed[step * imposed_stride + b], or null
+  int imposed_stride;  // B for a whole schedule, 0 for a single step's vector
+  int* step_counter;
+  int kmax, max_out, eos_id;
+  int distance_eps, min_block;
+};
+
+__global__ void fill_u64_kernel(unsigned long long* p, long n, unsigned long long v) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+__global__ void fill_i32_kernel(int* p, long n, int v) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// After the first invocation on the empty prefix: P <- heads at position 0, j = 0, L = 1.
+__global__ void prime_kernel(StateP s, const unsigned long long* keys, int B) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  if (b >= B) return;
+  if (lane < s.kmax) {
+    const int a = key_index(keys[b * s.kmax + lane]);
+    s.P[b * s.kmax + lane] = a;
+    s.A[(b * s.kmax + 0) * s.kmax + lane] = a;
+  }
+  if (lane == 0) { s.L[b] = 1; s.j[b] = 0; s.finished[b] = 0; s.accepted[b] = 0; }
+}
+
+// Verify / accept / commit for one sequence per wavefront.
+//   keys: [B][k][k] packed argmax keys of this invocation (row i', head i).
+//   verify (exact, or |P - argmax| <= eps):  lane i (1 <= i < k) tests proposal P[i] against
+//   head 1 at row i-1; the accepted length is the position of the first failing lane (a
+//   ballot and a count of trailing ones), forced up to min_block, or replaced by the imposed
+//   value; then cut at the first EOS (inclusive) and at max_len; append; L += k-hat commits
+//   the cache rows of the accepted tokens (rejected rows are simply overwritten next step);
+//   P <- row k-hat of the table.
+__global__ __launch_bounds__(64) void accept_kernel(StateP s, const unsigned long long* keys, int k, int B,
+                                                    int commit) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  if (b >= B) return;
+  for (int e = lane; e < k * k; e += 64) {
+    const int ip = e / k, i = e % k;
+    s.A[(b * s.kmax + ip) * s.kmax + i] = key_index(keys[(long)b * k * k + e]);
+  }
+  if (!commit) return;
+  const int step = *s.step_counter;
+  if (s.finished[b]) {
+    if (lane == 0) s.accepted[b] = 0;
+    return;
+  }
+  const int myP = lane < k ? s.P[b * s.kmax + lane] : -1;
+  bool ok = true;
+  if (lane >= 1 && lane < k) {
+    const int a1 = key_index(keys[(long)b * k * k + (lane - 1) * k + 0]);
+    const int diff = myP > a1 ? myP - a1 : a1 - myP;
+    ok = diff <= s.distance_eps;
+  }
+  const unsigned long long lanes_k = (k >= 64) ? ~0ull : ((1ull << k) - 1ull);
+  const unsigned long long bad = (~__ballot(ok)) & lanes_k;
+  int khat = bad ? __ffsll((long long)bad) - 1 : k;
+  if (khat < s.min_block) khat = s.min_block < k ? s.min_block : k;
+  if (s.imposed) {
+    int v = s.imposed[(long)step * s.imposed_stride + b];
+    khat = v < 1 ? 1 : (v > k ? k : v);
+  }
+  bool eos = false;
+  if (s.eos_id >= 0) {
+    const unsigned long long eb = __ballot(lane < khat && myP == s.eos_id);
+    if (eb) { khat = __ffsll((long long)eb); eos = true; }
+  }
+  const int j = s.j[b];
+  const int room = s.max_len[b] - j;
+  if (khat > room) { khat = room; eos = false; }   // the EOS, if any, was the last accepted token
+  if (lane < khat) s.out_ids[(long)b * s.max_out + j + lane] = myP;
+  const int nextP = lane < k ? key_index(keys[(long)b * k * k + (khat - 1) * k + lane]) : 0;
+  if (lane < k) s.P[b * s.kmax + lane] = nextP;
+  if (lane == 0) {
+    const int fin = eos || (j + khat >= s.max_len[b]);
+    s.j[b] = j + khat;
+    s.L[b] = s.L[b] + khat;
+    s.finished[b] = fin;
+    s.accepted[b] = khat;
+    atomicAdd((unsigned long long*)&s.stats[0], 1ull);
+    atomicAdd((unsigned long long*)&s.stats[1], (unsigned long long)khat);
+    if (fin) atomicAdd((unsigned long long*)&s.stats[2], 1ull);
+    atomicAdd((unsigned long long*)&s.stats[3 + khat], 1ull);
+    atomicMax((unsigned long long*)&s.stats[20], (unsigned long long)(step + 1));   // steps with a live sequence
+  }
+}
+
+__global__ void bump_step_kernel(int* step_counter) { *step_counter += 1; }

@@ -1,0 +1,241 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded
+inputs.  Comparison rules are stated in tests/harness.py."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import workloads as wl
+from harness import TOL, LockStep, check_argmax, gpu_context, oracle_model
+from oracle import blockwise_decode, greedy_decode, scorers
+
+pytestmark = pytest.mark.gpu
+
+SMALL_F32 = wl.Config("S-f32", 11, 2, 2, 64, 4, 128, 256, 4, 3, 12, 24, "f32", 2, src_kind="uniform3",
+                      src_len_kind="lognormal")
+SMALL_BF16 = wl.Config("S-bf16", 12, 2, 2, 128, 2, 256, 512, 5, 3, 12, 24, "bf16", 2, src_kind="uniform3",
+                       src_len_kind="lognormal")
+# several 16-row tiles and a ragged tail: 7 sequences x 6 rows = 42 rows, 252 vocab-projection rows
+MID_BF16 = wl.Config("M-bf16", 13, 2, 3, 256, 4, 512, 2000 + 16, 6, 7, 20, 40, "bf16", 2, src_len_kind="lognormal")
+MID_F32_DH16 = wl.Config("M-f32", 14, 1, 2, 64, 4, 96, 272, 3, 5, 9, 30, "f32", 2, src_kind="uniform3",
+                         src_len_kind="lognormal")
+
+
+def ragged_sources(cfg, seed):
+    src, n = wl.make_sources(cfg, seed=seed)
+    rng = np.random.default_rng(seed)
+    n = rng.integers(1, cfg.max_src + 1, size=cfg.batch).astype(np.int32)
+    n[0] = 1
+    n[-1] = cfg.max_src
+    for b in range(cfg.batch):
+        src[b, n[b]:] = cfg.pad_id
+    return src, n
+
+
+@pytest.mark.parametrize("cfg", [SMALL_F32, MID_F32_DH16, SMALL_BF16, MID_BF16], ids=lambda c: c.name)
+def test_lockstep_small(cfg):
+    """Teacher-forced steps with imposed and exact acceptance on ragged batches; logits, argmax
+    table, accepted lengths, appended tokens and termination all checked per step."""
+    # bf16 cases use the workloads' own N(0, 0.02): the 2e-2 logit tolerance is stated for it
+    weights = wl.make_weights(cfg, std=0.08 if cfg.dtype == "f32" else 0.02)
+    ctx = gpu_context(cfg, weights)
+    src, n = ragged_sources(cfg, 5)
+    max_len = np.array([cfg.max_out - 3 * b for b in range(cfg.batch)], dtype=np.int32)
+    ls = LockStep(cfg, weights, ctx, src, n, max_len)
+    sched = wl.make_schedule(cfg, 2.5, 64, seed=3)
+    for s in range(10):
+        ls.step(imposed=sched[s])
+    for s in range(6):
+        ls.step(imposed=None)
+    # run everything to the end with whole blocks
+    for s in range(cfg.max_out):
+        if all(ls.done.values()):
+            break
+        ls.step(imposed=np.full(cfg.batch, cfg.k, dtype=np.int32), check_logits=False)
+    assert all(ls.done.values())
+    st = ctx.bpd_get_stats()
+    assert st.finished == cfg.batch and st.invocations == st.steps + 1
+    assert st.accepted_total == sum(len(p) for p in ls.prefix.values())
+    assert sum(st.hist) == st.seq_steps
+    # and the table is bit-identical almost everywhere (bf16: wherever no near-tie occurs)
+    assert np.mean(ls.match) > (0.99 if cfg.dtype == "f32" else 0.6)
+    print(cfg.name, "max logit err", ls.max_logit_err, "bit-identical argmax fraction", np.mean(ls.match))
+
+
+def test_c0_exact_decode_equals_greedy():
+    """Workload C0 (fp32): free-running exact-match decoding on the GPU reproduces the oracle's
+    greedy output token for token; k = 1 does the same one token per step."""
+    cfg = wl.C0
+    weights = wl.make_weights(cfg)
+    model = oracle_model(cfg, weights)
+    src, n = wl.make_sources(cfg)
+    score, block = scorers(model, src[0, :n[0]])
+    gr = greedy_decode(score, cfg.max_out, cfg.eos_id)
+    ref = blockwise_decode(score, cfg.k, cfg.max_out, cfg.eos_id, block_score=block)
+    assert ref.tokens == gr.tokens
+    # margins of the greedy path: bit-exactness is only demanded where they exceed the tolerance
+    margins = []
+    for t in range(len(gr.tokens)):
+        z = np.sort(score(gr.tokens[:t])[0])
+        margins.append(z[-1] - z[-2])
+    ctx = gpu_context(cfg, weights)
+    for k in (cfg.k, 1, 2):
+        ctx.bpd_encode(src, n)
+        out_ids, out_len, st = ctx.bpd_decode(k)
+        got = out_ids[0, :out_len[0]].tolist()
+        if min(margins) >= 2 * TOL["f32"]:
+            assert got == gr.tokens
+        else:                                   # compare up to the first near-tie
+            first = int(np.argmax(np.array(margins) < 2 * TOL["f32"]))
+            assert got[:first] == gr.tokens[:first]
+        assert st.invocations == st.steps + 1
+        assert st.accepted_total == out_len[0]
+        if k == 1:
+            assert st.steps == out_len[0] and st.hist[1] == st.steps
+        if k == cfg.k and min(margins) >= 2 * TOL["f32"]:
+            assert st.steps == len(ref.steps)
+            assert [i for i in range(17) for _ in range(st.hist[i])] == sorted(ref.block_sizes)
+
+
+def test_free_running_bf16_is_a_valid_greedy_path():
+    """bf16, no teacher forcing: every token the GPU emits must be within tolerance of the
+    oracle's best token given the GPU's own prefix, and every block boundary consistent."""
+    cfg = SMALL_BF16
+    weights = wl.make_weights(cfg, std=0.02)
+    model = oracle_model(cfg, weights)
+    ctx = gpu_context(cfg, weights)
+    src, n = ragged_sources(cfg, 9)
+    ctx.bpd_encode(src, n)
+    out_ids, out_len, st = ctx.bpd_decode(cfg.k)
+    assert st.finished == cfg.batch
+    for b in range(cfg.batch):
+        toks = out_ids[b, :out_len[b]].tolist()
+        assert 1 <= len(toks) <= cfg.max_out
+        assert cfg.eos_id not in toks[:-1]
+        assert toks[-1] == cfg.eos_id or len(toks) == cfg.max_out
+        score, _ = scorers(model, src[b, :n[b]])
+        z = np.stack([score(toks[:t])[0] for t in range(len(toks))])
+        check_argmax(np.array(toks), z, TOL["bf16"], f"free-running b={b}")
+
+
+def test_determinism_and_k_smaller_than_kmax():
+    cfg = MID_BF16
+    weights = wl.make_weights(cfg, std=0.02)
+    ctx = gpu_context(cfg, weights)
+    src, n = ragged_sources(cfg, 2)
+    runs = []
+    for _ in range(2):
+        ctx.bpd_encode(src, n)
+        sched = wl.make_schedule(cfg, 2.0, 40, seed=8, k=4)
+        out_ids, out_len, st = ctx.bpd_decode(4, schedule=sched)
+        runs.append((out_ids.copy(), out_len.copy(), list(st.hist), ctx.bpd_get_state()))
+    np.testing.assert_array_equal(runs[0][0], runs[1][0])
+    np.testing.assert_array_equal(runs[0][1], runs[1][1])
+    assert runs[0][2] == runs[1][2]
+    for a, b in zip(runs[0][3], runs[1][3]):
+        np.testing.assert_array_equal(a, b)
+    # k = 4 of 6 heads, teacher-forced against the oracle
+    ls = LockStep(cfg, weights, ctx, src, n, np.full(cfg.batch, cfg.max_out, np.int32), k=4, sample=[0, 3, 6])
+    for s in range(4):
+        ls.step(imposed=np.array([1, 2, 3, 4, 4, 1, 2], dtype=np.int32))
+
+
+def test_relaxed_acceptance_on_gpu():
+    """Distance-based acceptance and minimum block size (Sections 5.2, 5.3) in the accept kernel:
+    eps = 0 / l = 1 is exact; l = k gives fixed blocks; a large eps accepts everything."""
+    cfg = SMALL_F32
+    weights = wl.make_weights(cfg, std=0.08)
+    ctx = gpu_context(cfg, weights)
+    src, n = ragged_sources(cfg, 4)
+    ctx.bpd_encode(src, n)
+    ids0, len0, st0 = ctx.bpd_decode(cfg.k)
+    ctx.bpd_set_acceptance(0, 1)
+    ctx.bpd_encode(src, n)
+    ids1, len1, st1 = ctx.bpd_decode(cfg.k)
+    np.testing.assert_array_equal(ids0, ids1)
+    for eps, lmin in [(cfg.vocab, 1), (0, cfg.k)]:
+        ctx.bpd_set_acceptance(eps, lmin)
+        ctx.bpd_encode(src, n)
+        ids, lens, st = ctx.bpd_decode(cfg.k)
+        # every step takes a full block unless cut by EOS or the budget
+        assert st.steps <= -(-cfg.max_out // cfg.k)
+        model = oracle_model(cfg, weights)
+        for b in range(cfg.batch):
+            score, block = scorers(model, src[b, :n[b]])
+            from oracle import accept_distance
+            ref = blockwise_decode(score, cfg.k, cfg.max_out, cfg.eos_id, accept=accept_distance(eps),
+                                   min_block=lmin, block_score=block)
+            assert ids[b, :lens[b]].tolist() == ref.tokens
+    ctx.bpd_set_acceptance(0, 1)
+
+
+def test_error_codes_on_gpu():
+    from paper_1811_03115_amd import binding
+    cfg = SMALL_F32
+    weights = wl.make_weights(cfg)
+    ctx = binding.Context(binding.config_from_workload(cfg))
+    src, n = ragged_sources(cfg, 1)
+    with pytest.raises(binding.BpdError) as e:
+        ctx.bpd_encode(src, n)                          # weights not loaded
+    assert e.value.code == -2
+    some = {k: v for i, (k, v) in enumerate(weights.items()) if i % 2 == 0}
+    ctx.bpd_load_weights(some)
+    with pytest.raises(binding.BpdError) as e:
+        ctx.bpd_encode(src, n)
+    assert e.value.code == -2
+    with pytest.raises(binding.BpdError) as e:
+        ctx.bpd_load_weights({"nonsense": np.zeros(3, np.float32)})
+    assert e.value.code == -4
+    with pytest.raises(binding.BpdError) as e:
+        ctx.bpd_load_weights({"emb": np.zeros((3, 3), np.float32)})
+    assert e.value.code == -4
+    ctx.bpd_load_weights(weights)
+    ctx.B = cfg.batch
+    with pytest.raises(binding.BpdError) as e:
+        ctx.bpd_step(cfg.k)                             # no encode yet
+    assert e.value.code == -2
+    big = np.zeros((cfg.batch + 1, cfg.max_src), np.int32) + 3
+    with pytest.raises(binding.BpdError) as e:
+        ctx.bpd_encode(big, np.ones(cfg.batch + 1, np.int32))
+    assert e.value.code == -3
+    bad_len = n.copy(); bad_len[0] = cfg.max_src + 1
+    with pytest.raises(binding.BpdError) as e:
+        ctx.bpd_encode(src, bad_len)
+    assert e.value.code == -1
+    bad_ids = src.copy(); bad_ids[0, 0] = cfg.vocab
+    with pytest.raises(binding.BpdError) as e:
+        ctx.bpd_encode(bad_ids, n)
+    assert e.value.code == -1
+    ctx.bpd_encode(src, n)
+    for k in (0, cfg.k + 1):
+        with pytest.raises(binding.BpdError) as e:
+            ctx.bpd_step(k)
+        assert e.value.code == -1
+    P, A, j, fin = ctx.bpd_get_state()
+    ctx.bpd_step(cfg.k)                                 # state was left usable by the failed calls
+    assert (ctx.bpd_get_state()[2] >= 1).all()
+    # too small a workspace is refused
+    c = binding.config_from_workload(cfg)
+    import torch
+    ws = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    h = ctypes.c_void_p()
+    base = (ws.data_ptr() + 255) // 256 * 256
+    assert binding.lib().bpd_create(ctypes.byref(c), base, 512, None, ctypes.byref(h)) == -3
+
+
+def test_degenerate_shapes():
+    """One-token source, budget of one token, single sequence, k = 1."""
+    cfg = SMALL_F32
+    weights = wl.make_weights(cfg, std=0.08)
+    ctx = gpu_context(cfg, weights)
+    src = np.full((1, 1), 7, dtype=np.int32)
+    n = np.array([1], np.int32)
+    ls = LockStep(cfg, weights, ctx, src, n, np.array([1], np.int32))
+    acc = ls.step(imposed=np.array([cfg.k], np.int32))
+    assert acc.tolist() == [1] and ls.done[0]
+    acc = ls.step(imposed=None, check_logits=False)          # finished sequences report 0
+    assert acc.tolist() == [0]
+    ls = LockStep(cfg, weights, ctx, src, n, np.array([5], np.int32), k=1)
+    for _ in range(5):
+        if not ls.done[0]:
+            assert ls.step().tolist() == [1]

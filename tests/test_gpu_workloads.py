@@ -1,0 +1,178 @@
+"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py
+times.  The oracle recomputes sampled sequences only (it needs seconds per block at these
+sizes); integer bookkeeping is replayed on the host for every sequence."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from harness import TOL, LockStep, check_argmax, gpu_context, oracle_model
+from oracle import scorers
+
+pytestmark = pytest.mark.gpu
+
+_cache = {}
+
+
+def big():
+    """Transformer-big weights and one context sized for batch 32 (shared by C2 and C3)."""
+    if "big" not in _cache:
+        w = wl.make_weights(wl.C2)
+        _cache["big"] = (w, gpu_context(wl.C3, w))
+    return _cache["big"]
+
+
+def replay_accept(cfg, out_ids, sched, max_len, k):
+    """Host replay of accept/commit bookkeeping for one sequence given the tokens it produced:
+    returns (out_len, block sizes)."""
+    j, blocks = 0, []
+    for s in range(sched.shape[0]):
+        if j >= max_len:
+            break
+        a = int(np.clip(sched[s], 1, k))
+        seg = out_ids[j:j + a].tolist()
+        eos = False
+        if cfg.eos_id >= 0 and cfg.eos_id in seg:
+            a = seg.index(cfg.eos_id) + 1
+            eos = True
+        if a > max_len - j:
+            a, eos = max_len - j, False
+        blocks.append(a)
+        j += a
+        if eos:
+            break
+    return j, blocks
+
+
+def check_state_against_oracle(ctx, cfg, model, src, n, b, k):
+    """At whatever state the GPU is in: its logits for the next block of sequence b against the
+    oracle's full recomputation over the GPU's own accepted prefix and proposals."""
+    out_ids, out_len = ctx.bpd_get_output()
+    P, _, j, _ = ctx.bpd_get_state()
+    prefix = out_ids[b, :out_len[b]].tolist()
+    _, block = scorers(model, src[b, :n[b]])
+    z = block(prefix, P[b, :k].tolist())[:, :k]
+    lg = ctx.bpd_debug_step_logits(k)[b].cpu().numpy()
+    err = float(np.abs(lg - z).max())
+    assert err <= TOL[cfg.dtype], f"logits at j={out_len[b]}: max abs err {err}"
+    _, A, _, _ = ctx.bpd_get_state()
+    check_argmax(A[b, :k, :k], z, TOL[cfg.dtype], f"A at j={out_len[b]}")
+    return err
+
+
+def test_c1_base_batch1():
+    cfg = wl.C1
+    weights = wl.make_weights(cfg)
+    ctx = gpu_context(cfg, weights)
+    src, n = wl.make_sources(cfg)
+    ls = LockStep(cfg, weights, ctx, src, n, wl.make_max_len(cfg, n))
+    sched = wl.make_schedule(cfg, 4, 8)
+    for s in range(3):
+        ls.step(imposed=sched[s])
+    ls.step(imposed=None)
+    print("C1 max logit err", ls.max_logit_err, "identical argmax fraction", np.mean(ls.match))
+    # whole decodes under the four imposed schedules (mean accepted length 1, 2, 4, 8)
+    for mean in (1, 2, 4, 8):
+        sched = wl.make_schedule(cfg, mean, cfg.max_out)
+        ctx.bpd_encode(src, n)
+        out_ids, out_len, st = ctx.bpd_decode(cfg.k, schedule=sched)
+        jl, blocks = replay_accept(cfg, out_ids[0], sched[:, 0], cfg.max_out, cfg.k)
+        assert out_len[0] == jl and st.steps == len(blocks) and st.accepted_total == jl
+        assert [st.hist[a] for a in range(17)] == [blocks.count(a) for a in range(17)]
+        assert st.invocations == st.steps + 1 and st.finished == 1
+        assert (out_ids[0, :jl] >= 0).all() and (out_ids[0, :jl] < cfg.vocab).all()
+
+
+def test_c2_big_batch1():
+    cfg = wl.C2
+    weights, ctx = big()
+    src, n = wl.make_sources(cfg)
+    ls = LockStep(cfg, weights, ctx, src, n, wl.make_max_len(cfg, n))
+    sched = wl.make_schedule(cfg, 5, 8)
+    for s in range(3):
+        ls.step(imposed=sched[s])
+    ls.step(imposed=None)
+    print("C2 max logit err", ls.max_logit_err, "identical argmax fraction", np.mean(ls.match))
+    # deeper in the decode: run on without the oracle, then check the state reached
+    for s in range(6):
+        ctx.bpd_step(cfg.k, np.array([cfg.k], np.int32))
+    err = check_state_against_oracle(ctx, cfg, ls.model, src, n, 0, cfg.k)
+    print("C2 logit err at depth", err)
+
+
+def test_c3_big_batch32_ragged():
+    cfg = wl.C3
+    weights, ctx = big()
+    src, n = wl.make_sources(cfg)
+    max_len = wl.make_max_len(cfg, n)
+    sample = [0, 13, 31]
+    ls = LockStep(cfg, weights, ctx, src, n, max_len, sample=sample)
+    sched = wl.make_schedule(cfg, 3, cfg.max_out)
+    for s in range(3):
+        ls.step(imposed=sched[s])
+    print("C3 max logit err", ls.max_logit_err, "identical argmax fraction", np.mean(ls.match))
+    # whole ragged decode: every sequence's bookkeeping replayed on the host
+    ctx.bpd_encode(src, n, max_len)
+    out_ids, out_len, st = ctx.bpd_decode(cfg.k, schedule=sched)
+    hist = [0] * 17
+    steps = 0
+    for b in range(cfg.batch):
+        jl, blocks = replay_accept(cfg, out_ids[b], sched[:, b], int(max_len[b]), cfg.k)
+        assert out_len[b] == jl, f"b={b}"
+        assert (out_ids[b, jl:] == cfg.pad_id).all()
+        for a in blocks:
+            hist[a] += 1
+        steps = max(steps, len(blocks))
+    assert [st.hist[a] for a in range(17)] == hist
+    assert st.steps == steps and st.finished == cfg.batch and st.accepted_total == int(out_len.sum())
+    # sequences ended at different steps
+    assert len(set(out_len.tolist())) > 4
+
+
+def test_c4_superres_long_cache():
+    cfg = wl.C4
+    weights = wl.make_weights(cfg)
+    ctx = gpu_context(cfg, weights)
+    model = oracle_model(cfg, weights)
+    src, n = wl.make_sources(cfg)
+    max_len = wl.make_max_len(cfg, n)
+    ls = LockStep(cfg, weights, ctx, src, n, max_len, sample=[0, 5])
+    sched = wl.make_schedule(cfg, 7, 600)
+    for s in range(2):
+        ls.step(imposed=sched[s])
+    print("C4 max logit err", ls.max_logit_err, "identical argmax fraction", np.mean(ls.match))
+    # fixed-length decoding (no EOS): run deep into the 3072-token output, check states on the way
+    ctx.bpd_encode(src, n, max_len)
+    full = np.full(cfg.batch, cfg.k, np.int32)
+    for s in range(60):
+        ctx.bpd_step(cfg.k, full)
+    e1 = check_state_against_oracle(ctx, cfg, model, src, n, 3, cfg.k)        # j = 600
+    out_ids, out_len, st = ctx.bpd_decode(cfg.k, schedule=sched)
+    assert (out_len == 3072).all() and st.finished == cfg.batch
+    assert out_ids.min() >= 0 and out_ids.max() < 256
+    for b in (0, 7):
+        jl, blocks = replay_accept(cfg, out_ids[b], np.concatenate([np.full(60, cfg.k), sched[:, b]]), 3072, cfg.k)
+        assert jl == 3072
+    print("C4 logit err at j=600:", e1, "steps", st.steps)
+
+
+def test_c4_near_full_cache():
+    """The last blocks of a 3072-token output: cache rows up to 3072 + k are live."""
+    cfg = wl.C4
+    weights = wl.make_weights(cfg)
+    ctx = gpu_context(wl.scaled(cfg, batch=2), weights)
+    model = oracle_model(cfg, weights)
+    src, n = wl.make_sources(cfg)
+    src, n = src[:2], n[:2]
+    ctx.bpd_encode(src, n)
+    full = np.full(2, cfg.k, np.int32)
+    for s in range(306):
+        ctx.bpd_step(cfg.k, full)
+    _, _, j, fin = ctx.bpd_get_state()
+    assert j.tolist() == [3060, 3060] and not fin.any()
+    err = check_state_against_oracle(ctx, cfg, model, src, n, 1, cfg.k)
+    print("C4 logit err at j=3060:", err)
+    acc = np.zeros(2, np.int32)
+    ctx.bpd_step(cfg.k, full)
+    ctx.bpd_step(cfg.k, full)
+    _, _, j, fin = ctx.bpd_get_state()
+    assert j.tolist() == [3072, 3072] and fin.all()
