@@ -40,7 +40,7 @@ struct Layout {
   // caches
   void *selfK, *selfV, *crossK, *crossV;        // [n_dec][B][slots|max_src][d]
   // decoder activations (M = max_batch * k_max rows)
-  float *x, *q, *h; void *xn, *attn, *ffh, *hn, *H, *O;
+  float *x, *q, *h, *stats_ln; void *xn, *attn, *ffh, *hn, *H, *O;
   unsigned long long* keys;
   // encoder activations (max_batch * max_src rows)
   float *xe, *qe; void *xen, *ke, *ve, *attne, *ffhe, *mem;
@@ -58,6 +58,7 @@ bool config_ok(const bpd_config& c) {
   if (c.d_model % c.n_heads) return false;
   const int dh = c.d_model / c.n_heads;
   if (dh != 16 && dh != 64) return false;
+  if (c.dtype == BPD_F32 && dh != 16) return false;     // fp32 mode is for small models only
   if (c.d_model % 32 || c.d_ff % 32 || c.vocab % 16 || c.vocab < 16) return false;
   if (c.k_max < 1 || c.k_max > 16) return false;
   if (c.max_batch < 1 || c.max_src_len < 1 || c.max_out_len < 1) return false;
@@ -94,7 +95,7 @@ size_t build_layout(const bpd_config& c, char* base, Layout& L) {
   L.selfK = a.take(nd * B * slots * d * as); L.selfV = a.take(nd * B * slots * d * as);
   L.crossK = a.take(nd * B * S * d * as);    L.crossV = a.take(nd * B * S * d * as);
   const size_t M = B * k;
-  L.x = vec(M * d); L.q = vec(M * d); L.h = vec(M * d);
+  L.x = vec(M * d); L.q = vec(M * d); L.h = vec(M * d); L.stats_ln = vec(64 * 16 * 2);
   L.xn = a.take(M * d * as); L.attn = a.take(M * d * as); L.ffh = a.take(M * F * as);
   L.hn = a.take(M * d * as); L.H = a.take(M * k * F * as); L.O = a.take(M * k * d * as);
   L.keys = (unsigned long long*)a.take(M * k * 8);
@@ -225,32 +226,136 @@ void launch_gemm_bf16(const GemmP& p, const Epi& e, int groups, hipStream_t s) {
   dim3 grid(KS == 4 ? (ntiles + NT - 1) / NT : (ntiles + 4 * NT - 1) / (4 * NT), (p.M + 16 * MT - 1) / (16 * MT), groups);
   hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, KS>), grid, dim3(256), 0, s, p, e);
 }
-template <int MT, int NT, int KS>
-void launch_vocab_bf16(const GemmP& p, unsigned long long* keys, float* logits, hipStream_t s) {
+
+// ---- skinny path: M <= 16 -------------------------------------------------------------
+template <int NT, bool XLN, bool ARGMAX>
+void launch_skinny(const GemmP& p, const Epi& e, const LnP& ln, unsigned long long* keys, float* logits, int groups,
+                   hipStream_t s) {
   const int ntiles = p.N / 16;
-  dim3 grid(KS == 4 ? (ntiles + NT - 1) / NT : (ntiles + 4 * NT - 1) / (4 * NT), (p.M + 16 * MT - 1) / (16 * MT), 1);
-  hipLaunchKernelGGL((vocab_argmax_bf16_kernel<MT, NT, KS>), grid, dim3(256), 0, s, p, keys, logits);
+  const int ngroups = (ntiles + NT - 1) / NT;
+  const int gx = ngroups > 512 ? 512 : ngroups;  // beyond 512 workgroups each one walks several column tiles
+  dim3 grid(gx, 1, groups);
+  // K split over the waves of a workgroup so that each wave holds all its k-steps in registers
+#define BPD_SK(W_, U_, P_) hipLaunchKernelGGL((skinny_gemm_kernel<NT, (W_ == 8 && U_ == 4) ? XLN : false, ARGMAX, W_, U_, P_>), grid, dim3(64 * W_), 0, s, p, e, ln, keys, logits)
+  if (XLN) {                                    // K <= 1024
+    if (ngroups > gx) BPD_SK(8, 4, true); else BPD_SK(8, 4, false);
+  } else if (p.K <= 1024) {
+    if (ngroups > gx) BPD_SK(4, 8, true); else BPD_SK(4, 8, false);
+  } else {                                      // K <= 4096
+    if (ngroups > gx) BPD_SK(8, 16, true); else BPD_SK(8, 16, false);
+  }
+#undef BPD_SK
 }
 
-// Tile shape by problem shape: few rows -> one workgroup per 16 columns with the 4 waves
-// splitting K (many small workgroups keep every CU streaming weights); many columns -> each
-// wave its own column tile; many rows -> 64x256 output tiles per workgroup.
-#define DISPATCH_TILES(LAUNCH, ...)                                          \
-  do {                                                                       \
-    const bool wide = (p.N / 16) >= 1024;                                    \
-    if (p.M > 128) { LAUNCH<4, 4, 1>(__VA_ARGS__); }                         \
-    else if (p.M > 64) { if (wide) LAUNCH<8, 1, 1>(__VA_ARGS__); else LAUNCH<8, 1, 4>(__VA_ARGS__); } \
-    else if (p.M > 32) { if (wide) LAUNCH<4, 1, 1>(__VA_ARGS__); else LAUNCH<4, 1, 4>(__VA_ARGS__); } \
-    else if (p.M > 16) { if (wide) LAUNCH<2, 1, 1>(__VA_ARGS__); else LAUNCH<2, 1, 4>(__VA_ARGS__); } \
-    else { if (wide) LAUNCH<1, 1, 1>(__VA_ARGS__); else LAUNCH<1, 1, 4>(__VA_ARGS__); }               \
-  } while (0)
+bool skinny_ok(const bpd_ctx* ctx, const GemmP& p) { return ctx->cfg.dtype == BPD_BF16 && p.M <= 16 && p.K <= 4096; }
+// LayerNorm statistics ride along with the residual stream when the whole block is one MFMA row tile
+bool stats_path(const bpd_ctx* ctx, int M) {
+  return ctx->cfg.dtype == BPD_BF16 && M <= 16 && ctx->cfg.d_model <= 1024;
+}
 
+// ---- ldsx path: many rows ---------------------------------------------------------------
+template <int MT, int NT, int KC, bool ARGMAX>
+void launch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* logits, int groups, hipStream_t s) {
+  const int ntiles = p.N / 16;
+  dim3 grid((ntiles + 4 * NT - 1) / (4 * NT), (p.M + 16 * MT - 1) / (16 * MT), groups);
+  const size_t lds = (size_t)2 * 16 * MT * (KC + 8) * 2;
+  static bool attr_set = false;                 // per instantiation: allow more than 64 KiB of LDS
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)gemm_ldsx_kernel<MT, NT, KC, ARGMAX>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((gemm_ldsx_kernel<MT, NT, KC, ARGMAX>), grid, dim3(256), lds, s, p, e, keys, logits);
+}
+
+// Row-tile height: the one of {128, 112, 80, 64, 32} rows that pads M least (ties: taller).
+int pick_mt(int M) {
+  const int cands[5] = {8, 7, 5, 4, 2};
+  int best = 8; long best_pad = -1;
+  for (int mt : cands) {
+    const long bm = 16 * mt, padded = (M + bm - 1) / bm * bm;
+    if (best_pad < 0 || padded < best_pad) { best_pad = padded; best = mt; }
+  }
+  return best;
+}
+// Column tiles per wave: as many as still leave >= 256 workgroups (one per CU).
+int pick_nt(int M, int N, int mt, int groups) {
+  const long mblocks = (M + 16 * mt - 1) / (16 * mt);
+  for (int nt : {4, 2}) {
+    const long wgs = ((N / 16 + 4 * nt - 1) / (4 * nt)) * mblocks * groups;
+    if (wgs >= 256) return nt;
+  }
+  return 1;
+}
+
+template <bool ARGMAX>
+void dispatch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* logits, int groups, hipStream_t s) {
+  const int mt = pick_mt(p.M), nt = pick_nt(p.M, p.N, mt, groups);
+  const long mblocks = (p.M + 16 * mt - 1) / (16 * mt);
+  // one row block and wide N: the kernel is a pure weight stream; deep chunks keep ~64 KiB of
+  // weights in flight per CU
+  if (mblocks == 1 && nt == 2 && p.K % 256 == 0) {
+#define BPD_CASE(MT_) if (mt == MT_) { launch_ldsx<MT_, 2, 256, ARGMAX>(p, e, keys, logits, groups, s); return; }
+    BPD_CASE(8) BPD_CASE(7) BPD_CASE(5) BPD_CASE(4) BPD_CASE(2)
+#undef BPD_CASE
+  }
+#define BPD_CASE(MT_, NT_) if (mt == MT_ && nt == NT_) { launch_ldsx<MT_, NT_, 64, ARGMAX>(p, e, keys, logits, groups, s); return; }
+  BPD_CASE(8, 4) BPD_CASE(8, 2) BPD_CASE(8, 1)
+  BPD_CASE(7, 4) BPD_CASE(7, 2) BPD_CASE(7, 1)
+  BPD_CASE(5, 4) BPD_CASE(5, 2) BPD_CASE(5, 1)
+  BPD_CASE(4, 4) BPD_CASE(4, 2) BPD_CASE(4, 1)
+  BPD_CASE(2, 4) BPD_CASE(2, 2) BPD_CASE(2, 1)
+#undef BPD_CASE
+}
+
+// Y = epilogue(X W).  bf16 mode: M <= 16 -> skinny kernel; otherwise the LDS-staged kernel
+// (K % 64 == 0) or the plain MFMA kernel.  fp32 mode: one thread per output.
 void gemm(bpd_ctx* ctx, const GemmP& p, const Epi& e, int groups = 1) {
-  if (ctx->cfg.dtype == BPD_BF16) {
-    DISPATCH_TILES(launch_gemm_bf16, p, e, groups, ctx->stream);
-  } else {
+  hipStream_t s = ctx->stream;
+  if (ctx->cfg.dtype != BPD_BF16) {
     dim3 grid((p.N + 127) / 128, p.M, groups);
-    hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(128), 0, ctx->stream, p, e);
+    hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(128), 0, s, p, e);
+    return;
+  }
+  if (skinny_ok(ctx, p)) {
+    LnP none{};
+    if (p.N / 16 >= 2048) launch_skinny<2, false, false>(p, e, none, nullptr, nullptr, groups, s);
+    else launch_skinny<1, false, false>(p, e, none, nullptr, nullptr, groups, s);
+  } else if (p.K % 64 == 0) {
+    dispatch_ldsx<false>(p, e, nullptr, nullptr, groups, s);
+  } else {
+    if (p.M > 64) launch_gemm_bf16<8, 1, 4>(p, e, groups, s);
+    else launch_gemm_bf16<4, 1, 4>(p, e, groups, s);
+  }
+}
+
+void layernorm(bpd_ctx* ctx, const float* x, LnW w, int M, void* ya, float* yf);
+
+// Y = epilogue(LayerNorm(x) W).  Block of <= 16 rows: LayerNorm is applied inside the skinny
+// kernel from the partial statistics the producer of x left in L.stats_ln.  Otherwise a
+// LayerNorm kernel (into `xn`, and `yf` in fp32 if given) followed by the GEMM.
+void gemm_ln(bpd_ctx* ctx, const float* x, LnW w, void* xn, float* yf, GemmP p, const Epi& e) {
+  if (stats_path(ctx, p.M) && p.K == ctx->cfg.d_model) {
+    LnP ln{x, w.g, w.b, ctx->lay.stats_ln, ctx->cfg.ln_eps};
+    if (p.N / 16 >= 2048) launch_skinny<2, true, false>(p, e, ln, nullptr, nullptr, 1, ctx->stream);
+    else launch_skinny<1, true, false>(p, e, ln, nullptr, nullptr, 1, ctx->stream);
+    return;
+  }
+  layernorm(ctx, x, w, p.M, xn, yf);
+  p.X = xn;
+  gemm(ctx, p, e);
+}
+
+// Vocabulary projection with fused arg-max (bf16 mode).
+void vocab_argmax(bpd_ctx* ctx, const GemmP& p, unsigned long long* keys, float* logits) {
+  hipStream_t s = ctx->stream;
+  Epi none{};
+  LnP noln{};
+  if (skinny_ok(ctx, p)) launch_skinny<2, false, true>(p, none, noln, keys, logits, 1, s);
+  else if (p.K % 64 == 0) dispatch_ldsx<true>(p, none, keys, logits, 1, s);
+  else {
+    const int ntiles = p.N / 16;
+    dim3 grid(ntiles, (p.M + 127) / 128, 1);
+    hipLaunchKernelGGL((vocab_argmax_bf16_kernel<8, 1, 4>), grid, dim3(256), 0, s, p, keys, logits);
   }
 }
 
@@ -280,35 +385,40 @@ void layernorm(bpd_ctx* ctx, const float* x, LnW w, int M, void* ya, float* yf) 
     hipLaunchKernelGGL(layernorm_kernel<float>, grid, dim3(256), 0, ctx->stream, x, w.g, w.b, M, d, ctx->cfg.ln_eps, (float*)ya, yf);
 }
 
-void attention(bpd_ctx* ctx, const float* Q, const void* Kc, const void* Vc, void* out, long kv_seq_stride,
+void attention(bpd_ctx* ctx, const float* Q, const void* Kc, const void* Vc, void* out, int cap,
                int B, int R, const int* limit, int causal) {
+  const long kv_seq_stride = (long)cap * ctx->cfg.d_model;
   const bpd_config& c = ctx->cfg;
   const int dh = c.d_model / c.n_heads;
   AttnP p{};
-  p.Q = Q; p.Kc = Kc; p.Vc = Vc; p.out = out; p.kv_seq_stride = kv_seq_stride; p.d = c.d_model; p.R = R;
+  p.Q = Q; p.Kc = Kc; p.Vc = Vc; p.out = out; p.kv_seq_stride = kv_seq_stride; p.cap = cap; p.d = c.d_model; p.R = R;
   p.limit = limit; p.causal = causal; p.scale = 1.0f / sqrtf((float)dh);
   dim3 grid(c.n_heads, B, (R + 15) / 16);
   if (c.dtype == BPD_BF16) {
     if (dh == 64) hipLaunchKernelGGL((attention_kernel<bf16_t, 64>), grid, dim3(256), 0, ctx->stream, p);
     else hipLaunchKernelGGL((attention_kernel<bf16_t, 16>), grid, dim3(256), 0, ctx->stream, p);
   } else {
-    if (dh == 64) hipLaunchKernelGGL((attention_kernel<float, 64>), grid, dim3(256), 0, ctx->stream, p);
-    else hipLaunchKernelGGL((attention_kernel<float, 16>), grid, dim3(256), 0, ctx->stream, p);
+    hipLaunchKernelGGL((attention_kernel<float, 16>), grid, dim3(256), 0, ctx->stream, p);
   }
 }
 
 void embed(bpd_ctx* ctx, const int* tok, int tok_ld, const int* base, int rows_per_seq, int M, const float* pos,
-           float* x, int zero_input) {
+           float* x, int zero_input, unsigned long long* keys = nullptr, int nkeys = 0) {
   const bpd_config& c = ctx->cfg;
   const long n = (long)M * c.d_model;
   dim3 grid((unsigned)((n + 255) / 256));
   const float scale = sqrtf((float)c.d_model);
+  if (stats_path(ctx, M) && x == ctx->lay.x) {
+    hipLaunchKernelGGL(embed_stats_kernel, dim3(c.d_model / 16), dim3(64), 0, ctx->stream, tok, tok_ld, base, rows_per_seq, M,
+                       c.d_model, (const bf16_t*)ctx->lay.emb, c.vocab, pos, scale, x, zero_input, ctx->lay.stats_ln, keys, nkeys);
+    return;
+  }
   if (c.dtype == BPD_BF16)
     hipLaunchKernelGGL(embed_kernel<true>, grid, dim3(256), 0, ctx->stream, tok, tok_ld, base, rows_per_seq, M, c.d_model,
-                       ctx->lay.emb, c.vocab, pos, scale, x, zero_input);
+                       ctx->lay.emb, c.vocab, pos, scale, x, zero_input, keys, nkeys);
   else
     hipLaunchKernelGGL(embed_kernel<false>, grid, dim3(256), 0, ctx->stream, tok, tok_ld, base, rows_per_seq, M, c.d_model,
-                       ctx->lay.emb, c.vocab, pos, scale, x, zero_input);
+                       ctx->lay.emb, c.vocab, pos, scale, x, zero_input, keys, nkeys);
 }
 
 void fill_i32(bpd_ctx* ctx, int* p, long n, int v) {
@@ -345,9 +455,17 @@ int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
   const int B = ctx->B, d = c.d_model, F = c.d_ff, M = B * R;
   const int slots = c.max_out_len + c.k_max + 1;
   const size_t as = act_size(c);
+  const long nk = (long)M * k;
+  const bool sp = stats_path(ctx, M);
+  // residual update x += ...; on the statistics path the kernel also leaves LayerNorm partial sums
+  auto residual = [&](const float* bias) {
+    Epi e = plain(bias, 0, L.x, d, L.x, d, nullptr, 0);
+    if (sp) e.stats_out = L.stats_ln;
+    return e;
+  };
   {
     PhaseTimer t(ctx, BPD_PHASE_LAYERS);
-    embed(ctx, L.P, c.k_max, L.L, R, M, L.pos_tgt, L.x, zero_input);
+    embed(ctx, L.P, c.k_max, L.L, R, M, L.pos_tgt, L.x, zero_input, L.keys, (int)nk);
     for (int l = 0; l < c.n_dec_layers; ++l) {
       DecL& w = L.dec[l];
       char* Kl = (char*)L.selfK + (size_t)l * c.max_batch * slots * d * as;
@@ -355,26 +473,24 @@ int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
       char* cK = (char*)L.crossK + (size_t)l * c.max_batch * c.max_src_len * d * as;
       char* cV = (char*)L.crossV + (size_t)l * c.max_batch * c.max_src_len * d * as;
       // self-attention sublayer: K/V of the block rows go straight into the cache at L_b + i'
-      layernorm(ctx, L.x, w.ln1, M, L.xn, nullptr);
-      gemm(ctx, gp(L.xn, d, w.wqkv, 3 * d, M, 3 * d, d), split(L.q, Kl, Vl, d, 0, R, slots, L.L));
-      attention(ctx, L.q, Kl, Vl, L.attn, (long)slots * d, B, R, L.L, 1);
-      gemm(ctx, gp(L.attn, d, w.wo, d, M, d, d), plain(nullptr, 0, L.x, d, L.x, d, nullptr, 0));
+      gemm_ln(ctx, L.x, w.ln1, L.xn, nullptr, gp(L.xn, d, w.wqkv, 3 * d, M, 3 * d, d), split(L.q, Kl, Vl, d, 0, R, slots, L.L));
+      attention(ctx, L.q, Kl, Vl, L.attn, slots, B, R, L.L, 1);
+      gemm(ctx, gp(L.attn, d, w.wo, d, M, d, d), residual(nullptr));
       // cross-attention sublayer over the encoder memory
-      layernorm(ctx, L.x, w.ln2, M, L.xn, nullptr);
-      gemm(ctx, gp(L.xn, d, w.cq, d, M, d, d), plain(nullptr, 0, nullptr, 0, L.q, d, nullptr, 0));
-      attention(ctx, L.q, cK, cV, L.attn, (long)c.max_src_len * d, B, R, L.src_len, 0);
-      gemm(ctx, gp(L.attn, d, w.co, d, M, d, d), plain(nullptr, 0, L.x, d, L.x, d, nullptr, 0));
+      gemm_ln(ctx, L.x, w.ln2, L.xn, nullptr, gp(L.xn, d, w.cq, d, M, d, d), plain(nullptr, 0, nullptr, 0, L.q, d, nullptr, 0));
+      attention(ctx, L.q, cK, cV, L.attn, c.max_src_len, B, R, L.src_len, 0);
+      gemm(ctx, gp(L.attn, d, w.co, d, M, d, d), residual(nullptr));
       // feed-forward sublayer
-      layernorm(ctx, L.x, w.ln3, M, L.xn, nullptr);
-      gemm(ctx, gp(L.xn, d, w.w1, F, M, F, d), plain(w.b1, 1, nullptr, 0, nullptr, 0, L.ffh, F));
-      gemm(ctx, gp(L.ffh, F, w.w2, d, M, d, F), plain(w.b2, 0, L.x, d, L.x, d, nullptr, 0));
+      gemm_ln(ctx, L.x, w.ln3, L.xn, nullptr, gp(L.xn, d, w.w1, F, M, F, d), plain(w.b1, 1, nullptr, 0, nullptr, 0, L.ffh, F));
+      gemm(ctx, gp(L.ffh, F, w.w2, d, M, d, F), residual(w.b2));
     }
-    layernorm(ctx, L.x, L.dec_lnf, M, L.hn, L.h);
   }
-  // the k residual FFN heads: hidden layers side by side, then one output layer per head
+  // the k residual FFN heads: final LayerNorm + hidden layers side by side (h kept in fp32
+  // for the residual), then one output layer per head
   {
     PhaseTimer t(ctx, BPD_PHASE_HEAD_HIDDEN);
-    gemm(ctx, gp(L.hn, d, L.hw1, c.k_max * F, M, k * F, d), plain(L.hb1, 1, nullptr, 0, nullptr, 0, L.H, k * F));
+    gemm_ln(ctx, L.x, L.dec_lnf, L.hn, L.h, gp(L.hn, d, L.hw1, c.k_max * F, M, k * F, d),
+            plain(L.hb1, 1, nullptr, 0, nullptr, 0, L.H, k * F));
   }
   {
     PhaseTimer t(ctx, BPD_PHASE_HEAD_OUT);
@@ -382,15 +498,15 @@ int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
     p.x_g = F; p.w_g = (long)F * d;
     Epi e = plain(L.hb2, 0, L.h, d, nullptr, 0, L.O, k * d);
     e.bias_g = d; e.r_g = 0; e.ya_g = d;
+    if (sp) {          // h = LayerNorm(x) is recomputed from x and the partial statistics
+      e.R = L.x; e.lnR_stats = L.stats_ln; e.lnR_g = L.dec_lnf.g; e.lnR_b = L.dec_lnf.b; e.lnR_K = d; e.lnR_eps = c.ln_eps;
+    }
     gemm(ctx, p, e, k);
   }
-  const long nk = (long)M * k;
-  hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)((nk + 255) / 256)), dim3(256), 0, ctx->stream, L.keys, nk, 0ull);
   {
     PhaseTimer t(ctx, BPD_PHASE_VOCAB);
     if (c.dtype == BPD_BF16) {
-      GemmP p = gp(L.O, d, L.emb, c.vocab, (int)nk, c.vocab, d);
-      DISPATCH_TILES(launch_vocab_bf16, p, L.keys, logits, ctx->stream);
+      vocab_argmax(ctx, gp(L.O, d, L.emb, c.vocab, (int)nk, c.vocab, d), L.keys, logits);
     } else {
       hipLaunchKernelGGL(vocab_argmax_f32_kernel, dim3((unsigned)nk), dim3(256), 0, ctx->stream, (const float*)L.O,
                          (const float*)L.emb, (int)nk, c.vocab, d, L.keys, logits);
@@ -405,7 +521,7 @@ StateP state_params(bpd_ctx* ctx) {
   StateP s{};
   s.L = L.L; s.j = L.j; s.finished = L.finished; s.max_len = L.max_len; s.P = L.P; s.A = L.A;
   s.accepted = L.accepted; s.out_ids = L.out_ids; s.stats = L.stats; s.imposed = nullptr; s.imposed_stride = 0;
-  s.step_counter = L.step_counter; s.kmax = ctx->cfg.k_max; s.max_out = ctx->cfg.max_out_len;
+  s.kmax = ctx->cfg.k_max; s.max_out = ctx->cfg.max_out_len;
   s.eos_id = ctx->cfg.eos_id; s.distance_eps = ctx->distance_eps; s.min_block = ctx->min_block;
   return s;
 }
@@ -418,12 +534,10 @@ int encoder(bpd_ctx* ctx) {
   embed(ctx, L.src_ids, S, nullptr, S, M, L.pos_src, L.xe, 0);
   for (int l = 0; l < c.n_enc_layers; ++l) {
     EncL& w = L.enc[l];
-    layernorm(ctx, L.xe, w.ln1, M, L.xen, nullptr);
-    gemm(ctx, gp(L.xen, d, w.wqkv, 3 * d, M, 3 * d, d), split(L.qe, L.ke, L.ve, d, 0, S, S, nullptr));
-    attention(ctx, L.qe, L.ke, L.ve, L.attne, (long)S * d, B, S, L.src_len, 0);
+    gemm_ln(ctx, L.xe, w.ln1, L.xen, nullptr, gp(L.xen, d, w.wqkv, 3 * d, M, 3 * d, d), split(L.qe, L.ke, L.ve, d, 0, S, S, nullptr));
+    attention(ctx, L.qe, L.ke, L.ve, L.attne, S, B, S, L.src_len, 0);
     gemm(ctx, gp(L.attne, d, w.wo, d, M, d, d), plain(nullptr, 0, L.xe, d, L.xe, d, nullptr, 0));
-    layernorm(ctx, L.xe, w.ln2, M, L.xen, nullptr);
-    gemm(ctx, gp(L.xen, d, w.w1, F, M, F, d), plain(w.b1, 1, nullptr, 0, nullptr, 0, L.ffhe, F));
+    gemm_ln(ctx, L.xe, w.ln2, L.xen, nullptr, gp(L.xen, d, w.w1, F, M, F, d), plain(w.b1, 1, nullptr, 0, nullptr, 0, L.ffhe, F));
     gemm(ctx, gp(L.ffhe, F, w.w2, d, M, d, F), plain(w.b2, 0, L.xe, d, L.xe, d, nullptr, 0));
   }
   layernorm(ctx, L.xe, L.enc_lnf, M, L.mem, nullptr);
@@ -598,7 +712,6 @@ int bpd_encode(bpd_ctx* ctx, const int32_t* src_ids, const int32_t* src_len, con
   fill_i32(ctx, L.finished, B, 0);
   fill_i32(ctx, L.accepted, B, 0);
   fill_i32(ctx, L.out_ids, (long)B * c.max_out_len, c.pad_id);
-  fill_i32(ctx, L.step_counter, 1, 0);
   fill_i32(ctx, (int*)L.stats, 64, 0);
   fill_i32(ctx, L.P, (long)B * c.k_max, 0);
   fill_i32(ctx, L.A, (long)B * c.k_max * c.k_max, 0);
@@ -612,7 +725,7 @@ int bpd_encode(bpd_ctx* ctx, const int32_t* src_ids, const int32_t* src_len, con
   return BPD_OK;
 }
 
-static int step_impl(bpd_ctx* ctx, int k, const int* imposed_dev, int imposed_stride) {
+static int step_impl(bpd_ctx* ctx, int k, const int* imposed_dev, int imposed_stride, int imposed_step, int* accepted_dev) {
   Layout& L = ctx->lay;
   PhaseTimer whole(ctx, BPD_PHASE_STEP);
   int rc = forward(ctx, k, k, 0, nullptr);
@@ -621,8 +734,7 @@ static int step_impl(bpd_ctx* ctx, int k, const int* imposed_dev, int imposed_st
     PhaseTimer t(ctx, BPD_PHASE_ACCEPT);
     StateP s = state_params(ctx);
     s.imposed = imposed_dev; s.imposed_stride = imposed_stride;
-    hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(64), 0, ctx->stream, s, L.keys, k, ctx->B, 1);
-    hipLaunchKernelGGL(bump_step_kernel, dim3(1), dim3(1), 0, ctx->stream, L.step_counter);
+    hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(64), 0, ctx->stream, s, L.keys, k, ctx->B, 1, imposed_step, accepted_dev);
   }
   LAUNCHCHK();
   ctx->steps++;
@@ -634,14 +746,20 @@ int bpd_step(bpd_ctx* ctx, int k, const int32_t* imposed_accept, int32_t* accept
   if (!ctx->encoded) return fail(ctx, BPD_E_STATE, "bpd_step: call bpd_encode first");
   if (k < 1 || k > ctx->cfg.k_max) return fail(ctx, BPD_E_ARG, "bpd_step: k outside 1..k_max");
   Layout& L = ctx->lay;
+  // device pointers are used in place by the accept kernel; host arrays go through a copy
   const int* imp = nullptr;
   if (imposed_accept) {
-    HIPCHK(hipMemcpyAsync(L.imposed1, imposed_accept, (size_t)ctx->B * 4, hipMemcpyDefault, ctx->stream));
-    imp = L.imposed1;
+    if (is_host_ptr(imposed_accept)) {
+      HIPCHK(hipMemcpyAsync(L.imposed1, imposed_accept, (size_t)ctx->B * 4, hipMemcpyHostToDevice, ctx->stream));
+      imp = L.imposed1;
+    } else {
+      imp = imposed_accept;
+    }
   }
-  int rc = step_impl(ctx, k, imp, 0);
+  const bool out_host = accepted_len && is_host_ptr(accepted_len);
+  int rc = step_impl(ctx, k, imp, 0, 0, out_host ? nullptr : accepted_len);
   if (rc) return rc;
-  if (accepted_len) HIPCHK(hipMemcpyAsync(accepted_len, L.accepted, (size_t)ctx->B * 4, hipMemcpyDefault, ctx->stream));
+  if (out_host) HIPCHK(hipMemcpyAsync(accepted_len, L.accepted, (size_t)ctx->B * 4, hipMemcpyDeviceToHost, ctx->stream));
   return BPD_OK;
 }
 
@@ -685,10 +803,10 @@ int bpd_decode(bpd_ctx* ctx, int k, const int32_t* schedule, int max_steps, int3
     const int rows = max_steps < ctx->cfg.max_out_len ? max_steps : ctx->cfg.max_out_len;
     if (rows > 0) HIPCHK(hipMemcpyAsync(L.sched, schedule, (size_t)rows * B * 4, hipMemcpyDefault, ctx->stream));
     if (max_steps > rows) max_steps = rows;
-    imp = L.sched - (long)ctx->steps * B;     // the kernel indexes by the global step counter
+    imp = L.sched;
   }
   for (int s = 0; s < max_steps; ++s) {
-    int rc = step_impl(ctx, k, imp, B);
+    int rc = step_impl(ctx, k, imp, B, s, nullptr);
     if (rc) return rc;
     if ((s & 3) == 3 || s + 1 == max_steps) {
       HIPCHK(hipMemcpyAsync(ctx->pinned, (int*)(L.stats + 2), 4, hipMemcpyDeviceToHost, ctx->stream));
@@ -733,7 +851,7 @@ int bpd_debug_step_logits(bpd_ctx* ctx, int k, float* logits) {
   if (k < 1 || k > ctx->cfg.k_max) return fail(ctx, BPD_E_ARG, "bpd_debug_step_logits: k outside 1..k_max");
   int rc = forward(ctx, k, k, 0, logits);
   if (rc) return rc;
-  hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(64), 0, ctx->stream, state_params(ctx), ctx->lay.keys, k, ctx->B, 0);
+  hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(64), 0, ctx->stream, state_params(ctx), ctx->lay.keys, k, ctx->B, 0, 0, nullptr);
   LAUNCHCHK();
   return BPD_OK;
 }

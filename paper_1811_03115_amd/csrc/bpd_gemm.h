@@ -1,0 +1,354 @@
+// Tuned bf16 MFMA GEMM kernels of libbpd (gfx950).  Included by bpd_kernels.h.
+//
+// Two regimes of the decoding step:
+//   * "skinny": the M = B*k block rows fit one 16-row MFMA tile (batch-1 decoding).  The step
+//     is then a chain of ~50 dependent small kernels whose cost is latency, not arithmetic:
+//     every global load a wave will need is issued in one batch at kernel entry (weights
+//     first, they do not depend on the previous kernel), LayerNorm is fused in as a prologue,
+//     and K is split over the 4 waves of a workgroup so that a matrix with only N/16 column
+//     tiles still spreads over N/16 CUs.
+//   * "ldsx": many rows (batched decoding, the k*k-row vocabulary projection).  Weights go
+//     straight from global memory into MFMA operand registers (the tiled layout makes each
+//     16x32 tile one coalesced 1 KiB load, and no two waves of a workgroup share a weight
+//     tile), activations are staged through LDS where all 4 waves reuse them.
+#pragma once
+
+template <int MT, int NT>
+__device__ __forceinline__ void store_tiles(const Epi& e, int g, const f32x4 (&acc)[MT][NT], int m0, int nt0,
+                                            int ntiles, int M, int lane) {
+#pragma unroll
+  for (int t = 0; t < MT; ++t) {
+    const int m = m0 + t * 16 + (lane & 15);
+    if (m >= M) continue;
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+      if (nt0 + u >= ntiles) continue;
+      const int n = (nt0 + u) * 16 + (lane >> 4) * 4;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) epi_store<bf16_t>(e, g, m, n + r, acc[t][u][r]);
+    }
+  }
+}
+
+// Row-wise arg-max over this wave's columns, merged into keys[] with a 64-bit atomic max.
+template <int MT, int NT>
+__device__ __forceinline__ void argmax_tiles(const f32x4 (&acc)[MT][NT], int m0, int nt0, int ntiles, int M, int N,
+                                             int lane, unsigned long long* keys, float* logits) {
+#pragma unroll
+  for (int t = 0; t < MT; ++t) {
+    const int m = m0 + t * 16 + (lane & 15);
+    unsigned long long best = 0ull;
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+      if (nt0 + u >= ntiles) continue;
+      const int n = (nt0 + u) * 16 + (lane >> 4) * 4;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float v = acc[t][u][r];
+        const unsigned long long key = argmax_key(v, (unsigned)(n + r));
+        best = key > best ? key : best;
+        if (logits && m < M) logits[(long)m * N + n + r] = v;
+      }
+    }
+    unsigned long long o = __shfl_xor(best, 16, 64); best = o > best ? o : best;
+    o = __shfl_xor(best, 32, 64); best = o > best ? o : best;
+    if (lane < 16 && m < M) atomicMax(&keys[m], best);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// LayerNorm statistics travel with the residual stream: every kernel that writes x (16-column
+// tile by tile) also writes, per tile and row, the partial sum and sum of squares of its 16
+// new values; a consumer adds the d/16 partials of a row in a fixed order.  This removes the
+// LayerNorm kernels and any cross-lane reduction over a whole row from the latency chain.
+//   stats[(tile * 16 + row) * 2 + {0,1}],  tile < K/16 <= 64, row < 16.
+__device__ __forceinline__ void row_stats(const float* stats, int K, float eps, int lane, float& mu, float& rstd) {
+  const int m = lane & 15, part = lane >> 4, slots = K >> 4;
+  float s = 0.f, q = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int t = part + 4 * i;
+    if (t < slots) {
+      const float2 v = ((const float2*)stats)[t * 16 + m];
+      s += v.x; q += v.y;
+    }
+  }
+  s += __shfl_xor(s, 16, 64); s += __shfl_xor(s, 32, 64);
+  q += __shfl_xor(q, 16, 64); q += __shfl_xor(q, 32, 64);
+  mu = s / K;
+  const float var = fmaxf(q / K - mu * mu, 0.f);
+  rstd = 1.0f / sqrtf(var + eps);
+}
+
+struct LnP {
+  const float* x;       // [M][K] fp32 residual stream (row stride K)
+  const float* g;       // [K]
+  const float* b;       // [K]
+  const float* stats;   // partial sums written by the producer of x
+  float eps;
+};
+
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) { return (unsigned)f2bf(lo) | ((unsigned)f2bf(hi) << 16); }
+
+// Skinny GEMM: M <= 16 rows.  Workgroup = WAVES waves sharing NT column tiles, K split WAVES
+// ways (wave w takes k-steps w, w+WAVES, ...; at most U per wave, so K <= 32*WAVES*U), partial
+// sums meet in LDS and wave 0 runs the epilogue.  A workgroup walks column-tile groups
+// blockIdx.x, blockIdx.x + gridDim.x, ... keeping its activation fragments in registers and
+// requesting the next tile's weights before the current tile is reduced (PERSIST; otherwise one
+// tile group per workgroup).
+//   XLN = false: X is bf16 [M][K] in global memory.
+//   XLN = true : X = LayerNorm(x) of the fp32 residual stream, normalised in registers from
+//                the producer's partial statistics.
+// Every global load of the first tile (weights, activations, statistics, bias and residual of
+// the epilogue) is issued before anything is waited for: one memory round trip per kernel.
+// Epilogue (mode 0) additionally supports: R = LayerNorm(R) via e.lnR_* (the heads' residual
+// is the normalised decoder output), and writing partial LayerNorm statistics of the result.
+template <int NT, bool XLN, bool ARGMAX, int WAVES, int U, bool PERSIST>
+__global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e, LnP ln, unsigned long long* keys,
+                                                                  float* logits) {
+  __shared__ f32x4 red[2][(WAVES - 1) * NT * 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = blockIdx.z;
+  const int ntiles = p.N >> 4, ksteps = p.K >> 5;
+  const int lr = lane & 15, lk = (lane >> 4) * 8;
+  const uint4* W = (const uint4*)((const bf16_t*)p.W + g * p.w_g) + lane;
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+  int nt0 = blockIdx.x * NT;
+  if (nt0 >= ntiles) return;
+
+  uint4 a_cur[U][NT], a_nxt[PERSIST ? U : 1][NT];
+#define BPD_LOAD_A(dst, tile0)                                                              \
+  _Pragma("unroll") for (int i = 0; i < U; ++i) {                                           \
+    const int ks_ = wave + WAVES * i;                                                       \
+    _Pragma("unroll") for (int u = 0; u < NT; ++u) {                                        \
+      int t_ = (tile0) + u; t_ = t_ < ntiles ? t_ : ntiles - 1;                             \
+      dst[i][u] = ks_ < ksteps ? W[((long)t_ * ksteps + ks_) * 64] : zero4;                 \
+    }                                                                                       \
+  }
+  BPD_LOAD_A(a_cur, nt0)                        // weights first: they do not depend on the producer kernel
+
+  const int mrow = lr < p.M ? lr : p.M - 1;
+  float4 r_pre[NT], bias_pre[NT];
+  const bool plain_epi = !ARGMAX && e.mode == 0;
+  if (plain_epi && wave == 0) {
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+      int t = nt0 + u; t = t < ntiles ? t : ntiles - 1;
+      const int n = t * 16 + (lane >> 4) * 4;
+      r_pre[u] = e.R ? *(const float4*)(e.R + g * e.r_g + (long)mrow * e.ldr + n) : make_float4(0, 0, 0, 0);
+      bias_pre[u] = e.bias ? *(const float4*)(e.bias + g * e.bias_g + n) : make_float4(0, 0, 0, 0);
+    }
+  }
+
+  // activation fragments, kept for all tiles of this workgroup
+  uint4 b[U];
+  if (XLN) {
+    float4 xv[U][2], gv[U][2], bv[U][2];
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      const int ks = wave + WAVES * i;
+      const int col = (ks < ksteps ? ks : 0) * 32 + lk;
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        xv[i][hh] = *(const float4*)(ln.x + (long)mrow * p.K + col + 4 * hh);
+        gv[i][hh] = *(const float4*)(ln.g + col + 4 * hh);
+        bv[i][hh] = *(const float4*)(ln.b + col + 4 * hh);
+      }
+    }
+    float mu, rstd;
+    row_stats(ln.stats, p.K, ln.eps, lane, mu, rstd);
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      float y[8];
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        y[4 * hh + 0] = (xv[i][hh].x - mu) * rstd * gv[i][hh].x + bv[i][hh].x;
+        y[4 * hh + 1] = (xv[i][hh].y - mu) * rstd * gv[i][hh].y + bv[i][hh].y;
+        y[4 * hh + 2] = (xv[i][hh].z - mu) * rstd * gv[i][hh].z + bv[i][hh].z;
+        y[4 * hh + 3] = (xv[i][hh].w - mu) * rstd * gv[i][hh].w + bv[i][hh].w;
+      }
+      b[i] = make_uint4(pack_bf16(y[0], y[1]), pack_bf16(y[2], y[3]), pack_bf16(y[4], y[5]), pack_bf16(y[6], y[7]));
+    }
+  } else {
+    const bf16_t* xg = (const bf16_t*)p.X + g * p.x_g + (long)mrow * p.ldx + lk;
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      const int ks = wave + WAVES * i;
+      b[i] = ks < ksteps ? *(const uint4*)(xg + ks * 32) : zero4;
+    }
+  }
+
+  int it = 0;
+  for (; nt0 < ntiles; nt0 += (PERSIST ? gridDim.x * NT : ntiles), ++it) {
+    f32x4 acc[1][NT];
+#pragma unroll
+    for (int u = 0; u < NT; ++u) acc[0][u] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int nt_next = nt0 + gridDim.x * NT;
+    if (PERSIST && nt_next < ntiles) { BPD_LOAD_A(a_nxt, nt_next) }
+#pragma unroll
+    for (int i = 0; i < U; ++i)
+#pragma unroll
+      for (int u = 0; u < NT; ++u)
+        acc[0][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_cur[i][u]),
+                                                            __builtin_bit_cast(bf16x8, b[i]), acc[0][u], 0, 0, 0);
+    if (PERSIST && nt_next < ntiles) {
+#pragma unroll
+      for (int i = 0; i < (PERSIST ? U : 1); ++i)
+#pragma unroll
+        for (int u = 0; u < NT; ++u) a_cur[i][u] = a_nxt[i][u];
+    }
+    // cross-wave reduction (double-buffered so that one barrier per tile suffices)
+    f32x4* rb = red[it & 1];
+    if (wave > 0) {
+#pragma unroll
+      for (int u = 0; u < NT; ++u) rb[((wave - 1) * NT + u) * 64 + lane] = acc[0][u];
+    }
+    __syncthreads();
+    if (wave != 0) continue;
+#pragma unroll
+    for (int w = 0; w < WAVES - 1; ++w)
+#pragma unroll
+      for (int u = 0; u < NT; ++u) acc[0][u] += rb[(w * NT + u) * 64 + lane];
+    if (ARGMAX) {
+      argmax_tiles<1, NT>(acc, 0, nt0, ntiles, p.M, p.N, lane, keys, logits);
+    } else if (e.mode != 0) {
+      store_tiles<1, NT>(e, g, acc, 0, nt0, ntiles, p.M, lane);
+    } else {
+      float mu = 0.f, rstd = 1.f;
+      if (e.lnR_stats) row_stats(e.lnR_stats, e.lnR_K, e.lnR_eps, lane, mu, rstd);
+#pragma unroll
+      for (int u = 0; u < NT; ++u) {
+        if (nt0 + u >= ntiles) continue;
+        const int n = (nt0 + u) * 16 + (lane >> 4) * 4;
+        float4 rv = r_pre[u], bs = bias_pre[u];
+        if (it > 0) {
+          rv = e.R ? *(const float4*)(e.R + g * e.r_g + (long)mrow * e.ldr + n) : make_float4(0, 0, 0, 0);
+          bs = e.bias ? *(const float4*)(e.bias + g * e.bias_g + n) : make_float4(0, 0, 0, 0);
+        }
+        if (e.lnR_stats) {
+          const float4 gg = *(const float4*)(e.lnR_g + n), bb = *(const float4*)(e.lnR_b + n);
+          rv.x = (rv.x - mu) * rstd * gg.x + bb.x; rv.y = (rv.y - mu) * rstd * gg.y + bb.y;
+          rv.z = (rv.z - mu) * rstd * gg.z + bb.z; rv.w = (rv.w - mu) * rstd * gg.w + bb.w;
+        }
+        float v[4] = {acc[0][u][0] + bs.x, acc[0][u][1] + bs.y, acc[0][u][2] + bs.z, acc[0][u][3] + bs.w};
+        if (e.relu) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) v[r] = fmaxf(v[r], 0.f);
+        }
+        v[0] += rv.x; v[1] += rv.y; v[2] += rv.z; v[3] += rv.w;
+        if (e.stats_out) {
+          float s = (v[0] + v[1]) + (v[2] + v[3]);
+          float q = (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
+          s += __shfl_xor(s, 16, 64); s += __shfl_xor(s, 32, 64);
+          q += __shfl_xor(q, 16, 64); q += __shfl_xor(q, 32, 64);
+          if (lane < 16) ((float2*)e.stats_out)[(nt0 + u) * 16 + lane] = make_float2(s, q);
+        }
+        if (lr < p.M) {
+          if (e.Yf) *(float4*)(e.Yf + g * e.yf_g + (long)lr * e.ldyf + n) = make_float4(v[0], v[1], v[2], v[3]);
+          if (e.Ya) *(uint2*)((bf16_t*)e.Ya + g * e.ya_g + (long)lr * e.ldya + n) =
+                        make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
+        }
+      }
+    }
+  }
+#undef BPD_LOAD_A
+}
+
+// ---------------------------------------------------------------------------------------
+// "ldsx" GEMM: BM = 16*MT rows x BN = 64*NT columns per workgroup, K walked in chunks of KC.
+// Wave w owns column tiles (4*blockIdx.x + w)*NT .. +NT and streams their weight tiles from
+// global memory one chunk ahead (KC/32 * NT fragments in flight per wave); the BM x KC
+// activation chunk is staged in LDS (double buffered, row stride KC+8 bf16 so that the 16-byte
+// operand reads of a wave spread evenly over the banks).  Requires K % KC == 0.
+// Dynamic LDS: 2 * BM * (KC + 8) * 2 bytes.
+template <int MT, int NT, int KC, bool ARGMAX>
+__global__ __launch_bounds__(256) void gemm_ldsx_kernel(GemmP p, Epi e, unsigned long long* keys, float* logits) {
+  constexpr int BM = 16 * MT, LD = KC + 8, KS = KC / 32, SEG = KC / 8;
+  constexpr int XI = (BM * SEG + 255) / 256;       // 16-byte segments per thread per chunk
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t* xs0 = (bf16_t*)smem_raw;
+  bf16_t* xs1 = xs0 + BM * LD;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = blockIdx.z;
+  const int ntiles = p.N >> 4, ksteps = p.K >> 5, nchunks = p.K / KC;
+  const int m0 = blockIdx.y * BM;
+  const int nt0 = (blockIdx.x * 4 + wave) * NT;
+  const int lr = lane & 15, lk = (lane >> 4) * 8;
+  const bf16_t* X = (const bf16_t*)p.X + g * p.x_g;
+  const bf16_t* W = (const bf16_t*)p.W + g * p.w_g;
+  const uint4* wt[NT];
+#pragma unroll
+  for (int u = 0; u < NT; ++u) {
+    int tile = nt0 + u;
+    tile = tile < ntiles ? tile : ntiles - 1;
+    wt[u] = (const uint4*)W + (long)tile * ksteps * 64 + lane;
+  }
+  // global source (element offset from X) of this thread's 16-byte segments of a chunk; the LDS
+  // destination is recomputed from the index where needed (keeps the register count down)
+  int xoff[XI];
+#pragma unroll
+  for (int i = 0; i < XI; ++i) {
+    const int idx = tid + 256 * i;
+    int row = m0 + idx / SEG;
+    row = row < p.M ? row : p.M - 1;
+    xoff[i] = row * p.ldx + (idx % SEG) * 8;
+  }
+#define BPD_XDST(i) (((tid + 256 * (i)) / SEG) * LD + ((tid + 256 * (i)) % SEG) * 8)
+#define BPD_XOK(i) (XI * 256 == BM * SEG || tid + 256 * (i) < BM * SEG)
+  uint4 xr[XI], a_cur[KS][NT], a_nxt[KS][NT];
+  f32x4 acc[MT][NT];
+#pragma unroll
+  for (int t = 0; t < MT; ++t)
+#pragma unroll
+    for (int u = 0; u < NT; ++u) acc[t][u] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int s = 0; s < KS; ++s)
+#pragma unroll
+    for (int u = 0; u < NT; ++u) a_cur[s][u] = wt[u][(long)s * 64];
+#pragma unroll
+  for (int i = 0; i < XI; ++i) xr[i] = *(const uint4*)(X + xoff[i]);
+#pragma unroll
+  for (int i = 0; i < XI; ++i)
+    if (BPD_XOK(i)) *(uint4*)(xs0 + BPD_XDST(i)) = xr[i];
+  __syncthreads();
+  for (int c = 0; c < nchunks; ++c) {
+    const bool more = c + 1 < nchunks;
+    if (more) {
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+#pragma unroll
+        for (int u = 0; u < NT; ++u) a_nxt[s][u] = wt[u][(long)((c + 1) * KS + s) * 64];
+#pragma unroll
+      for (int i = 0; i < XI; ++i) xr[i] = *(const uint4*)(X + xoff[i] + (c + 1) * KC);
+    }
+    const bf16_t* xb = (c & 1) ? xs1 : xs0;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      uint4 b[MT];
+#pragma unroll
+      for (int t = 0; t < MT; ++t) b[t] = *(const uint4*)(xb + (t * 16 + lr) * LD + s * 32 + lk);
+#pragma unroll
+      for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int u = 0; u < NT; ++u)
+          acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_cur[s][u]),
+                                                              __builtin_bit_cast(bf16x8, b[t]), acc[t][u], 0, 0, 0);
+    }
+    if (more) {
+      bf16_t* xn = (c & 1) ? xs0 : xs1;
+#pragma unroll
+      for (int i = 0; i < XI; ++i)
+        if (BPD_XOK(i)) *(uint4*)(xn + BPD_XDST(i)) = xr[i];
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+#pragma unroll
+        for (int u = 0; u < NT; ++u) a_cur[s][u] = a_nxt[s][u];
+    }
+    __syncthreads();
+  }
+#undef BPD_XDST
+#undef BPD_XOK
+  if (nt0 >= ntiles) return;
+  if (ARGMAX) argmax_tiles<MT, NT>(acc, m0, nt0, ntiles, p.M, p.N, lane, keys, logits);
+  else store_tiles<MT, NT>(e, g, acc, m0, nt0, ntiles, p.M, lane);
+}

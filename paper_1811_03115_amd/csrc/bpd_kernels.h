@@ -56,6 +56,10 @@ struct Epi {
   float* Yf;       int ldyf;
   void* Ya;        int ldya;
   long bias_g, r_g, yf_g, ya_g;      // per-group (blockIdx.z) element offsets
+  // skinny kernels only: the residual operand is LayerNorm(R) computed from partial statistics,
+  // and/or partial LayerNorm statistics of the result are written (see bpd_gemm.h)
+  const float* lnR_stats; const float* lnR_g; const float* lnR_b; int lnR_K; float lnR_eps;
+  float* stats_out;
   // mode 1
   float* Qf; void* Ka; void* Va;
   int dsplit, chunk0, rows_per_seq, cap;
@@ -241,6 +245,8 @@ __global__ __launch_bounds__(256) void vocab_argmax_bf16_kernel(GemmP p, unsigne
   }
 }
 
+#include "bpd_gemm.h"
+
 // ---------------------------------------------------------------------------------------
 // fp32 mode (small configurations): one thread per output element.
 __global__ void gemm_f32_kernel(GemmP p, Epi e) {
@@ -312,8 +318,9 @@ __global__ void convert_vector_kernel(const SRC* src, float* dst, long n) {
 template <bool BF16>
 __global__ void embed_kernel(const int* tok, int tok_ld, const int* base, int rows_per_seq, int M,
                              int d, const void* E, int V, const float* pos, float scale, float* x,
-                             int zero_input) {
+                             int zero_input, unsigned long long* keys, int nkeys) {
   const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < nkeys) keys[idx] = 0ull;          // argmax keys of this invocation start at "nothing"
   if (idx >= (long)M * d) return;
   const int row = (int)(idx / d), c = (int)(idx % d);
   const int b = row / rows_per_seq, i = row % rows_per_seq;
@@ -334,6 +341,39 @@ __global__ void embed_kernel(const int* tok, int tok_ld, const int* base, int ro
     v += scale * ev;
   }
   x[idx] = v;
+}
+
+// Embedding for a block of <= 16 rows (bf16 mode): one wavefront per 16-column tile, lane =
+// (row = lane % 16, 4 columns), so that the tile's partial LayerNorm statistics (sum, sum of
+// squares per row) are written along with x, in the layout row_stats() reads.
+__global__ __launch_bounds__(64) void embed_stats_kernel(const int* tok, int tok_ld, const int* base, int rows_per_seq,
+                                                         int M, int d, const bf16_t* E, int V, const float* pos,
+                                                         float scale, float* x, int zero_input, float* stats,
+                                                         unsigned long long* keys, int nkeys) {
+  const int tile = blockIdx.x, lane = threadIdx.x;
+  for (int i = tile * 64 + lane; i < nkeys; i += gridDim.x * 64) keys[i] = 0ull;
+  const int row = lane & 15, c0 = tile * 16 + (lane >> 4) * 4;
+  const int r = row < M ? row : M - 1;
+  const int b = r / rows_per_seq, i = r % rows_per_seq;
+  const int position = (base ? base[b] : 0) + i;
+  const float4 pv = *(const float4*)(pos + (long)position * d + c0);
+  float v[4] = {pv.x, pv.y, pv.z, pv.w};
+  if (!zero_input) {
+    int t = tok[b * tok_ld + i];
+    t = t < 0 ? 0 : (t >= V ? V - 1 : t);
+    const int ksteps = d >> 5;
+    const long tl = (long)(t >> 4) * ksteps + (c0 >> 5);
+    const int ln = 16 * ((c0 & 31) >> 3) + (t & 15);
+    const uint2 raw = *(const uint2*)(E + (tl * 64 + ln) * 8 + (c0 & 7));
+    v[0] += scale * __uint_as_float(raw.x << 16); v[1] += scale * __uint_as_float(raw.x & 0xFFFF0000u);
+    v[2] += scale * __uint_as_float(raw.y << 16); v[3] += scale * __uint_as_float(raw.y & 0xFFFF0000u);
+  }
+  float s = (v[0] + v[1]) + (v[2] + v[3]);
+  float q = (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
+  s += __shfl_xor(s, 16, 64); s += __shfl_xor(s, 32, 64);
+  q += __shfl_xor(q, 16, 64); q += __shfl_xor(q, 32, 64);
+  if (lane < 16) ((float2*)stats)[tile * 16 + lane] = make_float2(s, q);
+  if (row < M) *(float4*)(x + (long)row * d + c0) = make_float4(v[0], v[1], v[2], v[3]);
 }
 
 // LayerNorm over the last axis, one wavefront per row (biased variance, two passes).
@@ -367,6 +407,13 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float* x, const fl
 //   Kc,Vc act, sequence b at Kc + b*kv_seq_stride, key s at + s*d, head h at + h*DH
 template <typename ACT, int DH> struct RowLoader;
 template <int DH> struct RowLoader<float, DH> {
+  static __device__ __forceinline__ void unpack(const uint4* raw, float* out) {
+#pragma unroll
+    for (int x = 0; x < DH / 4; ++x) {
+      out[4 * x] = __uint_as_float(raw[x].x); out[4 * x + 1] = __uint_as_float(raw[x].y);
+      out[4 * x + 2] = __uint_as_float(raw[x].z); out[4 * x + 3] = __uint_as_float(raw[x].w);
+    }
+  }
   static __device__ __forceinline__ void load(const float* p, float* out) {
 #pragma unroll
     for (int x = 0; x < DH; x += 4) {
@@ -376,6 +423,17 @@ template <int DH> struct RowLoader<float, DH> {
   }
 };
 template <int DH> struct RowLoader<bf16_t, DH> {
+  static __device__ __forceinline__ void unpack(const uint4* raw, float* out) {
+#pragma unroll
+    for (int x = 0; x < DH / 8; ++x) {
+      const unsigned w[4] = {raw[x].x, raw[x].y, raw[x].z, raw[x].w};
+#pragma unroll
+      for (int y = 0; y < 4; ++y) {
+        out[8 * x + 2 * y] = __uint_as_float(w[y] << 16);
+        out[8 * x + 2 * y + 1] = __uint_as_float(w[y] & 0xFFFF0000u);
+      }
+    }
+  }
   static __device__ __forceinline__ void load(const bf16_t* p, float* out) {
 #pragma unroll
     for (int x = 0; x < DH; x += 8) {
@@ -395,6 +453,7 @@ struct AttnP {
   const void* Kc; const void* Vc;
   void* out;
   long kv_seq_stride;
+  int cap;                // rows per sequence in the K/V buffer (loads are clamped to it)
   int d, R;
   const int* limit;       // [B]: base (causal) or len (non-causal)
   int causal;
@@ -403,87 +462,127 @@ struct AttnP {
 
 template <typename ACT, int DH>
 __global__ __launch_bounds__(256) void attention_kernel(AttnP p) {
-  constexpr int RT = 16, CH = 256, G = 256 / DH;
-  __shared__ float q_s[RT][DH];
-  __shared__ float sc[RT][CH];
-  __shared__ float red[G][RT][DH];
+  constexpr int RT = 16, CH = 256, G = 256 / DH, KPG = CH / G, SLD = CH + 4;
+  __shared__ __attribute__((aligned(16))) float q_s[RT][DH];
+  __shared__ __attribute__((aligned(16))) float sc[RT][SLD];
+  __shared__ __attribute__((aligned(16))) ACT vs[CH][DH];
   __shared__ float m_s[RT], l_s[RT], alpha_s[RT];
   const int h = blockIdx.x, b = blockIdx.y, r0 = blockIdx.z * RT;
   const int nrows = min(RT, p.R - r0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int lim = p.limit[b];
   const ACT* Kb = (const ACT*)p.Kc + b * p.kv_seq_stride + h * DH;
   const ACT* Vb = (const ACT*)p.Vc + b * p.kv_seq_stride + h * DH;
+  // first chunk's K and V rows are requested before anything else: one memory round trip
+  constexpr int VW = DH * sizeof(ACT) / 16;               // 16-byte words per row
+  uint4 kraw[VW], vraw[VW];
+  {
+    const int key = tid < p.cap ? tid : p.cap - 1;         // independent of the length: no second round trip
+    const uint4* kp = (const uint4*)(Kb + (long)key * p.d);
+    const uint4* vp = (const uint4*)(Vb + (long)key * p.d);
+#pragma unroll
+    for (int x = 0; x < VW; ++x) { kraw[x] = kp[x]; vraw[x] = vp[x]; }
+  }
   for (int idx = tid; idx < RT * DH; idx += 256) {
     const int i = idx / DH, c = idx % DH;
     q_s[i][c] = i < nrows ? p.Q[((long)b * p.R + r0 + i) * p.d + h * DH + c] * p.scale : 0.f;
   }
+  int lim = p.limit[b];
+  lim = lim < 0 ? 0 : lim;
+  int nkeys = p.causal ? lim + r0 + nrows : lim;   // keys any row of the tile can see
+  nkeys = nkeys < p.cap ? nkeys : p.cap;
   if (tid < RT) { m_s[tid] = -INFINITY; l_s[tid] = 0.f; alpha_s[tid] = 1.f; }
-  const int nkeys = p.causal ? lim + r0 + nrows : lim;   // keys any row of the tile can see
   float acc[RT];
 #pragma unroll
   for (int i = 0; i < RT; ++i) acc[i] = 0.f;
   const int g = tid / DH, c = tid % DH;
   __syncthreads();
   for (int c0 = 0; c0 < nkeys; c0 += CH) {
-    // scores of this chunk: one key per thread
     const int key = c0 + tid;
-    if (key < nkeys) {
+    if (c0 > 0) {
+      const int kk = key < nkeys ? key : 0;
+      const uint4* kp = (const uint4*)(Kb + (long)kk * p.d);
+      const uint4* vp = (const uint4*)(Vb + (long)kk * p.d);
+#pragma unroll
+      for (int x = 0; x < VW; ++x) { kraw[x] = kp[x]; vraw[x] = vp[x]; }
+    }
+    // scores of this chunk: one key per thread
+    {
       float kr[DH];
-      RowLoader<ACT, DH>::load(Kb + (long)key * p.d, kr);
+      RowLoader<ACT, DH>::unpack(kraw, kr);
       for (int i = 0; i < nrows; ++i) {
         float s = 0.f;
 #pragma unroll
-        for (int x = 0; x < DH; ++x) s = fmaf(q_s[i][x], kr[x], s);
+        for (int x = 0; x < DH; x += 4) {
+          const float4 qv = *(const float4*)&q_s[i][x];
+          s = fmaf(qv.x, kr[x], s); s = fmaf(qv.y, kr[x + 1], s);
+          s = fmaf(qv.z, kr[x + 2], s); s = fmaf(qv.w, kr[x + 3], s);
+        }
         const int nvis = p.causal ? lim + r0 + i + 1 : lim;
         sc[i][tid] = key < nvis ? s : -INFINITY;
       }
-    } else {
-      for (int i = 0; i < nrows; ++i) sc[i][tid] = -INFINITY;
+      const bool live = key < nkeys;
+#pragma unroll
+      for (int x = 0; x < VW; ++x) ((uint4*)&vs[tid][0])[x] = live ? vraw[x] : make_uint4(0, 0, 0, 0);
     }
     __syncthreads();
-    // running max / sum per row; wave w owns rows w, w+4, ...
-    for (int i = wave; i < nrows; i += 4) {
-      float v[4], mx = -INFINITY;
+    // running max / sum: 16 lanes per row, 4 rows per wave at once
+    {
+      const int i = wave * 4 + (lane >> 4), j0 = lane & 15;
+      if (i < nrows) {
+        float v[16], mx = -INFINITY;
 #pragma unroll
-      for (int x = 0; x < 4; ++x) { v[x] = sc[i][lane + 64 * x]; mx = fmaxf(mx, v[x]); }
-      mx = wave_max(mx);
-      const float m_old = m_s[i];
-      const float m_new = fmaxf(m_old, mx);
-      float sum = 0.f;
+        for (int x = 0; x < 16; ++x) { v[x] = sc[i][j0 + 16 * x]; mx = fmaxf(mx, v[x]); }
 #pragma unroll
-      for (int x = 0; x < 4; ++x) {
-        const float pv = (m_new == -INFINITY) ? 0.f : __expf(v[x] - m_new);
-        sc[i][lane + 64 * x] = pv;
-        sum += pv;
-      }
-      sum = wave_sum(sum);
-      if (lane == 0) {
-        const float a = (m_new == -INFINITY) ? 1.f : __expf(m_old - m_new);
-        alpha_s[i] = a;
-        l_s[i] = l_s[i] * a + sum;
-        m_s[i] = m_new;
+        for (int o = 8; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+        const float m_old = m_s[i];
+        const float m_new = fmaxf(m_old, mx);
+        float sum = 0.f;
+#pragma unroll
+        for (int x = 0; x < 16; ++x) {
+          const float pv = (m_new == -INFINITY) ? 0.f : __expf(v[x] - m_new);
+          sc[i][j0 + 16 * x] = pv;
+          sum += pv;
+        }
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+        if (j0 == 0) {
+          const float a = (m_new == -INFINITY) ? 1.f : __expf(m_old - m_new);
+          alpha_s[i] = a;
+          l_s[i] = l_s[i] * a + sum;
+          m_s[i] = m_new;
+        }
+      } else if (i < RT) {
+#pragma unroll
+        for (int x = 0; x < 16; ++x) sc[i][j0 + 16 * x] = 0.f;      // unused rows contribute nothing
       }
     }
     __syncthreads();
-    // weighted values: thread (g, c) walks keys g, g+G, ... of the chunk for feature c
+    // weighted values: thread (g, c) takes keys g*KPG .. of the chunk for feature c
 #pragma unroll
     for (int i = 0; i < RT; ++i) acc[i] *= alpha_s[i];
     const int kend = min(CH, nkeys - c0);
-    for (int kk = g; kk < kend; kk += G) {
-      const float v = to_f<ACT>(Vb[(long)(c0 + kk) * p.d + c]);
+    for (int kk = g * KPG; kk < min((g + 1) * KPG, kend); kk += 4) {
+      float vv[4];
 #pragma unroll
-      for (int i = 0; i < RT; ++i) acc[i] = fmaf(sc[i][kk], v, acc[i]);
+      for (int y = 0; y < 4; ++y) vv[y] = to_f<ACT>(vs[kk + y][c]);
+#pragma unroll
+      for (int i = 0; i < RT; ++i) {
+        const float4 pv = *(const float4*)&sc[i][kk];
+        acc[i] = fmaf(pv.x, vv[0], acc[i]); acc[i] = fmaf(pv.y, vv[1], acc[i]);
+        acc[i] = fmaf(pv.z, vv[2], acc[i]); acc[i] = fmaf(pv.w, vv[3], acc[i]);
+      }
     }
     __syncthreads();
   }
+  // sum over the G key groups (reusing the score buffer), normalise, write
+  float* red = &sc[0][0];                     // needs G*RT*DH = 4096 floats <= RT*SLD
 #pragma unroll
-  for (int i = 0; i < RT; ++i) red[g][i][c] = acc[i];
+  for (int i = 0; i < RT; ++i) red[(g * RT + i) * DH + c] = acc[i];
   __syncthreads();
   for (int idx = tid; idx < nrows * DH; idx += 256) {
     const int i = idx / DH, cc = idx % DH;
     float s = 0.f;
-    for (int gg = 0; gg < G; ++gg) s += red[gg][i][cc];
+    for (int gg = 0; gg < G; ++gg) s += red[(gg * RT + i) * DH + cc];
     ((ACT*)p.out)[((long)b * p.R + r0 + i) * p.d + h * DH + cc] = from_f<ACT>(s / l_s[i]);
   }
 }
@@ -502,7 +601,6 @@ struct StateP {
   long long* stats;  // [0] seq_steps [1] accepted_total [2] finished [3..19] hist[0..16] [20] live steps
   const int* imposed;  // k-hat to impose: imposed[step * imposed_stride + b], or null
   int imposed_stride;  // B for a whole schedule, 0 for a single step's vector
-  int* step_counter;
   int kmax, max_out, eos_id;
   int distance_eps, min_block;
 };
@@ -537,7 +635,7 @@ __global__ void prime_kernel(StateP s, const unsigned long long* keys, int B) {
 //   the cache rows of the accepted tokens (rejected rows are simply overwritten next step);
 //   P <- row k-hat of the table.
 __global__ __launch_bounds__(64) void accept_kernel(StateP s, const unsigned long long* keys, int k, int B,
-                                                    int commit) {
+                                                    int commit, int step, int* accepted_out) {
   const int b = blockIdx.x, lane = threadIdx.x;
   if (b >= B) return;
   for (int e = lane; e < k * k; e += 64) {
@@ -545,9 +643,8 @@ __global__ __launch_bounds__(64) void accept_kernel(StateP s, const unsigned lon
     s.A[(b * s.kmax + ip) * s.kmax + i] = key_index(keys[(long)b * k * k + e]);
   }
   if (!commit) return;
-  const int step = *s.step_counter;
   if (s.finished[b]) {
-    if (lane == 0) s.accepted[b] = 0;
+    if (lane == 0) { s.accepted[b] = 0; if (accepted_out) accepted_out[b] = 0; }
     return;
   }
   const int myP = lane < k ? s.P[b * s.kmax + lane] : -1;
@@ -582,6 +679,7 @@ __global__ __launch_bounds__(64) void accept_kernel(StateP s, const unsigned lon
     s.L[b] = s.L[b] + khat;
     s.finished[b] = fin;
     s.accepted[b] = khat;
+    if (accepted_out) accepted_out[b] = khat;
     atomicAdd((unsigned long long*)&s.stats[0], 1ull);
     atomicAdd((unsigned long long*)&s.stats[1], (unsigned long long)khat);
     if (fin) atomicAdd((unsigned long long*)&s.stats[2], 1ull);
@@ -590,4 +688,3 @@ __global__ __launch_bounds__(64) void accept_kernel(StateP s, const unsigned lon
   }
 }
 
-__global__ void bump_step_kernel(int* step_counter) { *step_counter += 1; }
