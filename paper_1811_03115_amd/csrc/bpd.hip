@@ -40,7 +40,7 @@ struct Layout {
   // caches
   void *selfK, *selfV, *crossK, *crossV;        // [n_dec][B][slots|max_src][d]
   // decoder activations (M = max_batch * k_max rows)
-  float *x, *q, *h, *stats_ln; void *xn, *attn, *ffh, *hn, *H, *O;
+  float *x, *q, *h, *stats_ln, *zeros; size_t n_zeros; void *xn, *attn, *ffh, *hn, *H, *O;
   unsigned long long* keys;
   // encoder activations (max_batch * max_src rows)
   float *xe, *qe; void *xen, *ke, *ve, *attne, *ffhe, *mem;
@@ -96,6 +96,8 @@ size_t build_layout(const bpd_config& c, char* base, Layout& L) {
   L.crossK = a.take(nd * B * S * d * as);    L.crossV = a.take(nd * B * S * d * as);
   const size_t M = B * k;
   L.x = vec(M * d); L.q = vec(M * d); L.h = vec(M * d); L.stats_ln = vec(64 * 16 * 2);
+  L.n_zeros = k * F; if (V > L.n_zeros) L.n_zeros = V; if (3 * d > L.n_zeros) L.n_zeros = 3 * d;
+  L.zeros = vec(L.n_zeros);
   L.xn = a.take(M * d * as); L.attn = a.take(M * d * as); L.ffh = a.take(M * F * as);
   L.hn = a.take(M * d * as); L.H = a.take(M * k * F * as); L.O = a.take(M * k * d * as);
   L.keys = (unsigned long long*)a.take(M * k * 8);
@@ -228,23 +230,38 @@ void launch_gemm_bf16(const GemmP& p, const Epi& e, int groups, hipStream_t s) {
 }
 
 // ---- skinny path: M <= 16 -------------------------------------------------------------
-template <int NT, bool XLN, bool ARGMAX>
-void launch_skinny(const GemmP& p, const Epi& e, const LnP& ln, unsigned long long* keys, float* logits, int groups,
-                   hipStream_t s) {
+template <int MT, int NT, bool XLN, bool ARGMAX, int WAVES, int U, int DEPTH>
+void launch_skinny_cfg(const bpd_ctx* ctx, const GemmP& p, const Epi& e_in, const LnP& ln, unsigned long long* keys,
+                       float* logits, int groups, int cap = 512) {
+  hipStream_t s = ctx->stream;
+  Epi e = e_in;                                 // the kernel loads bias and residual unconditionally
+  if (!e.bias) { e.bias = ctx->lay.zeros; e.bias_g = 0; }
+  if (!e.R) { e.R = ctx->lay.zeros; e.ldr = 0; e.r_g = 0; }
   const int ntiles = p.N / 16;
   const int ngroups = (ntiles + NT - 1) / NT;
-  const int gx = ngroups > 512 ? 512 : ngroups;  // beyond 512 workgroups each one walks several column tiles
+  const int gx = ngroups > cap ? cap : ngroups;  // beyond `cap` each workgroup walks several column-tile groups
   dim3 grid(gx, 1, groups);
-  // K split over the waves of a workgroup so that each wave holds all its k-steps in registers
-#define BPD_SK(W_, U_, P_) hipLaunchKernelGGL((skinny_gemm_kernel<NT, (W_ == 8 && U_ == 4) ? XLN : false, ARGMAX, W_, U_, P_>), grid, dim3(64 * W_), 0, s, p, e, ln, keys, logits)
-  if (XLN) {                                    // K <= 1024
-    if (ngroups > gx) BPD_SK(8, 4, true); else BPD_SK(8, 4, false);
-  } else if (p.K <= 1024) {
-    if (ngroups > gx) BPD_SK(4, 8, true); else BPD_SK(4, 8, false);
-  } else {                                      // K <= 4096
-    if (ngroups > gx) BPD_SK(8, 16, true); else BPD_SK(8, 16, false);
+  const size_t lds = (size_t)2 * WAVES * MT * NT * 1024;
+  if (ngroups > gx) {
+    auto k = skinny_gemm_kernel<MT, NT, XLN, ARGMAX, WAVES, U, DEPTH>;
+    static bool attr = false;
+    if (!attr) { (void)hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); attr = true; }
+    hipLaunchKernelGGL(k, grid, dim3(64 * WAVES), lds, s, p, e, ln, keys, logits);
+  } else {
+    auto k = skinny_gemm_kernel<MT, NT, XLN, ARGMAX, WAVES, U, 0>;
+    static bool attr = false;
+    if (!attr) { (void)hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); attr = true; }
+    hipLaunchKernelGGL(k, grid, dim3(64 * WAVES), lds, s, p, e, ln, keys, logits);
   }
-#undef BPD_SK
+}
+
+// One 16-row tile (M <= 16): K split over the waves so that each wave holds all its k-steps.
+template <int NT, bool XLN, bool ARGMAX>
+void launch_skinny(const bpd_ctx* ctx, const GemmP& p, const Epi& e, const LnP& ln, unsigned long long* keys, float* logits,
+                   int groups) {
+  if (XLN) launch_skinny_cfg<1, NT, XLN, ARGMAX, 8, 4, 2>(ctx, p, e, ln, keys, logits, groups);            // K <= 1024
+  else if (p.K <= 1024) launch_skinny_cfg<1, NT, false, ARGMAX, 4, 8, 2>(ctx, p, e, ln, keys, logits, groups);
+  else launch_skinny_cfg<1, NT, false, ARGMAX, 8, 16, 1>(ctx, p, e, ln, keys, logits, groups);             // K <= 4096
 }
 
 bool skinny_ok(const bpd_ctx* ctx, const GemmP& p) { return ctx->cfg.dtype == BPD_BF16 && p.M <= 16 && p.K <= 4096; }
@@ -318,8 +335,8 @@ void gemm(bpd_ctx* ctx, const GemmP& p, const Epi& e, int groups = 1) {
   }
   if (skinny_ok(ctx, p)) {
     LnP none{};
-    if (p.N / 16 >= 2048) launch_skinny<2, false, false>(p, e, none, nullptr, nullptr, groups, s);
-    else launch_skinny<1, false, false>(p, e, none, nullptr, nullptr, groups, s);
+    if (p.N / 16 >= 2048) launch_skinny<2, false, false>(ctx, p, e, none, nullptr, nullptr, groups);
+    else launch_skinny<1, false, false>(ctx, p, e, none, nullptr, nullptr, groups);
   } else if (p.K % 64 == 0) {
     dispatch_ldsx<false>(p, e, nullptr, nullptr, groups, s);
   } else {
@@ -336,8 +353,8 @@ void layernorm(bpd_ctx* ctx, const float* x, LnW w, int M, void* ya, float* yf);
 void gemm_ln(bpd_ctx* ctx, const float* x, LnW w, void* xn, float* yf, GemmP p, const Epi& e) {
   if (stats_path(ctx, p.M) && p.K == ctx->cfg.d_model) {
     LnP ln{x, w.g, w.b, ctx->lay.stats_ln, ctx->cfg.ln_eps};
-    if (p.N / 16 >= 2048) launch_skinny<2, true, false>(p, e, ln, nullptr, nullptr, 1, ctx->stream);
-    else launch_skinny<1, true, false>(p, e, ln, nullptr, nullptr, 1, ctx->stream);
+    if (p.N / 16 >= 2048) launch_skinny<2, true, false>(ctx, p, e, ln, nullptr, nullptr, 1);
+    else launch_skinny<1, true, false>(ctx, p, e, ln, nullptr, nullptr, 1);
     return;
   }
   layernorm(ctx, x, w, p.M, xn, yf);
@@ -350,7 +367,9 @@ void vocab_argmax(bpd_ctx* ctx, const GemmP& p, unsigned long long* keys, float*
   hipStream_t s = ctx->stream;
   Epi none{};
   LnP noln{};
-  if (skinny_ok(ctx, p)) launch_skinny<2, false, true>(p, none, noln, keys, logits, 1, s);
+  if (skinny_ok(ctx, p)) launch_skinny<2, false, true>(ctx, p, none, noln, keys, logits, 1);
+  else if (p.M <= 64 && p.K <= 1024) launch_skinny_cfg<4, 1, false, true, 4, 8, 1>(ctx, p, none, noln, keys, logits, 1, 256);
+  else if (p.M <= 112 && p.K <= 1024) launch_skinny_cfg<7, 1, false, true, 4, 8, 1>(ctx, p, none, noln, keys, logits, 1, 256);
   else if (p.K % 64 == 0) dispatch_ldsx<true>(p, none, keys, logits, 1, s);
   else {
     const int ntiles = p.N / 16;
@@ -588,6 +607,8 @@ int bpd_create(const bpd_config* cfg, void* workspace, size_t workspace_bytes, v
   ctx->stream = (hipStream_t)hip_stream;
   build_layout(*cfg, (char*)workspace, ctx->lay);
   build_table(ctx);
+  (void)hipMemsetAsync(ctx->lay.zeros, 0, ctx->lay.n_zeros * 4, ctx->stream);
+  (void)hipMemsetAsync(ctx->lay.stats_ln, 0, 64 * 16 * 2 * 4, ctx->stream);
   if (hipHostMalloc((void**)&ctx->pinned, 64 * sizeof(int), hipHostMallocDefault) != hipSuccess) {
     delete ctx;
     return BPD_E_HIP;

@@ -64,14 +64,19 @@ __device__ __forceinline__ void argmax_tiles(const f32x4 (&acc)[MT][NT], int m0,
 //   stats[(tile * 16 + row) * 2 + {0,1}],  tile < K/16 <= 64, row < 16.
 __device__ __forceinline__ void row_stats(const float* stats, int K, float eps, int lane, float& mu, float& rstd) {
   const int m = lane & 15, part = lane >> 4, slots = K >> 4;
-  float s = 0.f, q = 0.f;
+  // branch-free on purpose: conditional loads make the compiler wait for each one in turn
+  float2 v[16];
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
     const int t = part + 4 * i;
-    if (t < slots) {
-      const float2 v = ((const float2*)stats)[t * 16 + m];
-      s += v.x; q += v.y;
-    }
+    v[i] = ((const float2*)stats)[(t < slots ? t : 0) * 16 + m];
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  float s = 0.f, q = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const float w = (part + 4 * i) < slots ? 1.f : 0.f;
+    s = fmaf(w, v[i].x, s); q = fmaf(w, v[i].y, q);
   }
   s += __shfl_xor(s, 16, 64); s += __shfl_xor(s, 32, 64);
   q += __shfl_xor(q, 16, 64); q += __shfl_xor(q, 32, 64);
@@ -90,23 +95,28 @@ struct LnP {
 
 __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) { return (unsigned)f2bf(lo) | ((unsigned)f2bf(hi) << 16); }
 
-// Skinny GEMM: M <= 16 rows.  Workgroup = WAVES waves sharing NT column tiles, K split WAVES
-// ways (wave w takes k-steps w, w+WAVES, ...; at most U per wave, so K <= 32*WAVES*U), partial
-// sums meet in LDS and wave 0 runs the epilogue.  A workgroup walks column-tile groups
-// blockIdx.x, blockIdx.x + gridDim.x, ... keeping its activation fragments in registers and
-// requesting the next tile's weights before the current tile is reduced (PERSIST; otherwise one
-// tile group per workgroup).
+// Skinny GEMM: M <= 16*MT rows, all of them resident in registers.  Workgroup = WAVES waves
+// sharing NT column tiles, K split WAVES ways (wave w takes k-steps w, w+WAVES, ...; at most U
+// per wave, so K <= 32*WAVES*U).  A wave keeps its MT x U activation fragments in registers and
+// streams weight tiles; per column-tile group the WAVES partial sums meet in LDS (double
+// buffered: one barrier per group) and the MT*NT output tiles are finished by the waves in
+// turn (tile id % WAVES).  A workgroup walks tile groups blockIdx.x, blockIdx.x + gridDim.x,
+// ... with the weights of the next DEPTH groups in flight (DEPTH == 0: one group per
+// workgroup).
 //   XLN = false: X is bf16 [M][K] in global memory.
-//   XLN = true : X = LayerNorm(x) of the fp32 residual stream, normalised in registers from
-//                the producer's partial statistics.
-// Every global load of the first tile (weights, activations, statistics, bias and residual of
+//   XLN = true : (MT == 1) X = LayerNorm(x) of the fp32 residual stream, normalised in
+//                registers from the producer's partial statistics.
+// Every global load of the first group (weights, activations, statistics, bias and residual of
 // the epilogue) is issued before anything is waited for: one memory round trip per kernel.
 // Epilogue (mode 0) additionally supports: R = LayerNorm(R) via e.lnR_* (the heads' residual
 // is the normalised decoder output), and writing partial LayerNorm statistics of the result.
-template <int NT, bool XLN, bool ARGMAX, int WAVES, int U, bool PERSIST>
+// Dynamic LDS: 2 * WAVES * MT * NT * 1024 bytes.
+template <int MT, int NT, bool XLN, bool ARGMAX, int WAVES, int U, int DEPTH>
 __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e, LnP ln, unsigned long long* keys,
                                                                   float* logits) {
-  __shared__ f32x4 red[2][(WAVES - 1) * NT * 64];
+  constexpr int TILES = MT * NT, OWN = (TILES + WAVES - 1) / WAVES;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  f32x4* red = (f32x4*)smem_raw;               // [2][WAVES][TILES][64]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = blockIdx.z;
   const int ntiles = p.N >> 4, ksteps = p.K >> 5;
@@ -116,33 +126,46 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
   int nt0 = blockIdx.x * NT;
   if (nt0 >= ntiles) return;
 
-  uint4 a_cur[U][NT], a_nxt[PERSIST ? U : 1][NT];
+  constexpr bool PERSIST = DEPTH > 0;
+  const int stride = gridDim.x * NT;            // distance between consecutive tile groups of this workgroup
+  uint4 a[DEPTH + 1][U][NT];                    // a[0]: current group, a[1..DEPTH]: groups in flight
 #define BPD_LOAD_A(dst, tile0)                                                              \
   _Pragma("unroll") for (int i = 0; i < U; ++i) {                                           \
     const int ks_ = wave + WAVES * i;                                                       \
+    const int ksc_ = ks_ < ksteps ? ks_ : ksteps - 1;                                       \
     _Pragma("unroll") for (int u = 0; u < NT; ++u) {                                        \
       int t_ = (tile0) + u; t_ = t_ < ntiles ? t_ : ntiles - 1;                             \
-      dst[i][u] = ks_ < ksteps ? W[((long)t_ * ksteps + ks_) * 64] : zero4;                 \
+      dst[i][u] = W[((long)t_ * ksteps + ksc_) * 64];                                       \
     }                                                                                       \
   }
-  BPD_LOAD_A(a_cur, nt0)                        // weights first: they do not depend on the producer kernel
-
-  const int mrow = lr < p.M ? lr : p.M - 1;
-  float4 r_pre[NT], bias_pre[NT];
-  const bool plain_epi = !ARGMAX && e.mode == 0;
-  if (plain_epi && wave == 0) {
+  BPD_LOAD_A(a[0], nt0)                         // weights first: they do not depend on the producer kernel
 #pragma unroll
-    for (int u = 0; u < NT; ++u) {
-      int t = nt0 + u; t = t < ntiles ? t : ntiles - 1;
-      const int n = t * 16 + (lane >> 4) * 4;
-      r_pre[u] = e.R ? *(const float4*)(e.R + g * e.r_g + (long)mrow * e.ldr + n) : make_float4(0, 0, 0, 0);
-      bias_pre[u] = e.bias ? *(const float4*)(e.bias + g * e.bias_g + n) : make_float4(0, 0, 0, 0);
-    }
-  }
+  for (int dd = 1; dd < DEPTH; ++dd)
+    if (nt0 + dd * stride < ntiles) { BPD_LOAD_A(a[dd], nt0 + dd * stride) }
 
-  // activation fragments, kept for all tiles of this workgroup
-  uint4 b[U];
+  // operands of the epilogue (bias, residual) for the tiles this wave will finish; the host passes
+  // a zero-filled buffer where there is no bias / residual so that the loads are unconditional
+  const bool plain_epi = !ARGMAX && e.mode == 0;
+  float4 r_cur[OWN], bias_cur[OWN], r_nxt[OWN], bias_nxt[OWN];
+#define BPD_LOAD_EPI(rdst, bdst, tile0)                                                     \
+  if (!ARGMAX) {                                                                            \
+    _Pragma("unroll") for (int j = 0; j < OWN; ++j) {                                       \
+      int id_ = wave + WAVES * j; id_ = id_ < TILES ? id_ : TILES - 1;                      \
+      const int t_ = id_ / NT, u_ = id_ % NT;                                               \
+      int nt_ = (tile0) + u_; nt_ = nt_ < ntiles ? nt_ : ntiles - 1;                        \
+      const int n_ = nt_ * 16 + (lane >> 4) * 4;                                            \
+      int m_ = t_ * 16 + lr; m_ = m_ < p.M ? m_ : p.M - 1;                                  \
+      rdst[j] = *(const float4*)(e.R + g * e.r_g + (long)m_ * e.ldr + n_);                  \
+      bdst[j] = *(const float4*)(e.bias + g * e.bias_g + n_);                               \
+    }                                                                                       \
+  }
+  BPD_LOAD_EPI(r_cur, bias_cur, nt0)
+  __builtin_amdgcn_sched_barrier(0);            // keep the issue order: the scheduler would sink loads to their uses
+
+  // activation fragments, kept for all tile groups of this workgroup
+  uint4 b[MT][U];
   if (XLN) {
+    const int mrow = lr < p.M ? lr : p.M - 1;
     float4 xv[U][2], gv[U][2], bv[U][2];
 #pragma unroll
     for (int i = 0; i < U; ++i) {
@@ -155,6 +178,7 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
         bv[i][hh] = *(const float4*)(ln.b + col + 4 * hh);
       }
     }
+    __builtin_amdgcn_sched_barrier(0);
     float mu, rstd;
     row_stats(ln.stats, p.K, ln.eps, lane, mu, rstd);
 #pragma unroll
@@ -167,91 +191,133 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
         y[4 * hh + 2] = (xv[i][hh].z - mu) * rstd * gv[i][hh].z + bv[i][hh].z;
         y[4 * hh + 3] = (xv[i][hh].w - mu) * rstd * gv[i][hh].w + bv[i][hh].w;
       }
-      b[i] = make_uint4(pack_bf16(y[0], y[1]), pack_bf16(y[2], y[3]), pack_bf16(y[4], y[5]), pack_bf16(y[6], y[7]));
+      const uint4 yb = make_uint4(pack_bf16(y[0], y[1]), pack_bf16(y[2], y[3]), pack_bf16(y[4], y[5]), pack_bf16(y[6], y[7]));
+      b[0][i] = (wave + WAVES * i) < ksteps ? yb : zero4;
     }
   } else {
-    const bf16_t* xg = (const bf16_t*)p.X + g * p.x_g + (long)mrow * p.ldx + lk;
 #pragma unroll
-    for (int i = 0; i < U; ++i) {
-      const int ks = wave + WAVES * i;
-      b[i] = ks < ksteps ? *(const uint4*)(xg + ks * 32) : zero4;
+    for (int t = 0; t < MT; ++t) {
+      int row = t * 16 + lr; row = row < p.M ? row : p.M - 1;
+      const bf16_t* xg = (const bf16_t*)p.X + g * p.x_g + (long)row * p.ldx + lk;
+#pragma unroll
+      for (int i = 0; i < U; ++i) {
+        const int ks = wave + WAVES * i;
+        const uint4 v = *(const uint4*)(xg + (ks < ksteps ? ks : ksteps - 1) * 32);
+        b[t][i] = ks < ksteps ? v : zero4;          // k-steps beyond K contribute nothing
+      }
     }
+    __builtin_amdgcn_sched_barrier(0);
   }
 
-  int it = 0;
-  for (; nt0 < ntiles; nt0 += (PERSIST ? gridDim.x * NT : ntiles), ++it) {
-    f32x4 acc[1][NT];
+  unsigned long long best_run[OWN];
 #pragma unroll
-    for (int u = 0; u < NT; ++u) acc[0][u] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const int nt_next = nt0 + gridDim.x * NT;
-    if (PERSIST && nt_next < ntiles) { BPD_LOAD_A(a_nxt, nt_next) }
+  for (int j = 0; j < OWN; ++j) best_run[j] = 0ull;
+  int it = 0;
+  for (; nt0 < ntiles; nt0 += (PERSIST ? stride : ntiles), ++it) {
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+      for (int u = 0; u < NT; ++u) acc[t][u] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int nt_next = nt0 + stride;
+    const bool more = PERSIST && nt_next < ntiles;
+    if (PERSIST && nt0 + DEPTH * stride < ntiles) { BPD_LOAD_A(a[DEPTH], nt0 + DEPTH * stride) }
+    if (more) { BPD_LOAD_EPI(r_nxt, bias_nxt, nt_next) }
 #pragma unroll
     for (int i = 0; i < U; ++i)
 #pragma unroll
-      for (int u = 0; u < NT; ++u)
-        acc[0][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_cur[i][u]),
-                                                            __builtin_bit_cast(bf16x8, b[i]), acc[0][u], 0, 0, 0);
-    if (PERSIST && nt_next < ntiles) {
+      for (int t = 0; t < MT; ++t)
 #pragma unroll
-      for (int i = 0; i < (PERSIST ? U : 1); ++i)
+        for (int u = 0; u < NT; ++u)
+          acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[0][i][u]),
+                                                              __builtin_bit_cast(bf16x8, b[t][i]), acc[t][u], 0, 0, 0);
+    // partial sums of all waves meet in LDS
+    f32x4* rb = red + (it & 1) * (WAVES * TILES * 64);
 #pragma unroll
-        for (int u = 0; u < NT; ++u) a_cur[i][u] = a_nxt[i][u];
-    }
-    // cross-wave reduction (double-buffered so that one barrier per tile suffices)
-    f32x4* rb = red[it & 1];
-    if (wave > 0) {
+    for (int t = 0; t < MT; ++t)
 #pragma unroll
-      for (int u = 0; u < NT; ++u) rb[((wave - 1) * NT + u) * 64 + lane] = acc[0][u];
-    }
+      for (int u = 0; u < NT; ++u) rb[(wave * TILES + t * NT + u) * 64 + lane] = acc[t][u];
     __syncthreads();
-    if (wave != 0) continue;
+    float mu = 0.f, rstd = 1.f;
+    if (plain_epi && e.lnR_stats && wave < TILES) row_stats(e.lnR_stats, e.lnR_K, e.lnR_eps, lane, mu, rstd);
 #pragma unroll
-    for (int w = 0; w < WAVES - 1; ++w)
+    for (int j = 0; j < OWN; ++j) {
+      const int id = wave + WAVES * j;
+      if (id >= TILES) continue;
+      const int t = id / NT, u = id % NT;
+      if (nt0 + u >= ntiles) continue;
+      f32x4 sum = rb[id * 64 + lane];
 #pragma unroll
-      for (int u = 0; u < NT; ++u) acc[0][u] += rb[(w * NT + u) * 64 + lane];
-    if (ARGMAX) {
-      argmax_tiles<1, NT>(acc, 0, nt0, ntiles, p.M, p.N, lane, keys, logits);
-    } else if (e.mode != 0) {
-      store_tiles<1, NT>(e, g, acc, 0, nt0, ntiles, p.M, lane);
-    } else {
-      float mu = 0.f, rstd = 1.f;
-      if (e.lnR_stats) row_stats(e.lnR_stats, e.lnR_K, e.lnR_eps, lane, mu, rstd);
+      for (int w = 1; w < WAVES; ++w) sum += rb[(w * TILES + id) * 64 + lane];
+      const int m = t * 16 + lr;
+      const int n = (nt0 + u) * 16 + (lane >> 4) * 4;
+      if (ARGMAX) {
+        // running best over all column tiles this workgroup walks; merged into keys[] once at the end
+        // (atomics on one row's key serialise, so their number is what matters)
 #pragma unroll
-      for (int u = 0; u < NT; ++u) {
-        if (nt0 + u >= ntiles) continue;
-        const int n = (nt0 + u) * 16 + (lane >> 4) * 4;
-        float4 rv = r_pre[u], bs = bias_pre[u];
-        if (it > 0) {
-          rv = e.R ? *(const float4*)(e.R + g * e.r_g + (long)mrow * e.ldr + n) : make_float4(0, 0, 0, 0);
-          bs = e.bias ? *(const float4*)(e.bias + g * e.bias_g + n) : make_float4(0, 0, 0, 0);
+        for (int r = 0; r < 4; ++r) {
+          const unsigned long long key = argmax_key(sum[r], (unsigned)(n + r));
+          best_run[j] = key > best_run[j] ? key : best_run[j];
         }
+        if (logits && m < p.M) *(float4*)(logits + (long)m * p.N + n) = make_float4(sum[0], sum[1], sum[2], sum[3]);
+      } else if (e.mode != 0) {
+        if (m < p.M) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) epi_store<bf16_t>(e, g, m, n + r, sum[r]);
+        }
+      } else {
+        float4 rv = r_cur[j];
+        const float4 bs = bias_cur[j];
         if (e.lnR_stats) {
           const float4 gg = *(const float4*)(e.lnR_g + n), bb = *(const float4*)(e.lnR_b + n);
           rv.x = (rv.x - mu) * rstd * gg.x + bb.x; rv.y = (rv.y - mu) * rstd * gg.y + bb.y;
           rv.z = (rv.z - mu) * rstd * gg.z + bb.z; rv.w = (rv.w - mu) * rstd * gg.w + bb.w;
         }
-        float v[4] = {acc[0][u][0] + bs.x, acc[0][u][1] + bs.y, acc[0][u][2] + bs.z, acc[0][u][3] + bs.w};
+        float v[4] = {sum[0] + bs.x, sum[1] + bs.y, sum[2] + bs.z, sum[3] + bs.w};
         if (e.relu) {
 #pragma unroll
           for (int r = 0; r < 4; ++r) v[r] = fmaxf(v[r], 0.f);
         }
         v[0] += rv.x; v[1] += rv.y; v[2] += rv.z; v[3] += rv.w;
-        if (e.stats_out) {
-          float s = (v[0] + v[1]) + (v[2] + v[3]);
-          float q = (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
-          s += __shfl_xor(s, 16, 64); s += __shfl_xor(s, 32, 64);
-          q += __shfl_xor(q, 16, 64); q += __shfl_xor(q, 32, 64);
-          if (lane < 16) ((float2*)e.stats_out)[(nt0 + u) * 16 + lane] = make_float2(s, q);
+        if (e.stats_out) {          // MT == 1 on this path: row = lane % 16
+          float sv = (v[0] + v[1]) + (v[2] + v[3]);
+          float qv = (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
+          sv += __shfl_xor(sv, 16, 64); sv += __shfl_xor(sv, 32, 64);
+          qv += __shfl_xor(qv, 16, 64); qv += __shfl_xor(qv, 32, 64);
+          if (lane < 16) ((float2*)e.stats_out)[(nt0 + u) * 16 + lane] = make_float2(sv, qv);
         }
-        if (lr < p.M) {
-          if (e.Yf) *(float4*)(e.Yf + g * e.yf_g + (long)lr * e.ldyf + n) = make_float4(v[0], v[1], v[2], v[3]);
-          if (e.Ya) *(uint2*)((bf16_t*)e.Ya + g * e.ya_g + (long)lr * e.ldya + n) =
+        if (m < p.M) {
+          if (e.Yf) *(float4*)(e.Yf + g * e.yf_g + (long)m * e.ldyf + n) = make_float4(v[0], v[1], v[2], v[3]);
+          if (e.Ya) *(uint2*)((bf16_t*)e.Ya + g * e.ya_g + (long)m * e.ldya + n) =
                         make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
         }
       }
     }
+    if (more) {
+#pragma unroll
+      for (int dd = 0; dd < DEPTH; ++dd)
+#pragma unroll
+        for (int i = 0; i < U; ++i)
+#pragma unroll
+          for (int u = 0; u < NT; ++u) a[dd][i][u] = a[dd + 1][i][u];
+#pragma unroll
+      for (int j = 0; j < OWN; ++j) { r_cur[j] = r_nxt[j]; bias_cur[j] = bias_nxt[j]; }
+    }
+  }
+  if (ARGMAX) {
+#pragma unroll
+    for (int j = 0; j < OWN; ++j) {
+      const int id = wave + WAVES * j;
+      if (id >= TILES) continue;
+      const int m = (id / NT) * 16 + lr;
+      unsigned long long best = best_run[j];
+      unsigned long long o = __shfl_xor(best, 16, 64); best = o > best ? o : best;
+      o = __shfl_xor(best, 32, 64); best = o > best ? o : best;
+      if (keys && lane < 16 && m < p.M && best != 0ull) atomicMax(&keys[m], best);
+    }
   }
 #undef BPD_LOAD_A
+#undef BPD_LOAD_EPI
 }
 
 // ---------------------------------------------------------------------------------------
@@ -348,7 +414,38 @@ __global__ __launch_bounds__(256) void gemm_ldsx_kernel(GemmP p, Epi e, unsigned
   }
 #undef BPD_XDST
 #undef BPD_XOK
+  if (ARGMAX) {
+    // per-row best of each wave -> LDS -> one atomic per row and workgroup
+    unsigned long long* wb = (unsigned long long*)smem_raw;       // [4][BM], the staging buffers are free now
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+      const int m = m0 + t * 16 + lr;
+      unsigned long long best = 0ull;
+#pragma unroll
+      for (int u = 0; u < NT; ++u) {
+        if (nt0 + u >= ntiles) continue;
+        const int n = (nt0 + u) * 16 + (lane >> 4) * 4;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const unsigned long long key = argmax_key(acc[t][u][r], (unsigned)(n + r));
+          best = key > best ? key : best;
+        }
+        if (logits && m < p.M)
+          *(float4*)(logits + (long)m * p.N + n) = make_float4(acc[t][u][0], acc[t][u][1], acc[t][u][2], acc[t][u][3]);
+      }
+      unsigned long long o = __shfl_xor(best, 16, 64); best = o > best ? o : best;
+      o = __shfl_xor(best, 32, 64); best = o > best ? o : best;
+      if (lane < 16) wb[wave * BM + t * 16 + lane] = best;
+    }
+    __syncthreads();
+    if (tid < BM && m0 + tid < p.M) {
+      unsigned long long best = wb[tid];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) { const unsigned long long o = wb[w * BM + tid]; best = o > best ? o : best; }
+      if (best != 0ull) atomicMax(&keys[m0 + tid], best);
+    }
+    return;
+  }
   if (nt0 >= ntiles) return;
-  if (ARGMAX) argmax_tiles<MT, NT>(acc, m0, nt0, ntiles, p.M, p.N, lane, keys, logits);
-  else store_tiles<MT, NT>(e, g, acc, m0, nt0, ntiles, p.M, lane);
+  store_tiles<MT, NT>(e, g, acc, m0, nt0, ntiles, p.M, lane);
 }

@@ -482,14 +482,29 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnP p) {
 #pragma unroll
     for (int x = 0; x < VW; ++x) { kraw[x] = kp[x]; vraw[x] = vp[x]; }
   }
-  for (int idx = tid; idx < RT * DH; idx += 256) {
-    const int i = idx / DH, c = idx % DH;
-    q_s[i][c] = i < nrows ? p.Q[((long)b * p.R + r0 + i) * p.d + h * DH + c] * p.scale : 0.f;
+  // queries: RT*DH/256 consecutive features per thread, one unconditional load (rows clamped)
+  constexpr int QE = RT * DH / 256;
+  float qreg[QE];
+  {
+    const int i = tid * QE / DH, c = tid * QE % DH;
+    const int row = r0 + (i < nrows ? i : nrows - 1);
+    const float* qp = p.Q + ((long)b * p.R + row) * p.d + h * DH + c;
+    if (QE == 4) { const float4 v = *(const float4*)qp; qreg[0] = v.x; qreg[1 % QE] = v.y; qreg[2 % QE] = v.z; qreg[3 % QE] = v.w; }
+    else {
+#pragma unroll
+      for (int x = 0; x < QE; ++x) qreg[x] = qp[x];
+    }
   }
   int lim = p.limit[b];
   lim = lim < 0 ? 0 : lim;
   int nkeys = p.causal ? lim + r0 + nrows : lim;   // keys any row of the tile can see
   nkeys = nkeys < p.cap ? nkeys : p.cap;
+  __builtin_amdgcn_sched_barrier(0);              // all global loads above are in flight before the first wait
+  {
+    const int i = tid * QE / DH, c = tid * QE % DH;
+#pragma unroll
+    for (int x = 0; x < QE; ++x) q_s[i][c + x] = i < nrows ? qreg[x] * p.scale : 0.f;
+  }
   if (tid < RT) { m_s[tid] = -INFINITY; l_s[tid] = 0.f; alpha_s[tid] = 1.f; }
   float acc[RT];
 #pragma unroll
