@@ -275,7 +275,7 @@ template <int MT, int NT, int KC, bool ARGMAX>
 void launch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* logits, int groups, hipStream_t s) {
   const int ntiles = p.N / 16;
   dim3 grid((ntiles + 4 * NT - 1) / (4 * NT), (p.M + 16 * MT - 1) / (16 * MT), groups);
-  const size_t lds = (size_t)2 * 16 * MT * (KC + 8) * 2;
+  const size_t lds = (size_t)2 * ((16 * MT * (KC / 8) + 255) / 256) * 4096;
   static bool attr_set = false;                 // per instantiation: allow more than 64 KiB of LDS
   if (!attr_set) {
     (void)hipFuncSetAttribute((const void*)gemm_ldsx_kernel<MT, NT, KC, ARGMAX>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

@@ -323,23 +323,26 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
 // ---------------------------------------------------------------------------------------
 // "ldsx" GEMM: BM = 16*MT rows x BN = 64*NT columns per workgroup, K walked in chunks of KC.
 // Wave w owns column tiles (4*blockIdx.x + w)*NT .. +NT and streams their weight tiles from
-// global memory one chunk ahead (KC/32 * NT fragments in flight per wave); the BM x KC
-// activation chunk is staged in LDS (double buffered, row stride KC+8 bf16 so that the 16-byte
-// operand reads of a wave spread evenly over the banks).  Requires K % KC == 0.
-// Dynamic LDS: 2 * BM * (KC + 8) * 2 bytes.
+// global memory into registers one chunk ahead (KC/32 * NT fragments in flight per wave).  The
+// BM x KC activation chunk goes global -> LDS directly (global_load_lds_dwordx4, no staging
+// registers), double buffered.  Such a load writes 64 consecutive 16-byte slots per wave, so
+// rows cannot be padded; instead the 16-byte segment index within a row is XOR-ed with
+// (row & 7), which spreads the MFMA operand reads of a wave evenly over the LDS banks.
+// Requires K % KC == 0, KC % 64 == 0.  Dynamic LDS: 2 * XI * 4096 bytes.
 template <int MT, int NT, int KC, bool ARGMAX>
-__global__ __launch_bounds__(256) void gemm_ldsx_kernel(GemmP p, Epi e, unsigned long long* keys, float* logits) {
-  constexpr int BM = 16 * MT, LD = KC + 8, KS = KC / 32, SEG = KC / 8;
-  constexpr int XI = (BM * SEG + 255) / 256;       // 16-byte segments per thread per chunk
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (MT * NT >= 16 ? 1 : 2)))) void gemm_ldsx_kernel(GemmP p, Epi e, unsigned long long* keys, float* logits) {
+  constexpr int BM = 16 * MT, KS = KC / 32, SEG = KC / 8;
+  constexpr int XI = (BM * SEG + 255) / 256;       // direct-to-LDS loads per thread per chunk
+  constexpr int BUF = XI * 256 * 8;                // bf16 elements per buffer (whole wave-loads)
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t* xs0 = (bf16_t*)smem_raw;
-  bf16_t* xs1 = xs0 + BM * LD;
+  bf16_t* xs1 = xs0 + BUF;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = blockIdx.z;
   const int ntiles = p.N >> 4, ksteps = p.K >> 5, nchunks = p.K / KC;
   const int m0 = blockIdx.y * BM;
   const int nt0 = (blockIdx.x * 4 + wave) * NT;
-  const int lr = lane & 15, lk = (lane >> 4) * 8;
+  const int lr = lane & 15, lq = lane >> 4;
   const bf16_t* X = (const bf16_t*)p.X + g * p.x_g;
   const bf16_t* W = (const bf16_t*)p.W + g * p.w_g;
   const uint4* wt[NT];
@@ -349,19 +352,21 @@ __global__ __launch_bounds__(256) void gemm_ldsx_kernel(GemmP p, Epi e, unsigned
     tile = tile < ntiles ? tile : ntiles - 1;
     wt[u] = (const uint4*)W + (long)tile * ksteps * 64 + lane;
   }
-  // global source (element offset from X) of this thread's 16-byte segments of a chunk; the LDS
-  // destination is recomputed from the index where needed (keeps the register count down)
+  // slot i*256 + tid of a buffer holds row = slot / SEG, segment (slot % SEG) ^ (row & 7)
   int xoff[XI];
 #pragma unroll
   for (int i = 0; i < XI; ++i) {
-    const int idx = tid + 256 * i;
-    int row = m0 + idx / SEG;
+    const int slot = tid + 256 * i;
+    const int r = slot / SEG;
+    int row = m0 + r;
     row = row < p.M ? row : p.M - 1;
-    xoff[i] = row * p.ldx + (idx % SEG) * 8;
+    xoff[i] = row * p.ldx + (((slot % SEG) ^ (r & 7)) * 8);
   }
-#define BPD_XDST(i) (((tid + 256 * (i)) / SEG) * LD + ((tid + 256 * (i)) % SEG) * 8)
-#define BPD_XOK(i) (XI * 256 == BM * SEG || tid + 256 * (i) < BM * SEG)
-  uint4 xr[XI], a_cur[KS][NT], a_nxt[KS][NT];
+#define BPD_X_TO_LDS(buf, chunk)                                                            \
+  _Pragma("unroll") for (int i = 0; i < XI; ++i)                                            \
+    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(X + xoff[i] + (chunk) * KC), \
+                                     (void __attribute__((address_space(3)))*)((buf) + (i * 256 + wave * 64) * 8), 16, 0, 0);
+  uint4 a_cur[KS][NT], a_nxt[KS][NT];
   f32x4 acc[MT][NT];
 #pragma unroll
   for (int t = 0; t < MT; ++t)
@@ -371,28 +376,27 @@ __global__ __launch_bounds__(256) void gemm_ldsx_kernel(GemmP p, Epi e, unsigned
   for (int s = 0; s < KS; ++s)
 #pragma unroll
     for (int u = 0; u < NT; ++u) a_cur[s][u] = wt[u][(long)s * 64];
-#pragma unroll
-  for (int i = 0; i < XI; ++i) xr[i] = *(const uint4*)(X + xoff[i]);
-#pragma unroll
-  for (int i = 0; i < XI; ++i)
-    if (BPD_XOK(i)) *(uint4*)(xs0 + BPD_XDST(i)) = xr[i];
+  BPD_X_TO_LDS(xs0, 0)
+  __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
   for (int c = 0; c < nchunks; ++c) {
-    const bool more = c + 1 < nchunks;
-    if (more) {
+    // next chunk in flight while this one is multiplied (the last iteration re-requests its own
+    // chunk so that the code stays branch-free)
+    const int cn = c + 1 < nchunks ? c + 1 : c;
+    bf16_t* xn = (c & 1) ? xs0 : xs1;
+    BPD_X_TO_LDS(xn, cn)
 #pragma unroll
-      for (int s = 0; s < KS; ++s)
+    for (int s = 0; s < KS; ++s)
 #pragma unroll
-        for (int u = 0; u < NT; ++u) a_nxt[s][u] = wt[u][(long)((c + 1) * KS + s) * 64];
-#pragma unroll
-      for (int i = 0; i < XI; ++i) xr[i] = *(const uint4*)(X + xoff[i] + (c + 1) * KC);
-    }
+      for (int u = 0; u < NT; ++u) a_nxt[s][u] = wt[u][(long)(cn * KS + s) * 64];
+    __builtin_amdgcn_sched_barrier(0);
     const bf16_t* xb = (c & 1) ? xs1 : xs0;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       uint4 b[MT];
 #pragma unroll
-      for (int t = 0; t < MT; ++t) b[t] = *(const uint4*)(xb + (t * 16 + lr) * LD + s * 32 + lk);
+      for (int t = 0; t < MT; ++t)
+        b[t] = *(const uint4*)(xb + (t * 16 + lr) * KC + (((s * 4 + lq) ^ (lr & 7)) * 8));
 #pragma unroll
       for (int t = 0; t < MT; ++t)
 #pragma unroll
@@ -400,20 +404,15 @@ __global__ __launch_bounds__(256) void gemm_ldsx_kernel(GemmP p, Epi e, unsigned
           acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_cur[s][u]),
                                                               __builtin_bit_cast(bf16x8, b[t]), acc[t][u], 0, 0, 0);
     }
-    if (more) {
-      bf16_t* xn = (c & 1) ? xs0 : xs1;
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int i = 0; i < XI; ++i)
-        if (BPD_XOK(i)) *(uint4*)(xn + BPD_XDST(i)) = xr[i];
+    for (int s = 0; s < KS; ++s)
 #pragma unroll
-      for (int s = 0; s < KS; ++s)
-#pragma unroll
-        for (int u = 0; u < NT; ++u) a_cur[s][u] = a_nxt[s][u];
-    }
+      for (int u = 0; u < NT; ++u) a_cur[s][u] = a_nxt[s][u];
+    __builtin_amdgcn_s_waitcnt(0);              // the direct-to-LDS loads are not tracked by the compiler
     __syncthreads();
   }
-#undef BPD_XDST
-#undef BPD_XOK
+#undef BPD_X_TO_LDS
   if (ARGMAX) {
     // per-row best of each wave -> LDS -> one atomic per row and workgroup
     unsigned long long* wb = (unsigned long long*)smem_raw;       // [4][BM], the staging buffers are free now
