@@ -60,6 +60,7 @@ bool config_ok(const bpd_config& c) {
   if (dh != 16 && dh != 64) return false;
   if (c.dtype == BPD_F32 && dh != 16) return false;     // fp32 mode is for small models only
   if (c.d_model % 32 || c.d_ff % 32 || c.vocab % 16 || c.vocab < 16) return false;
+  if (c.d_model > 2048) return false;                   // LayerNorm kernel keeps a row in registers
   if (c.k_max < 1 || c.k_max > 16) return false;
   if (c.max_batch < 1 || c.max_src_len < 1 || c.max_out_len < 1) return false;
   if (c.dtype != BPD_F32 && c.dtype != BPD_BF16) return false;
@@ -240,7 +241,7 @@ void launch_skinny_cfg(const bpd_ctx* ctx, const GemmP& p, const Epi& e_in, cons
   const int ntiles = p.N / 16;
   const int ngroups = (ntiles + NT - 1) / NT;
   const int gx = ngroups > cap ? cap : ngroups;  // beyond `cap` each workgroup walks several column-tile groups
-  dim3 grid(gx, 1, groups);
+  dim3 grid(gx, (p.M + 16 * MT - 1) / (16 * MT), groups);
   const size_t lds = (size_t)2 * WAVES * MT * NT * 1024;
   if (ngroups > gx) {
     auto k = skinny_gemm_kernel<MT, NT, XLN, ARGMAX, WAVES, U, DEPTH>;
@@ -333,10 +334,17 @@ void gemm(bpd_ctx* ctx, const GemmP& p, const Epi& e, int groups = 1) {
     hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(128), 0, s, p, e);
     return;
   }
+  LnP none{};
   if (skinny_ok(ctx, p)) {
-    LnP none{};
     if (p.N / 16 >= 2048) launch_skinny<2, false, false>(ctx, p, e, none, nullptr, nullptr, groups);
     else launch_skinny<1, false, false>(ctx, p, e, none, nullptr, nullptr, groups);
+  } else if (p.M <= 640 && p.K <= 1024) {
+    // a few row blocks: rows resident in registers, K split over the waves, no LDS staging
+    if (p.M <= 32) launch_skinny_cfg<2, 1, false, false, 4, 8, 2>(ctx, p, e, none, nullptr, nullptr, groups);
+    else if (p.M <= 64) launch_skinny_cfg<4, 1, false, false, 4, 8, 2>(ctx, p, e, none, nullptr, nullptr, groups);
+    else launch_skinny_cfg<5, 1, false, false, 4, 8, 2>(ctx, p, e, none, nullptr, nullptr, groups);
+  } else if (p.M <= 640 && p.K <= 4096) {
+    launch_skinny_cfg<1, 1, false, false, 8, 16, 1>(ctx, p, e, none, nullptr, nullptr, groups);   // row blocks of 16
   } else if (p.K % 64 == 0) {
     dispatch_ldsx<false>(p, e, nullptr, nullptr, groups, s);
   } else {

@@ -95,7 +95,7 @@ struct LnP {
 
 __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) { return (unsigned)f2bf(lo) | ((unsigned)f2bf(hi) << 16); }
 
-// Skinny GEMM: M <= 16*MT rows, all of them resident in registers.  Workgroup = WAVES waves
+// Skinny GEMM: blocks of 16*MT rows (blockIdx.y), all rows of a block resident in registers.  Workgroup = WAVES waves
 // sharing NT column tiles, K split WAVES ways (wave w takes k-steps w, w+WAVES, ...; at most U
 // per wave, so K <= 32*WAVES*U).  A wave keeps its MT x U activation fragments in registers and
 // streams weight tiles; per column-tile group the WAVES partial sums meet in LDS (double
@@ -125,6 +125,7 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
   const uint4 zero4 = make_uint4(0, 0, 0, 0);
   int nt0 = blockIdx.x * NT;
   if (nt0 >= ntiles) return;
+  const int mb0 = blockIdx.y * (16 * MT);       // row block of this workgroup
 
   constexpr bool PERSIST = DEPTH > 0;
   const int stride = gridDim.x * NT;            // distance between consecutive tile groups of this workgroup
@@ -154,7 +155,7 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
       const int t_ = id_ / NT, u_ = id_ % NT;                                               \
       int nt_ = (tile0) + u_; nt_ = nt_ < ntiles ? nt_ : ntiles - 1;                        \
       const int n_ = nt_ * 16 + (lane >> 4) * 4;                                            \
-      int m_ = t_ * 16 + lr; m_ = m_ < p.M ? m_ : p.M - 1;                                  \
+      int m_ = mb0 + t_ * 16 + lr; m_ = m_ < p.M ? m_ : p.M - 1;                                \
       rdst[j] = *(const float4*)(e.R + g * e.r_g + (long)m_ * e.ldr + n_);                  \
       bdst[j] = *(const float4*)(e.bias + g * e.bias_g + n_);                               \
     }                                                                                       \
@@ -165,7 +166,7 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
   // activation fragments, kept for all tile groups of this workgroup
   uint4 b[MT][U];
   if (XLN) {
-    const int mrow = lr < p.M ? lr : p.M - 1;
+    const int mrow = mb0 + lr < p.M ? mb0 + lr : p.M - 1;
     float4 xv[U][2], gv[U][2], bv[U][2];
 #pragma unroll
     for (int i = 0; i < U; ++i) {
@@ -197,7 +198,7 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
   } else {
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
-      int row = t * 16 + lr; row = row < p.M ? row : p.M - 1;
+      int row = mb0 + t * 16 + lr; row = row < p.M ? row : p.M - 1;
       const bf16_t* xg = (const bf16_t*)p.X + g * p.x_g + (long)row * p.ldx + lk;
 #pragma unroll
       for (int i = 0; i < U; ++i) {
@@ -249,7 +250,7 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
       f32x4 sum = rb[id * 64 + lane];
 #pragma unroll
       for (int w = 1; w < WAVES; ++w) sum += rb[(w * TILES + id) * 64 + lane];
-      const int m = t * 16 + lr;
+      const int m = mb0 + t * 16 + lr;
       const int n = (nt0 + u) * 16 + (lane >> 4) * 4;
       if (ARGMAX) {
         // running best over all column tiles this workgroup walks; merged into keys[] once at the end
@@ -309,7 +310,7 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
     for (int j = 0; j < OWN; ++j) {
       const int id = wave + WAVES * j;
       if (id >= TILES) continue;
-      const int m = (id / NT) * 16 + lr;
+      const int m = mb0 + (id / NT) * 16 + lr;
       unsigned long long best = best_run[j];
       unsigned long long o = __shfl_xor(best, 16, 64); best = o > best ? o : best;
       o = __shfl_xor(best, 32, 64); best = o > best ? o : best;

@@ -376,7 +376,9 @@ __global__ __launch_bounds__(64) void embed_stats_kernel(const int* tok, int tok
   if (row < M) *(float4*)(x + (long)row * d + c0) = make_float4(v[0], v[1], v[2], v[3]);
 }
 
-// LayerNorm over the last axis, one wavefront per row (biased variance, two passes).
+// LayerNorm over the last axis, one wavefront per row (biased variance, two passes over
+// registers).  The row is fetched with one batch of loads; d <= 64 * 4 * LN_V.
+constexpr int LN_V = 8;
 template <typename ACT>
 __global__ __launch_bounds__(256) void layernorm_kernel(const float* x, const float* g, const float* b, int M,
                                                         int d, float eps, ACT* ya, float* yf) {
@@ -384,16 +386,39 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const float* x, const fl
   const int lane = threadIdx.x & 63;
   if (row >= M) return;
   const float* xr = x + (long)row * d;
+  const int nv = d >> 2;                         // float4 per row
+  float4 v[LN_V], gg[LN_V], bb[LN_V];
+#pragma unroll
+  for (int i = 0; i < LN_V; ++i) {
+    const int c4 = lane + 64 * i;
+    const int cc = c4 < nv ? c4 : 0;
+    v[i] = ((const float4*)xr)[cc]; gg[i] = ((const float4*)g)[cc]; bb[i] = ((const float4*)b)[cc];
+  }
+  __builtin_amdgcn_sched_barrier(0);
   float s = 0.f;
-  for (int c = lane; c < d; c += 64) s += xr[c];
+#pragma unroll
+  for (int i = 0; i < LN_V; ++i) {
+    const float w = (lane + 64 * i) < nv ? 1.f : 0.f;
+    s += w * ((v[i].x + v[i].y) + (v[i].z + v[i].w));
+  }
   const float mu = wave_sum(s) / d;
   float q = 0.f;
-  for (int c = lane; c < d; c += 64) { const float t = xr[c] - mu; q += t * t; }
+#pragma unroll
+  for (int i = 0; i < LN_V; ++i) {
+    const float w = (lane + 64 * i) < nv ? 1.f : 0.f;
+    const float a0 = v[i].x - mu, a1 = v[i].y - mu, a2 = v[i].z - mu, a3 = v[i].w - mu;
+    q += w * ((a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3));
+  }
   const float rstd = 1.0f / sqrtf(wave_sum(q) / d + eps);
-  for (int c = lane; c < d; c += 64) {
-    const float v = (xr[c] - mu) * rstd * g[c] + b[c];
-    if (ya) ya[(long)row * d + c] = from_f<ACT>(v);
-    if (yf) yf[(long)row * d + c] = v;
+#pragma unroll
+  for (int i = 0; i < LN_V; ++i) {
+    const int c4 = lane + 64 * i;
+    if (c4 < nv) {
+      const float y0 = (v[i].x - mu) * rstd * gg[i].x + bb[i].x, y1 = (v[i].y - mu) * rstd * gg[i].y + bb[i].y;
+      const float y2 = (v[i].z - mu) * rstd * gg[i].z + bb[i].z, y3 = (v[i].w - mu) * rstd * gg[i].w + bb[i].w;
+      if (ya) { ACT* o = ya + (long)row * d + 4 * c4; o[0] = from_f<ACT>(y0); o[1] = from_f<ACT>(y1); o[2] = from_f<ACT>(y2); o[3] = from_f<ACT>(y3); }
+      if (yf) ((float4*)(yf + (long)row * d))[c4] = make_float4(y0, y1, y2, y3);
+    }
   }
 }
 
