@@ -308,11 +308,10 @@ int pick_nt(int M, int N, int mt, int groups) {
 template <bool ARGMAX>
 void dispatch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* logits, int groups, hipStream_t s) {
   const int mt = pick_mt(p.M), nt = pick_nt(p.M, p.N, mt, groups);
-  const long mblocks = (p.M + 16 * mt - 1) / (16 * mt);
-  // one row block and wide N: the kernel is a pure weight stream; deep chunks keep ~64 KiB of
-  // weights in flight per CU
-  if (mblocks == 1 && nt == 2 && p.K % 256 == 0) {
-#define BPD_CASE(MT_) if (mt == MT_) { launch_ldsx<MT_, 2, 256, ARGMAX>(p, e, keys, logits, groups, s); return; }
+  // long K with one column tile per wave: little work per 64-wide chunk, so walk K in chunks of
+  // 256 (fewer barriers, 8 weight fragments per wave in flight)
+  if (nt == 1 && p.K >= 2048 && p.K % 256 == 0) {
+#define BPD_CASE(MT_) if (mt == MT_) { launch_ldsx<MT_, 1, 256, ARGMAX>(p, e, keys, logits, groups, s); return; }
     BPD_CASE(8) BPD_CASE(7) BPD_CASE(5) BPD_CASE(4) BPD_CASE(2)
 #undef BPD_CASE
   }
@@ -339,12 +338,15 @@ void gemm(bpd_ctx* ctx, const GemmP& p, const Epi& e, int groups = 1) {
     if (p.N / 16 >= 2048) launch_skinny<2, false, false>(ctx, p, e, none, nullptr, nullptr, groups);
     else launch_skinny<1, false, false>(ctx, p, e, none, nullptr, nullptr, groups);
   } else if (p.M <= 640 && p.K <= 1024) {
-    // a few row blocks: rows resident in registers, K split over the waves, no LDS staging
-    if (p.M <= 32) launch_skinny_cfg<2, 1, false, false, 4, 8, 2>(ctx, p, e, none, nullptr, nullptr, groups);
-    else if (p.M <= 64) launch_skinny_cfg<4, 1, false, false, 4, 8, 2>(ctx, p, e, none, nullptr, nullptr, groups);
-    else launch_skinny_cfg<5, 1, false, false, 4, 8, 2>(ctx, p, e, none, nullptr, nullptr, groups);
-  } else if (p.M <= 640 && p.K <= 4096) {
-    launch_skinny_cfg<1, 1, false, false, 8, 16, 1>(ctx, p, e, none, nullptr, nullptr, groups);   // row blocks of 16
+    // a few row blocks: rows resident in registers, K split over the waves, no LDS staging.  Each
+    // workgroup pays for loading its row block once, so it walks several column tiles.
+    const int mt = p.M <= 32 ? 2 : (p.M <= 64 ? 4 : 5);
+    const int mblocks = (p.M + 16 * mt - 1) / (16 * mt);
+    int cap = 512 / (mblocks * groups);
+    cap = cap < 64 ? 64 : cap;
+    if (mt == 2) launch_skinny_cfg<2, 1, false, false, 4, 8, 2>(ctx, p, e, none, nullptr, nullptr, groups, cap);
+    else if (mt == 4) launch_skinny_cfg<4, 1, false, false, 4, 8, 2>(ctx, p, e, none, nullptr, nullptr, groups, cap);
+    else launch_skinny_cfg<5, 1, false, false, 4, 8, 2>(ctx, p, e, none, nullptr, nullptr, groups, cap);
   } else if (p.K % 64 == 0) {
     dispatch_ldsx<false>(p, e, nullptr, nullptr, groups, s);
   } else {
