@@ -114,6 +114,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-batch32", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch a plain 256 MiB copy kernel a few times (reference for rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE scaling)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every box here has one); "
@@ -126,6 +129,14 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+
+    if args.copy_calibration:
+        a = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")      # 256 MiB
+        b = torch.empty_like(a)
+        for _ in range(5):
+            torch.mul(a, 1.0, out=b)          # one elementwise kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del a, b
 
     cfg1, cfg32 = wl.C2, wl.C3
     weights = wl.make_weights(cfg1)
@@ -148,8 +159,15 @@ def main():
         ms = profile_phase(ctx, phase, cfg1, src, n, max_len, sched, k, min(args.steps, 60), torch)
         kern[name] = {"ms": ms, "GBps": nbytes[name] / ms / 1e6}
     dom = max(("head_hidden", "head_out", "vocab"), key=lambda q: kern[q]["ms"])
+    # HBM bytes per launch of that kernel measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by
+    # a copy kernel of known size); recorded by hand from the runs summarised under profiles/
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("C2", {}).get(dom)
     roofline = {"bound": "hbm", "kernel": dom, "achieved": kern[dom]["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": kern[dom]["GBps"] / HBM_PEAK_GBS, "traffic": None,
+                "frac": kern[dom]["GBps"] / HBM_PEAK_GBS, "traffic": traffic,
                 "step_achieved": total_bytes / (ms_step * 1e6), "step_frac": total_bytes / (ms_step * 1e6) / HBM_PEAK_GBS,
                 "kernels": kern}
 
