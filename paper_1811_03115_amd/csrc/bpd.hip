@@ -315,6 +315,8 @@ void dispatch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float
     BPD_CASE(8) BPD_CASE(7) BPD_CASE(5) BPD_CASE(4) BPD_CASE(2)
 #undef BPD_CASE
   }
+  // big tiles: chunks of 128 keep twice the weight fragments in flight per wave
+  if (nt == 4 && mt == 8 && p.K % 128 == 0) { launch_ldsx<8, 4, 128, ARGMAX>(p, e, keys, logits, groups, s); return; }
 #define BPD_CASE(MT_, NT_) if (mt == MT_ && nt == NT_) { launch_ldsx<MT_, NT_, 64, ARGMAX>(p, e, keys, logits, groups, s); return; }
   BPD_CASE(8, 4) BPD_CASE(8, 2) BPD_CASE(8, 1)
   BPD_CASE(7, 4) BPD_CASE(7, 2) BPD_CASE(7, 1)

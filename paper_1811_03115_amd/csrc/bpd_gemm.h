@@ -341,8 +341,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (MT * NT
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = blockIdx.z;
   const int ntiles = p.N >> 4, ksteps = p.K >> 5, nchunks = p.K / KC;
-  const int m0 = blockIdx.y * BM;
-  const int nt0 = (blockIdx.x * 4 + wave) * NT;
+  // Workgroups are handed to the 8 XCDs round-robin in launch order and each XCD has its own L2.
+  // Remap so that an XCD owns column blocks (weights) congruent to its index and sweeps the row
+  // blocks fastest: a weight block is then fetched from memory once instead of once per row block.
+  int bx = blockIdx.x, by = blockIdx.y;
+  {
+    const int NB = gridDim.x, MB = gridDim.y, L = blockIdx.x + NB * blockIdx.y;
+    if ((NB & 7) == 0) { const int j = L >> 3; by = j % MB; bx = (L & 7) + 8 * (j / MB); }
+    else { by = L % MB; bx = L / MB; }
+  }
+  const int m0 = by * BM;
+  const int nt0 = (bx * 4 + wave) * NT;
   const int lr = lane & 15, lq = lane >> 4;
   const bf16_t* X = (const bf16_t*)p.X + g * p.x_g;
   const bf16_t* W = (const bf16_t*)p.W + g * p.w_g;
