@@ -14,6 +14,7 @@
 namespace {
 
 constexpr size_t ALIGN = 256;
+constexpr int ATTN_PART_SLOTS = 512;   // workgroups of one split attention launch (partial-result slots)
 
 struct Arena {
   char* base;
@@ -40,7 +41,7 @@ struct Layout {
   // caches
   void *selfK, *selfV, *crossK, *crossV;        // [n_dec][B][slots|max_src][d]
   // decoder activations (M = max_batch * k_max rows)
-  float *x, *q, *h, *stats_ln, *zeros; size_t n_zeros; void *xn, *attn, *ffh, *hn, *H, *O;
+  float *x, *q, *h, *stats_ln, *zeros, *attn_part; size_t n_zeros; void *xn, *attn, *ffh, *hn, *H, *O;
   unsigned long long* keys;
   // encoder activations (max_batch * max_src rows)
   float *xe, *qe; void *xen, *ke, *ve, *attne, *ffhe, *mem;
@@ -99,6 +100,7 @@ size_t build_layout(const bpd_config& c, char* base, Layout& L) {
   L.x = vec(M * d); L.q = vec(M * d); L.h = vec(M * d); L.stats_ln = vec(64 * 16 * 2);
   L.n_zeros = k * F; if (V > L.n_zeros) L.n_zeros = V; if (3 * d > L.n_zeros) L.n_zeros = 3 * d;
   L.zeros = vec(L.n_zeros);
+  L.attn_part = vec((size_t)ATTN_PART_SLOTS * 16 * (d / c.n_heads + 2));
   L.xn = a.take(M * d * as); L.attn = a.take(M * d * as); L.ffh = a.take(M * F * as);
   L.hn = a.take(M * d * as); L.H = a.take(M * k * F * as); L.O = a.take(M * k * d * as);
   L.keys = (unsigned long long*)a.take(M * k * 8);
@@ -315,8 +317,6 @@ void dispatch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float
     BPD_CASE(8) BPD_CASE(7) BPD_CASE(5) BPD_CASE(4) BPD_CASE(2)
 #undef BPD_CASE
   }
-  // big tiles: chunks of 128 keep twice the weight fragments in flight per wave
-  if (nt == 4 && mt == 8 && p.K % 128 == 0) { launch_ldsx<8, 4, 128, ARGMAX>(p, e, keys, logits, groups, s); return; }
 #define BPD_CASE(MT_, NT_) if (mt == MT_ && nt == NT_) { launch_ldsx<MT_, NT_, 64, ARGMAX>(p, e, keys, logits, groups, s); return; }
   BPD_CASE(8, 4) BPD_CASE(8, 2) BPD_CASE(8, 1)
   BPD_CASE(7, 4) BPD_CASE(7, 2) BPD_CASE(7, 1)
@@ -424,12 +424,28 @@ void attention(bpd_ctx* ctx, const float* Q, const void* Kc, const void* Vc, voi
   AttnP p{};
   p.Q = Q; p.Kc = Kc; p.Vc = Vc; p.out = out; p.kv_seq_stride = kv_seq_stride; p.cap = cap; p.d = c.d_model; p.R = R;
   p.limit = limit; p.causal = causal; p.scale = 1.0f / sqrtf((float)dh);
-  dim3 grid(c.n_heads, B, (R + 15) / 16);
+  // Few (head, sequence) pairs over a long cache: deal the 256-key chunks to several workgroups
+  // and merge their partial softmax results in a second kernel.
+  const int tiles = (R + 15) / 16, chunks = (cap + 255) / 256, wgs = c.n_heads * B * tiles;
+  int nsplit = 1;
+  if (chunks >= 3 && wgs * 2 <= ATTN_PART_SLOTS) {
+    nsplit = ATTN_PART_SLOTS / wgs;
+    if (nsplit > chunks) nsplit = chunks;
+    if (nsplit > 16) nsplit = 16;
+  }
+  p.nsplit = nsplit; p.part = ctx->lay.attn_part;
+  dim3 grid(c.n_heads, B, tiles * nsplit), cgrid(c.n_heads, B, tiles);
   if (c.dtype == BPD_BF16) {
-    if (dh == 64) hipLaunchKernelGGL((attention_kernel<bf16_t, 64>), grid, dim3(256), 0, ctx->stream, p);
-    else hipLaunchKernelGGL((attention_kernel<bf16_t, 16>), grid, dim3(256), 0, ctx->stream, p);
+    if (dh == 64) {
+      hipLaunchKernelGGL((attention_kernel<bf16_t, 64>), grid, dim3(256), 0, ctx->stream, p);
+      if (nsplit > 1) hipLaunchKernelGGL((attention_combine_kernel<bf16_t, 64>), cgrid, dim3(256), 0, ctx->stream, p);
+    } else {
+      hipLaunchKernelGGL((attention_kernel<bf16_t, 16>), grid, dim3(256), 0, ctx->stream, p);
+      if (nsplit > 1) hipLaunchKernelGGL((attention_combine_kernel<bf16_t, 16>), cgrid, dim3(256), 0, ctx->stream, p);
+    }
   } else {
     hipLaunchKernelGGL((attention_kernel<float, 16>), grid, dim3(256), 0, ctx->stream, p);
+    if (nsplit > 1) hipLaunchKernelGGL((attention_combine_kernel<float, 16>), cgrid, dim3(256), 0, ctx->stream, p);
   }
 }
 

@@ -330,8 +330,18 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
 // rows cannot be padded; instead the 16-byte segment index within a row is XOR-ed with
 // (row & 7), which spreads the MFMA operand reads of a wave evenly over the LDS banks.
 // Requires K % KC == 0, KC % 64 == 0.  Dynamic LDS: 2 * XI * 4096 bytes.
+// Two workgroups share a CU whenever the accumulators (4*MT*NT registers), the two weight chunks
+// (8*NT*KC/32) and the operand fragments (4*MT) leave room for it in half the register file: the
+// second wave per SIMD covers the LDS and memory latencies of the first.
+template <int MT, int NT, int KC>
+constexpr int ldsx_regs() { return 4 * MT * NT + 8 * NT * (KC / 32) + 4 * MT + 40; }
+template <int MT, int NT, int KC>
+constexpr int ldsx_waves_min() { return ldsx_regs<MT, NT, KC>() <= 272 ? 2 : 1; }
+template <int MT, int NT, int KC>
+constexpr int ldsx_waves_max() { return ldsx_regs<MT, NT, KC>() <= 168 ? 4 : ldsx_waves_min<MT, NT, KC>(); }
+
 template <int MT, int NT, int KC, bool ARGMAX>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, (MT * NT >= 16 ? 1 : 2)))) void gemm_ldsx_kernel(GemmP p, Epi e, unsigned long long* keys, float* logits) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_min<MT, NT, KC>(), ldsx_waves_max<MT, NT, KC>()))) void gemm_ldsx_kernel(GemmP p, Epi e, unsigned long long* keys, float* logits) {
   constexpr int BM = 16 * MT, KS = KC / 32, SEG = KC / 8;
   constexpr int XI = (BM * SEG + 255) / 256;       // direct-to-LDS loads per thread per chunk
   constexpr int BUF = XI * 256 * 8;                // bf16 elements per buffer (whole wave-loads)

@@ -483,8 +483,13 @@ struct AttnP {
   const int* limit;       // [B]: base (causal) or len (non-causal)
   int causal;
   float scale;
+  int nsplit;             // key chunks are dealt round-robin to nsplit workgroups per (head, sequence, row tile)
+  float* part;            // nsplit > 1: partial results [b][h][tile][split][16*DH acc | 16 max | 16 sum]
 };
 
+// With nsplit == 1 the kernel writes the attention output.  With nsplit > 1 (long caches, few
+// sequences) every workgroup leaves its running maximum, sum and un-normalised weighted values
+// in p.part and attention_combine_kernel merges them.
 template <typename ACT, int DH>
 __global__ __launch_bounds__(256) void attention_kernel(AttnP p) {
   constexpr int RT = 16, CH = 256, G = 256 / DH, KPG = CH / G, SLD = CH + 4;
@@ -492,7 +497,9 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnP p) {
   __shared__ __attribute__((aligned(16))) float sc[RT][SLD];
   __shared__ __attribute__((aligned(16))) ACT vs[CH][DH];
   __shared__ float m_s[RT], l_s[RT], alpha_s[RT];
-  const int h = blockIdx.x, b = blockIdx.y, r0 = blockIdx.z * RT;
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int split = blockIdx.z % p.nsplit, tile = blockIdx.z / p.nsplit, r0 = tile * RT;
+  const int first = split * CH, hop = p.nsplit * CH;
   const int nrows = min(RT, p.R - r0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const ACT* Kb = (const ACT*)p.Kc + b * p.kv_seq_stride + h * DH;
@@ -501,7 +508,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnP p) {
   constexpr int VW = DH * sizeof(ACT) / 16;               // 16-byte words per row
   uint4 kraw[VW], vraw[VW];
   {
-    const int key = tid < p.cap ? tid : p.cap - 1;         // independent of the length: no second round trip
+    const int key = first + tid < p.cap ? first + tid : p.cap - 1;   // independent of the length: no second round trip
     const uint4* kp = (const uint4*)(Kb + (long)key * p.d);
     const uint4* vp = (const uint4*)(Vb + (long)key * p.d);
 #pragma unroll
@@ -536,9 +543,9 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnP p) {
   for (int i = 0; i < RT; ++i) acc[i] = 0.f;
   const int g = tid / DH, c = tid % DH;
   __syncthreads();
-  for (int c0 = 0; c0 < nkeys; c0 += CH) {
+  for (int c0 = first; c0 < nkeys; c0 += hop) {
     const int key = c0 + tid;
-    if (c0 > 0) {
+    if (c0 != first) {
       const int kk = key < nkeys ? key : 0;
       const uint4* kp = (const uint4*)(Kb + (long)kk * p.d);
       const uint4* vp = (const uint4*)(Vb + (long)kk * p.d);
@@ -619,11 +626,55 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnP p) {
 #pragma unroll
   for (int i = 0; i < RT; ++i) red[(g * RT + i) * DH + c] = acc[i];
   __syncthreads();
-  for (int idx = tid; idx < nrows * DH; idx += 256) {
+  if (p.nsplit == 1) {
+    for (int idx = tid; idx < nrows * DH; idx += 256) {
+      const int i = idx / DH, cc = idx % DH;
+      float s = 0.f;
+      for (int gg = 0; gg < G; ++gg) s += red[(gg * RT + i) * DH + cc];
+      ((ACT*)p.out)[((long)b * p.R + r0 + i) * p.d + h * DH + cc] = from_f<ACT>(s / l_s[i]);
+    }
+  } else {
+    const int tiles = gridDim.z / p.nsplit;
+    float* part = p.part + ((((long)b * gridDim.x + h) * tiles + tile) * p.nsplit + split) * (RT * (DH + 2));
+    for (int idx = tid; idx < RT * DH; idx += 256) {
+      const int i = idx / DH, cc = idx % DH;
+      float s = 0.f;
+      for (int gg = 0; gg < G; ++gg) s += red[(gg * RT + i) * DH + cc];
+      part[idx] = s;
+    }
+    if (tid < RT) { part[RT * DH + tid] = m_s[tid]; part[RT * DH + RT + tid] = l_s[tid]; }
+  }
+}
+
+// Merge of the nsplit partial results of attention_kernel: with M the largest of the partial
+// maxima, output = sum_s acc_s e^(m_s - M) / sum_s l_s e^(m_s - M).  Grid (heads, B, row tiles).
+template <typename ACT, int DH>
+__global__ __launch_bounds__(256) void attention_combine_kernel(AttnP p) {
+  constexpr int RT = 16, PS = RT * (DH + 2), NS = 16;
+  const int h = blockIdx.x, b = blockIdx.y, tile = blockIdx.z, r0 = tile * RT;
+  const int nrows = min(RT, p.R - r0);
+  const float* part = p.part + (((long)b * gridDim.x + h) * gridDim.z + tile) * p.nsplit * PS;
+  for (int idx = threadIdx.x; idx < nrows * DH; idx += 256) {
     const int i = idx / DH, cc = idx % DH;
-    float s = 0.f;
-    for (int gg = 0; gg < G; ++gg) s += red[(gg * RT + i) * DH + cc];
-    ((ACT*)p.out)[((long)b * p.R + r0 + i) * p.d + h * DH + cc] = from_f<ACT>(s / l_s[i]);
+    float m[NS], l[NS], a[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const int ss = s < p.nsplit ? s : 0;                 // unconditional loads, unused ones masked below
+      m[s] = part[ss * PS + RT * DH + i];
+      l[s] = part[ss * PS + RT * DH + RT + i];
+      a[s] = part[ss * PS + idx];
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) mx = fmaxf(mx, s < p.nsplit ? m[s] : -INFINITY);
+    float num = 0.f, den = 0.f;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      const float w = (s < p.nsplit && m[s] != -INFINITY) ? __expf(m[s] - mx) : 0.f;
+      num = fmaf(a[s], w, num);
+      den = fmaf(l[s], w, den);
+    }
+    ((ACT*)p.out)[((long)b * p.R + r0 + i) * p.d + h * DH + cc] = from_f<ACT>(num / den);
   }
 }
 
