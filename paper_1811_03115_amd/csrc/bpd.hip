@@ -14,6 +14,7 @@
 namespace {
 
 constexpr size_t ALIGN = 256;
+constexpr int KSPLIT_MAX = 16;          // K slices of a split-K GEMM
 constexpr int ATTN_PART_SLOTS = 512;   // workgroups of one split attention launch (partial-result slots)
 
 struct Arena {
@@ -41,7 +42,7 @@ struct Layout {
   // caches
   void *selfK, *selfV, *crossK, *crossV;        // [n_dec][B][slots|max_src][d]
   // decoder activations (M = max_batch * k_max rows)
-  float *x, *q, *h, *stats_ln, *zeros, *attn_part; size_t n_zeros; void *xn, *attn, *ffh, *hn, *H, *O;
+  float *x, *q, *h, *stats_ln, *zeros, *attn_part, *kpart; size_t n_zeros, n_kpart; void *xn, *attn, *ffh, *hn, *H, *O;
   unsigned long long* keys;
   // encoder activations (max_batch * max_src rows)
   float *xe, *qe; void *xen, *ke, *ve, *attne, *ffhe, *mem;
@@ -101,6 +102,8 @@ size_t build_layout(const bpd_config& c, char* base, Layout& L) {
   L.n_zeros = k * F; if (V > L.n_zeros) L.n_zeros = V; if (3 * d > L.n_zeros) L.n_zeros = 3 * d;
   L.zeros = vec(L.n_zeros);
   L.attn_part = vec((size_t)ATTN_PART_SLOTS * 16 * (d / c.n_heads + 2));
+  L.n_kpart = (size_t)KSPLIT_MAX * M * d;      // K slices of one residual update of the decoder block
+  L.kpart = vec(L.n_kpart);
   L.xn = a.take(M * d * as); L.attn = a.take(M * d * as); L.ffh = a.take(M * F * as);
   L.hn = a.take(M * d * as); L.H = a.take(M * k * F * as); L.O = a.take(M * k * d * as);
   L.keys = (unsigned long long*)a.take(M * k * 8);
@@ -148,6 +151,8 @@ struct bpd_ctx {
   std::vector<hipEvent_t> prof_ev;
   size_t prof_used = 0;
   int64_t prof_launches = 0;
+  // a split-K residual update whose slices the next LayerNorm of `pend_x` still has to add
+  int pend_slices = 0; const float* pend_bias = nullptr; const float* pend_x = nullptr;
 };
 
 namespace {
@@ -309,10 +314,11 @@ int pick_nt(int M, int N, int mt, int groups) {
 
 template <bool ARGMAX>
 void dispatch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* logits, int groups, hipStream_t s) {
-  const int mt = pick_mt(p.M), nt = pick_nt(p.M, p.N, mt, groups);
+  const int mt = pick_mt(p.M), nt = p.ksplit > 1 ? 1 : pick_nt(p.M, p.N, mt, groups);
+  const int kslice = p.ksplit > 1 ? p.K / p.ksplit : p.K;
   // long K with one column tile per wave: little work per 64-wide chunk, so walk K in chunks of
   // 256 (fewer barriers, 8 weight fragments per wave in flight)
-  if (nt == 1 && p.K >= 2048 && p.K % 256 == 0) {
+  if (nt == 1 && (p.K >= 2048 || p.ksplit > 1) && kslice % 256 == 0) {
 #define BPD_CASE(MT_) if (mt == MT_) { launch_ldsx<MT_, 1, 256, ARGMAX>(p, e, keys, logits, groups, s); return; }
     BPD_CASE(8) BPD_CASE(7) BPD_CASE(5) BPD_CASE(4) BPD_CASE(2)
 #undef BPD_CASE
@@ -350,6 +356,23 @@ void gemm(bpd_ctx* ctx, const GemmP& p, const Epi& e, int groups = 1) {
     else if (mt == 4) launch_skinny_cfg<4, 1, false, false, 4, 8, 2>(ctx, p, e, none, nullptr, nullptr, groups, cap);
     else launch_skinny_cfg<5, 1, false, false, 4, 8, 2>(ctx, p, e, none, nullptr, nullptr, groups, cap);
   } else if (p.K % 64 == 0) {
+    // In-place residual update with a long K and few output tiles: split K over workgroups.  The
+    // slices are added, in a fixed order, by the LayerNorm kernel that reads the residual next.
+    if (groups == 1 && e.mode == 0 && e.R && e.R == e.Yf && !e.Ya && !e.relu && !e.stats_out && !e.lnR_stats &&
+        e.ldr == p.N && e.ldyf == p.N && p.N == ctx->cfg.d_model && p.K >= 2048) {
+      const int mt = pick_mt(p.M);
+      const long tiles = (long)((p.M + 16 * mt - 1) / (16 * mt)) * ((p.N + 63) / 64);
+      int ns = 1;
+      while (ns * 2 <= KSPLIT_MAX && tiles * ns * 2 <= 512 && p.K % (ns * 2 * 64) == 0 && p.K / (ns * 2) >= 128 &&
+             (size_t)ns * 2 * p.M * p.N <= ctx->lay.n_kpart) ns *= 2;
+      if (ns > 1) {
+        GemmP q = p;
+        q.ksplit = ns; q.part = ctx->lay.kpart;
+        dispatch_ldsx<false>(q, e, nullptr, nullptr, ns, s);
+        ctx->pend_slices = ns; ctx->pend_bias = e.bias ? e.bias : ctx->lay.zeros; ctx->pend_x = e.Yf;
+        return;
+      }
+    }
     dispatch_ldsx<false>(p, e, nullptr, nullptr, groups, s);
   } else {
     if (p.M > 64) launch_gemm_bf16<8, 1, 4>(p, e, groups, s);
@@ -357,12 +380,12 @@ void gemm(bpd_ctx* ctx, const GemmP& p, const Epi& e, int groups = 1) {
   }
 }
 
-void layernorm(bpd_ctx* ctx, const float* x, LnW w, int M, void* ya, float* yf);
+void layernorm(bpd_ctx* ctx, float* x, LnW w, int M, void* ya, float* yf);
 
 // Y = epilogue(LayerNorm(x) W).  Block of <= 16 rows: LayerNorm is applied inside the skinny
 // kernel from the partial statistics the producer of x left in L.stats_ln.  Otherwise a
 // LayerNorm kernel (into `xn`, and `yf` in fp32 if given) followed by the GEMM.
-void gemm_ln(bpd_ctx* ctx, const float* x, LnW w, void* xn, float* yf, GemmP p, const Epi& e) {
+void gemm_ln(bpd_ctx* ctx, float* x, LnW w, void* xn, float* yf, GemmP p, const Epi& e) {
   if (stats_path(ctx, p.M) && p.K == ctx->cfg.d_model) {
     LnP ln{x, w.g, w.b, ctx->lay.stats_ln, ctx->cfg.ln_eps};
     if (p.N / 16 >= 2048) launch_skinny<2, true, false>(ctx, p, e, ln, nullptr, nullptr, 1);
@@ -407,13 +430,20 @@ Epi split(float* Qf, void* Ka, void* Va, int dsplit, int chunk0, int rows_per_se
   return e;
 }
 
-void layernorm(bpd_ctx* ctx, const float* x, LnW w, int M, void* ya, float* yf) {
+void layernorm(bpd_ctx* ctx, float* x, LnW w, int M, void* ya, float* yf) {
   const int d = ctx->cfg.d_model;
   dim3 grid((M + 3) / 4);
-  if (ctx->cfg.dtype == BPD_BF16)
-    hipLaunchKernelGGL(layernorm_kernel<bf16_t>, grid, dim3(256), 0, ctx->stream, x, w.g, w.b, M, d, ctx->cfg.ln_eps, (bf16_t*)ya, yf);
-  else
-    hipLaunchKernelGGL(layernorm_kernel<float>, grid, dim3(256), 0, ctx->stream, x, w.g, w.b, M, d, ctx->cfg.ln_eps, (float*)ya, yf);
+  int nsl = 0;
+  const float* bias = nullptr;
+  if (ctx->pend_slices && ctx->pend_x == x) { nsl = ctx->pend_slices; bias = ctx->pend_bias; ctx->pend_slices = 0; }
+#define BPD_LN(ACT_, V_) hipLaunchKernelGGL((layernorm_kernel<ACT_, V_>), grid, dim3(256), 0, ctx->stream, x, w.g, w.b, M, d, \
+                                            ctx->cfg.ln_eps, (ACT_*)ya, yf, (const float*)ctx->lay.kpart, nsl, bias)
+  if (ctx->cfg.dtype == BPD_BF16) {
+    if (d <= 1024) BPD_LN(bf16_t, 4); else BPD_LN(bf16_t, LN_V);
+  } else {
+    if (d <= 1024) BPD_LN(float, 4); else BPD_LN(float, LN_V);
+  }
+#undef BPD_LN
 }
 
 void attention(bpd_ctx* ctx, const float* Q, const void* Kc, const void* Vc, void* out, int cap,
@@ -560,6 +590,7 @@ int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
     }
   }
   LAUNCHCHK();
+  if (ctx->pend_slices) return fail(ctx, BPD_E_STATE, "split-K slices were left unreduced");
   return BPD_OK;
 }
 

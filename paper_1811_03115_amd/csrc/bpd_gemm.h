@@ -349,8 +349,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
   bf16_t* xs0 = (bf16_t*)smem_raw;
   bf16_t* xs1 = xs0 + BUF;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int g = blockIdx.z;
-  const int ntiles = p.N >> 4, ksteps = p.K >> 5, nchunks = p.K / KC;
+  const int g = p.ksplit > 1 ? 0 : blockIdx.z;
+  const int ntiles = p.N >> 4, ksteps = p.K >> 5;
+  const int nchunks = p.K / KC / (p.ksplit > 1 ? p.ksplit : 1);      // chunks of this K slice
+  const int cbase = p.ksplit > 1 ? blockIdx.z * nchunks : 0;
   // Workgroups are handed to the 8 XCDs round-robin in launch order and each XCD has its own L2.
   // Remap so that an XCD owns column blocks (weights) congruent to its index and sweeps the row
   // blocks fastest: a weight block is then fetched from memory once instead of once per row block.
@@ -395,14 +397,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
 #pragma unroll
   for (int s = 0; s < KS; ++s)
 #pragma unroll
-    for (int u = 0; u < NT; ++u) a_cur[s][u] = wt[u][(long)s * 64];
-  BPD_X_TO_LDS(xs0, 0)
+    for (int u = 0; u < NT; ++u) a_cur[s][u] = wt[u][(long)(cbase * KS + s) * 64];
+  BPD_X_TO_LDS(xs0, cbase)
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
   for (int c = 0; c < nchunks; ++c) {
     // next chunk in flight while this one is multiplied (the last iteration re-requests its own
     // chunk so that the code stays branch-free)
-    const int cn = c + 1 < nchunks ? c + 1 : c;
+    const int cn = cbase + (c + 1 < nchunks ? c + 1 : c);
     bf16_t* xn = (c & 1) ? xs0 : xs1;
     BPD_X_TO_LDS(xn, cn)
 #pragma unroll
@@ -466,5 +468,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
     return;
   }
   if (nt0 >= ntiles) return;
+  if (p.ksplit > 1) {
+    float* part = p.part + (long)blockIdx.z * p.M * p.N;
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+      const int m = m0 + t * 16 + lr;
+      if (m >= p.M) continue;
+#pragma unroll
+      for (int u = 0; u < NT; ++u) {
+        if (nt0 + u >= ntiles) continue;
+        *(float4*)(part + (long)m * p.N + (nt0 + u) * 16 + lq * 4) = make_float4(acc[t][u][0], acc[t][u][1], acc[t][u][2], acc[t][u][3]);
+      }
+    }
+    return;
+  }
   store_tiles<MT, NT>(e, g, acc, m0, nt0, ntiles, p.M, lane);
 }

@@ -93,6 +93,9 @@ struct GemmP {
   const void* W; long w_g;             // bf16: packed tiles;  fp32: row-major [K][ldw]
   int ldw;
   int M, N, K;
+  // split-K (gemm_ldsx_kernel, one group): blockIdx.z = slice of K; the raw fp32 product of slice z
+  // goes to part + z*M*N and the consumer (layernorm_kernel) adds the slices in index order
+  int ksplit; float* part;
 };
 
 // ---------------------------------------------------------------------------------------
@@ -378,40 +381,81 @@ __global__ __launch_bounds__(64) void embed_stats_kernel(const int* tok, int tok
 
 // LayerNorm over the last axis, one wavefront per row (biased variance, two passes over
 // registers).  The row is fetched with one batch of loads; d <= 64 * 4 * LN_V.
+// If the producer of x was a split-K GEMM (nsl > 0 slices of the product in `part`, slice s at
+// part + s*M*d), the row is first completed, x += bias + part[0] + part[1] + ... in that order,
+// and written back.
 constexpr int LN_V = 8;
-template <typename ACT>
-__global__ __launch_bounds__(256) void layernorm_kernel(const float* x, const float* g, const float* b, int M,
-                                                        int d, float eps, ACT* ya, float* yf) {
+template <typename ACT, int V>
+__global__ __launch_bounds__(256) void layernorm_kernel(float* x, const float* g, const float* b, int M,
+                                                        int d, float eps, ACT* ya, float* yf,
+                                                        const float* part, int nsl, const float* pbias) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (row >= M) return;
-  const float* xr = x + (long)row * d;
+  float* xr = x + (long)row * d;
   const int nv = d >> 2;                         // float4 per row
-  float4 v[LN_V], gg[LN_V], bb[LN_V];
+  float4 v[V], gg[V], bb[V];
 #pragma unroll
-  for (int i = 0; i < LN_V; ++i) {
+  for (int i = 0; i < V; ++i) {
     const int c4 = lane + 64 * i;
     const int cc = c4 < nv ? c4 : 0;
     v[i] = ((const float4*)xr)[cc]; gg[i] = ((const float4*)g)[cc]; bb[i] = ((const float4*)b)[cc];
   }
+  if (nsl > 0) {
+    float4 pb[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      const int c4 = lane + 64 * i;
+      pb[i] = ((const float4*)pbias)[c4 < nv ? c4 : 0];
+    }
+#pragma unroll
+    for (int i = 0; i < V; ++i) { v[i].x += pb[i].x; v[i].y += pb[i].y; v[i].z += pb[i].z; v[i].w += pb[i].w; }
+    for (int s0 = 0; s0 < nsl; s0 += 4) {       // four slices per batch of loads
+      float4 q[4][V];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int sl = s0 + j < nsl ? s0 + j : nsl - 1;
+        const float4* pr = (const float4*)(part + ((long)sl * M + row) * d);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          const int c4 = lane + 64 * i;
+          q[j][i] = pr[c4 < nv ? c4 : 0];
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float w = s0 + j < nsl ? 1.f : 0.f;
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          v[i].x = fmaf(w, q[j][i].x, v[i].x); v[i].y = fmaf(w, q[j][i].y, v[i].y);
+          v[i].z = fmaf(w, q[j][i].z, v[i].z); v[i].w = fmaf(w, q[j][i].w, v[i].w);
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+      const int c4 = lane + 64 * i;
+      if (c4 < nv) ((float4*)xr)[c4] = v[i];
+    }
+  }
   __builtin_amdgcn_sched_barrier(0);
   float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < LN_V; ++i) {
+  for (int i = 0; i < V; ++i) {
     const float w = (lane + 64 * i) < nv ? 1.f : 0.f;
     s += w * ((v[i].x + v[i].y) + (v[i].z + v[i].w));
   }
   const float mu = wave_sum(s) / d;
   float q = 0.f;
 #pragma unroll
-  for (int i = 0; i < LN_V; ++i) {
+  for (int i = 0; i < V; ++i) {
     const float w = (lane + 64 * i) < nv ? 1.f : 0.f;
     const float a0 = v[i].x - mu, a1 = v[i].y - mu, a2 = v[i].z - mu, a3 = v[i].w - mu;
     q += w * ((a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3));
   }
   const float rstd = 1.0f / sqrtf(wave_sum(q) / d + eps);
 #pragma unroll
-  for (int i = 0; i < LN_V; ++i) {
+  for (int i = 0; i < V; ++i) {
     const int c4 = lane + 64 * i;
     if (c4 < nv) {
       const float y0 = (v[i].x - mu) * rstd * gg[i].x + bb[i].x, y1 = (v[i].y - mu) * rstd * gg[i].y + bb[i].y;
