@@ -292,43 +292,40 @@ void launch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* 
   hipLaunchKernelGGL((gemm_ldsx_kernel<MT, NT, KC, ARGMAX>), grid, dim3(256), lds, s, p, e, keys, logits);
 }
 
-// Row-tile height: the one of {128, 112, 80, 64, 32} rows that pads M least (ties: taller).
-int pick_mt(int M) {
-  const int cands[5] = {8, 7, 5, 4, 2};
-  int best = 8; long best_pad = -1;
-  for (int mt : cands) {
-    const long bm = 16 * mt, padded = (M + bm - 1) / bm * bm;
-    if (best_pad < 0 || padded < best_pad) { best_pad = padded; best = mt; }
+// Tile of the LDS-staged GEMM: 16*mt rows x 64*nt columns per workgroup, K walked in chunks of
+// 256 / 128 / 64 for nt = 1 / 2 / 4 (eight weight fragments per wave in flight either way).
+// Chosen: the largest tile that still gives the chip about two workgroups per CU (counting K
+// slices and groups); ties go to less row padding, then to the narrower tile (longer chunks).
+// With nt = 1 at most 48 rows, so that the two 256-deep staging buffers leave room for three
+// workgroups per CU.  If nothing qualifies the smallest tile spreads the work furthest.
+constexpr long LDSX_MIN_WGS = 448;
+void pick_tile(int M, int N, int K, long zdim, bool argmax, int& mt, int& nt) {
+  const int mts[7] = {8, 7, 5, 4, 3, 2, 1};
+  long best_area = 0, best_pad = 0;
+  mt = 1; nt = (K % 256 == 0) ? 1 : 4;
+  for (int n : {1, 2, 4}) {
+    if (K % (256 / n) != 0) continue;
+    const long cols = (N / 16 + 4 * n - 1) / (4 * n);
+    for (int m : mts) {
+      if (n == 1 && m > 3) continue;
+      if (n == 4 && m == 8 && !argmax) continue;     // its epilogue does not fit the register budget
+      const long bm = 16 * m, mblocks = (M + bm - 1) / bm, pad = mblocks * bm;
+      if (mblocks * cols * zdim < LDSX_MIN_WGS) continue;
+      const long area = (long)m * n;
+      if (area > best_area || (area == best_area && pad < best_pad)) { best_area = area; best_pad = pad; mt = m; nt = n; }
+    }
   }
-  return best;
-}
-// Column tiles per wave: as many as still leave >= 256 workgroups (one per CU).
-int pick_nt(int M, int N, int mt, int groups) {
-  const long mblocks = (M + 16 * mt - 1) / (16 * mt);
-  for (int nt : {4, 2}) {
-    const long wgs = ((N / 16 + 4 * nt - 1) / (4 * nt)) * mblocks * groups;
-    if (wgs >= 256) return nt;
-  }
-  return 1;
 }
 
 template <bool ARGMAX>
 void dispatch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* logits, int groups, hipStream_t s) {
-  const int mt = pick_mt(p.M), nt = p.ksplit > 1 ? 1 : pick_nt(p.M, p.N, mt, groups);
+  int mt, nt;
   const int kslice = p.ksplit > 1 ? p.K / p.ksplit : p.K;
-  // long K with one column tile per wave: little work per 64-wide chunk, so walk K in chunks of
-  // 256 (fewer barriers, 8 weight fragments per wave in flight)
-  if (nt == 1 && (p.K >= 2048 || p.ksplit > 1) && kslice % 256 == 0) {
-#define BPD_CASE(MT_) if (mt == MT_) { launch_ldsx<MT_, 1, 256, ARGMAX>(p, e, keys, logits, groups, s); return; }
-    BPD_CASE(8) BPD_CASE(7) BPD_CASE(5) BPD_CASE(4) BPD_CASE(2)
-#undef BPD_CASE
-  }
-#define BPD_CASE(MT_, NT_) if (mt == MT_ && nt == NT_) { launch_ldsx<MT_, NT_, 64, ARGMAX>(p, e, keys, logits, groups, s); return; }
-  BPD_CASE(8, 4) BPD_CASE(8, 2) BPD_CASE(8, 1)
-  BPD_CASE(7, 4) BPD_CASE(7, 2) BPD_CASE(7, 1)
-  BPD_CASE(5, 4) BPD_CASE(5, 2) BPD_CASE(5, 1)
-  BPD_CASE(4, 4) BPD_CASE(4, 2) BPD_CASE(4, 1)
-  BPD_CASE(2, 4) BPD_CASE(2, 2) BPD_CASE(2, 1)
+  pick_tile(p.M, p.N, kslice, groups, ARGMAX, mt, nt);       // groups = K slices for a split-K launch
+#define BPD_CASE(MT_, NT_, KC_) if (mt == MT_ && nt == NT_) { launch_ldsx<MT_, NT_, KC_, ARGMAX>(p, e, keys, logits, groups, s); return; }
+  BPD_CASE(3, 1, 256) BPD_CASE(2, 1, 256) BPD_CASE(1, 1, 256)
+  BPD_CASE(8, 2, 128) BPD_CASE(7, 2, 128) BPD_CASE(5, 2, 128) BPD_CASE(4, 2, 128) BPD_CASE(3, 2, 128) BPD_CASE(2, 2, 128) BPD_CASE(1, 2, 128)
+  BPD_CASE(8, 4, 64) BPD_CASE(7, 4, 64) BPD_CASE(5, 4, 64) BPD_CASE(4, 4, 64) BPD_CASE(3, 4, 64) BPD_CASE(2, 4, 64) BPD_CASE(1, 4, 64)
 #undef BPD_CASE
 }
 
@@ -345,26 +342,22 @@ void gemm(bpd_ctx* ctx, const GemmP& p, const Epi& e, int groups = 1) {
   if (skinny_ok(ctx, p)) {
     if (p.N / 16 >= 2048) launch_skinny<2, false, false>(ctx, p, e, none, nullptr, nullptr, groups);
     else launch_skinny<1, false, false>(ctx, p, e, none, nullptr, nullptr, groups);
-  } else if (p.M <= 640 && p.K <= 1024) {
-    // a few row blocks: rows resident in registers, K split over the waves, no LDS staging.  Each
-    // workgroup pays for loading its row block once, so it walks several column tiles.
-    const int mt = p.M <= 32 ? 2 : (p.M <= 64 ? 4 : 5);
-    const int mblocks = (p.M + 16 * mt - 1) / (16 * mt);
-    int cap = 512 / (mblocks * groups);
-    cap = cap < 64 ? 64 : cap;
-    if (mt == 2) launch_skinny_cfg<2, 1, false, false, 4, 8, 2>(ctx, p, e, none, nullptr, nullptr, groups, cap);
-    else if (mt == 4) launch_skinny_cfg<4, 1, false, false, 4, 8, 2>(ctx, p, e, none, nullptr, nullptr, groups, cap);
-    else launch_skinny_cfg<5, 1, false, false, 4, 8, 2>(ctx, p, e, none, nullptr, nullptr, groups, cap);
   } else if (p.K % 64 == 0) {
     // In-place residual update with a long K and few output tiles: split K over workgroups.  The
     // slices are added, in a fixed order, by the LayerNorm kernel that reads the residual next.
     if (groups == 1 && e.mode == 0 && e.R && e.R == e.Yf && !e.Ya && !e.relu && !e.stats_out && !e.lnR_stats &&
         e.ldr == p.N && e.ldyf == p.N && p.N == ctx->cfg.d_model && p.K >= 2048) {
-      const int mt = pick_mt(p.M);
-      const long tiles = (long)((p.M + 16 * mt - 1) / (16 * mt)) * ((p.N + 63) / 64);
-      int ns = 1;
-      while (ns * 2 <= KSPLIT_MAX && tiles * ns * 2 <= 512 && p.K % (ns * 2 * 64) == 0 && p.K / (ns * 2) >= 128 &&
-             (size_t)ns * 2 * p.M * p.N <= ctx->lay.n_kpart) ns *= 2;
+      // fewest slices with which a tile of at least 48 rows still fills the chip; if no slicing gets
+      // there, the most slices allowed (each at least 256 deep)
+      int mt, nt, ns = 1;
+      pick_tile(p.M, p.N, p.K, 1, false, mt, nt);
+      if (nt == 1 && mt < 3) {
+        for (int t = 2; t <= KSPLIT_MAX && p.K % (t * 256) == 0 && (size_t)t * p.M * p.N <= ctx->lay.n_kpart; t *= 2) {
+          ns = t;
+          pick_tile(p.M, p.N, p.K / t, t, false, mt, nt);
+          if (nt > 1 || mt >= 3) break;
+        }
+      }
       if (ns > 1) {
         GemmP q = p;
         q.ksplit = ns; q.part = ctx->lay.kpart;
