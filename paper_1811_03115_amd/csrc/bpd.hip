@@ -460,7 +460,7 @@ void attention(bpd_ctx* ctx, const float* Q, const void* Kc, const void* Vc, voi
   dim3 grid(c.n_heads, B, tiles * nsplit), cgrid(c.n_heads, B, tiles);
   if (c.dtype == BPD_BF16) {
     if (dh == 64) {
-      hipLaunchKernelGGL((attention_kernel<bf16_t, 64>), grid, dim3(256), 0, ctx->stream, p);
+      hipLaunchKernelGGL(attention_mfma_kernel, grid, dim3(256), 0, ctx->stream, p);
       if (nsplit > 1) hipLaunchKernelGGL((attention_combine_kernel<bf16_t, 64>), cgrid, dim3(256), 0, ctx->stream, p);
     } else {
       hipLaunchKernelGGL((attention_kernel<bf16_t, 16>), grid, dim3(256), 0, ctx->stream, p);

@@ -690,6 +690,186 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnP p) {
   }
 }
 
+// bf16, 64-wide heads: the same computation on the matrix cores.  Per 256-key chunk
+//   scores^T = K Q^T     keys are the 16-wide "feature" side of the MFMA, the <= 16 query rows the
+//                        other; K fragments come straight from the cache (a key row is contiguous
+//                        along the contracted head dimension), wave w takes keys 64w .. 64w+63;
+//   softmax              running (max, sum) per row as in attention_kernel, probabilities in LDS;
+//   out^T  = V^T P^T     contracted over keys: wave w owns head dimensions 16w .. 16w+15 and gathers
+//                        its V^T fragments from the chunk of V rows staged in LDS (row stride 68
+//                        elements, so the four key groups of a fragment read disjoint banks).
+// fp32 operands (Q, the probabilities) are fed as a bf16 pair hi + lo, which keeps them to ~2^-17:
+// the result matches the scalar kernel to fp32 rounding.  Same arguments, grid and partial-result
+// layout as attention_kernel.
+__device__ __forceinline__ void split_bf16x8(const float (&v)[8], bf16x8& hi, bf16x8& lo) {
+  unsigned h[4], l[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const bf16_t h0 = f2bf(v[2 * j]), h1 = f2bf(v[2 * j + 1]);
+    const bf16_t l0 = f2bf(v[2 * j] - bf2f(h0)), l1 = f2bf(v[2 * j + 1] - bf2f(h1));
+    h[j] = (unsigned)h0 | ((unsigned)h1 << 16);
+    l[j] = (unsigned)l0 | ((unsigned)l1 << 16);
+  }
+  hi = __builtin_bit_cast(bf16x8, make_uint4(h[0], h[1], h[2], h[3]));
+  lo = __builtin_bit_cast(bf16x8, make_uint4(l[0], l[1], l[2], l[3]));
+}
+
+__global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p) {
+  constexpr int RT = 16, CH = 256, DH = 64, SLD = CH + 4, VLD = DH + 4;
+  __shared__ __attribute__((aligned(16))) float sc[RT][SLD];
+  __shared__ __attribute__((aligned(16))) bf16_t vs[CH][VLD];
+  __shared__ float m_s[RT], l_s[RT], alpha_s[RT];
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int split = blockIdx.z % p.nsplit, tile = blockIdx.z / p.nsplit, r0 = tile * RT;
+  const int first = split * CH, hop = p.nsplit * CH;
+  const int nrows = min(RT, p.R - r0);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 15, lq = lane >> 4;
+  const bf16_t* Kb = (const bf16_t*)p.Kc + b * p.kv_seq_stride + h * DH;
+  const bf16_t* Vb = (const bf16_t*)p.Vc + b * p.kv_seq_stride + h * DH;
+  // first chunk: K fragments (4 key tiles x 2 halves of the head dimension) and this thread's V row
+  uint4 kf[4][2], vraw[8];
+#define BPD_LOAD_KV(c0)                                                                         \
+  {                                                                                             \
+    _Pragma("unroll") for (int kt = 0; kt < 4; ++kt) {                                          \
+      int key = (c0) + wave * 64 + kt * 16 + lr;                                                \
+      key = key < p.cap ? key : p.cap - 1;                                                      \
+      const bf16_t* kp = Kb + (long)key * p.d + 8 * lq;                                         \
+      kf[kt][0] = *(const uint4*)kp; kf[kt][1] = *(const uint4*)(kp + 32);                      \
+    }                                                                                           \
+    int vkey = (c0) + tid;                                                                      \
+    vkey = vkey < p.cap ? vkey : p.cap - 1;                                                     \
+    const uint4* vp = (const uint4*)(Vb + (long)vkey * p.d);                                    \
+    _Pragma("unroll") for (int x = 0; x < 8; ++x) vraw[x] = vp[x];                              \
+  }
+  BPD_LOAD_KV(first)
+  // queries: row lr (clamped), head dimensions 32s + 8*lq .. +8, scaled, as bf16 hi + lo
+  bf16x8 qhi[2], qlo[2];
+  {
+    const int row = r0 + (lr < nrows ? lr : nrows - 1);
+    const float* qp = p.Q + ((long)b * p.R + row) * p.d + h * DH + 8 * lq;
+    float4 qa[2][2];
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) { qa[s2][0] = *(const float4*)(qp + 32 * s2); qa[s2][1] = *(const float4*)(qp + 32 * s2 + 4); }
+    int lim0 = p.limit[b];
+    __builtin_amdgcn_sched_barrier(0);            // every global load above is in flight before the first wait
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      const float v[8] = {qa[s2][0].x * p.scale, qa[s2][0].y * p.scale, qa[s2][0].z * p.scale, qa[s2][0].w * p.scale,
+                          qa[s2][1].x * p.scale, qa[s2][1].y * p.scale, qa[s2][1].z * p.scale, qa[s2][1].w * p.scale};
+      split_bf16x8(v, qhi[s2], qlo[s2]);
+    }
+    (void)lim0;
+  }
+  int lim = p.limit[b];
+  lim = lim < 0 ? 0 : lim;
+  int nkeys = p.causal ? lim + r0 + nrows : lim;
+  nkeys = nkeys < p.cap ? nkeys : p.cap;
+  const int nvis = lr < nrows ? (p.causal ? lim + r0 + lr + 1 : lim) : 0;     // keys row lr may see
+  if (tid < RT) { m_s[tid] = -INFINITY; l_s[tid] = 0.f; alpha_s[tid] = 1.f; }
+  f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};         // out^T: head dimensions 16*wave + 4*lq + r, row lr
+  __syncthreads();
+  for (int c0 = first; c0 < nkeys; c0 += hop) {
+    if (c0 != first) BPD_LOAD_KV(c0)
+    // scores of this wave's 64 keys
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) {
+      f32x4 sacc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const bf16x8 ka = __builtin_bit_cast(bf16x8, kf[kt][s2]);
+        sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qhi[s2], sacc, 0, 0, 0);
+        sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qlo[s2], sacc, 0, 0, 0);
+      }
+      const int kl = wave * 64 + kt * 16 + 4 * lq;           // chunk-local index of the first of 4 keys
+      float4 o;
+      o.x = c0 + kl + 0 < nvis ? sacc[0] : -INFINITY;
+      o.y = c0 + kl + 1 < nvis ? sacc[1] : -INFINITY;
+      o.z = c0 + kl + 2 < nvis ? sacc[2] : -INFINITY;
+      o.w = c0 + kl + 3 < nvis ? sacc[3] : -INFINITY;
+      *(float4*)&sc[lr][kl] = o;
+    }
+    {
+      const bool live = c0 + tid < nkeys;
+#pragma unroll
+      for (int x = 0; x < 8; ++x) {
+        const uint4 v = live ? vraw[x] : make_uint4(0, 0, 0, 0);
+        *(uint2*)&vs[tid][8 * x] = make_uint2(v.x, v.y);
+        *(uint2*)&vs[tid][8 * x + 4] = make_uint2(v.z, v.w);
+      }
+    }
+    __syncthreads();
+    // running max / sum: 16 lanes per row, 4 rows per wave at once
+    {
+      const int i = wave * 4 + (lane >> 4), j0 = lane & 15;
+      if (i < nrows) {
+        float v[16], mx = -INFINITY;
+#pragma unroll
+        for (int x = 0; x < 16; ++x) { v[x] = sc[i][j0 + 16 * x]; mx = fmaxf(mx, v[x]); }
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+        const float m_old = m_s[i];
+        const float m_new = fmaxf(m_old, mx);
+        float sum = 0.f;
+#pragma unroll
+        for (int x = 0; x < 16; ++x) {
+          const float pv = (m_new == -INFINITY) ? 0.f : __expf(v[x] - m_new);
+          sc[i][j0 + 16 * x] = pv;
+          sum += pv;
+        }
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+        if (j0 == 0) {
+          const float a = (m_new == -INFINITY) ? 1.f : __expf(m_old - m_new);
+          alpha_s[i] = a;
+          l_s[i] = l_s[i] * a + sum;
+          m_s[i] = m_new;
+        }
+      } else {
+#pragma unroll
+        for (int x = 0; x < 16; ++x) sc[i][j0 + 16 * x] = 0.f;      // unused rows contribute nothing
+      }
+    }
+    __syncthreads();
+    // weighted values
+    {
+      const float al = alpha_s[lr];
+      acc[0] *= al; acc[1] *= al; acc[2] *= al; acc[3] *= al;
+      const int ksteps = (min(CH, nkeys - c0) + 31) >> 5;
+      for (int ks = 0; ks < ksteps; ++ks) {
+        const int k0 = 32 * ks + 8 * lq;
+        unsigned short vv[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) vv[j] = vs[k0 + j][16 * wave + lr];
+        const bf16x8 va = __builtin_bit_cast(bf16x8, make_uint4((unsigned)vv[0] | ((unsigned)vv[1] << 16), (unsigned)vv[2] | ((unsigned)vv[3] << 16),
+                                                                 (unsigned)vv[4] | ((unsigned)vv[5] << 16), (unsigned)vv[6] | ((unsigned)vv[7] << 16)));
+        const float4 p0 = *(const float4*)&sc[lr][k0], p1 = *(const float4*)&sc[lr][k0 + 4];
+        const float pvv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+        bf16x8 phi, plo;
+        split_bf16x8(pvv, phi, plo);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, phi, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, plo, acc, 0, 0, 0);
+      }
+    }
+    __syncthreads();
+  }
+#undef BPD_LOAD_KV
+  const int dim = 16 * wave + 4 * lq;
+  if (p.nsplit == 1) {
+    if (lr < nrows) {
+      const float inv = 1.0f / l_s[lr];
+      bf16_t* o = (bf16_t*)p.out + ((long)b * p.R + r0 + lr) * p.d + h * DH + dim;
+      *(uint2*)o = make_uint2((unsigned)f2bf(acc[0] * inv) | ((unsigned)f2bf(acc[1] * inv) << 16),
+                              (unsigned)f2bf(acc[2] * inv) | ((unsigned)f2bf(acc[3] * inv) << 16));
+    }
+  } else {
+    const int tiles = gridDim.z / p.nsplit;
+    float* part = p.part + ((((long)b * gridDim.x + h) * tiles + tile) * p.nsplit + split) * (RT * (DH + 2));
+    *(float4*)(part + lr * DH + dim) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    if (tid < RT) { part[RT * DH + tid] = m_s[tid]; part[RT * DH + RT + tid] = l_s[tid]; }
+  }
+}
+
 // Merge of the nsplit partial results of attention_kernel: with M the largest of the partial
 // maxima, output = sum_s acc_s e^(m_s - M) / sum_s l_s e^(m_s - M).  Grid (heads, B, row tiles).
 template <typename ACT, int DH>
