@@ -311,8 +311,10 @@ void pick_tile(int M, int N, int K, long zdim, bool argmax, int& mt, int& nt) {
       if (n == 4 && m == 8 && !argmax) continue;     // its epilogue does not fit the register budget
       const long bm = 16 * m, mblocks = (M + bm - 1) / bm, pad = mblocks * bm;
       if (mblocks * cols * zdim < LDSX_MIN_WGS) continue;
-      const long area = (long)m * n;
-      if (area > best_area || (area == best_area && pad < best_pad)) { best_area = area; best_pad = pad; mt = m; nt = n; }
+      const long area = (long)m * n;                  // compared as area * M / pad: padded rows are wasted work
+      if (best_area == 0 || area * best_pad > best_area * pad || (area * best_pad == best_area * pad && pad < best_pad)) {
+        best_area = area; best_pad = pad; mt = m; nt = n;
+      }
     }
   }
 }
@@ -396,8 +398,6 @@ void vocab_argmax(bpd_ctx* ctx, const GemmP& p, unsigned long long* keys, float*
   Epi none{};
   LnP noln{};
   if (skinny_ok(ctx, p)) launch_skinny<2, false, true>(ctx, p, none, noln, keys, logits, 1);
-  else if (p.M <= 64 && p.K <= 1024) launch_skinny_cfg<4, 1, false, true, 4, 8, 1>(ctx, p, none, noln, keys, logits, 1, 256);
-  else if (p.M <= 112 && p.K <= 1024) launch_skinny_cfg<7, 1, false, true, 4, 8, 1>(ctx, p, none, noln, keys, logits, 1, 256);
   else if (p.K % 64 == 0) dispatch_ldsx<true>(p, none, keys, logits, 1, s);
   else {
     const int ntiles = p.N / 16;
