@@ -87,6 +87,46 @@ def profile_phase(ctx, phase, cfg, src, n, max_len, sched, k, steps, torch):
     return ms / max(1, launches)
 
 
+def other_configs(torch, binding):
+    """bpd_step latency of the remaining workloads (parity-test configurations, reported for context):
+    C0 and C1 over a decode session, C4 at three cache lengths (accepting one token per step so
+    that the cache length stays put while timing)."""
+    res = {}
+    for name in ("C0", "C1", "C4"):
+        cfg = wl.CONFIGS[name]
+        ctx = binding.Context(binding.config_from_workload(cfg))
+        ctx.bpd_load_weights(wl.make_weights(cfg))
+        src, n = wl.make_sources(cfg)
+        ml = wl.make_max_len(cfg, n)
+        if name != "C4":
+            mean = {"C0": 2, "C1": 4}[name]
+            sched = wl.make_schedule(cfg, mean, cfg.max_out)
+            run_sessions(ctx, cfg, src, n, ml, sched, cfg.k, 10, torch)
+            sec, acc, st = run_sessions(ctx, cfg, src, n, ml, sched, cfg.k, 60, torch)
+            res[name] = {"ms_per_step": 1e3 * sec / st, "tokens_per_s": acc / sec, "imposed_mean": mean, "batch": cfg.batch, "k": cfg.k}
+        else:
+            one = torch.ones((cfg.batch,), dtype=torch.int32, device="cuda")
+            full = torch.full((cfg.batch,), cfg.k, dtype=torch.int32, device="cuda")
+            ctx.bpd_encode(src, n, ml)
+            L = 1
+            for target in (256, 1536, 3000):
+                while L < target - 10:
+                    ctx.bpd_step(cfg.k, full)
+                    L += cfg.k
+                for _ in range(3):
+                    ctx.bpd_step(cfg.k, one)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(20):
+                    ctx.bpd_step(cfg.k, one)
+                torch.cuda.synchronize()
+                L += 23
+                res[f"C4@L{target}"] = {"ms_per_step": 1e3 * (time.perf_counter() - t0) / 20, "batch": cfg.batch, "k": cfg.k,
+                                        "scored_positions_per_s": cfg.batch * cfg.k * 20 / (time.perf_counter() - t0)}
+        ctx.close()
+    return res
+
+
 def cpu_baseline(cfg, weights, src, n, sched_col, tokens_target=40):
     """The oracle as it stands, on the host cores: blockwise decoding of the first
     `tokens_target` tokens of the batch-1 sentence under the same imposed schedule."""
@@ -114,6 +154,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-batch32", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain 256 MiB copy kernel a few times (reference for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE scaling)")
@@ -204,6 +245,9 @@ def main():
                          "step_achieved": sum(fl.values()) / (ms32 * 1e9),
                          "step_frac": sum(fl.values()) / (ms32 * 1e9) / MFMA_BF16_PEAK_TFLOPS},
         }
+
+    if not args.no_other_configs:
+        out["other_configs"] = other_configs(torch, binding)
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg1, weights, src, n, sched[:, 0])

@@ -134,6 +134,15 @@ int bpd_step(bpd_ctx* ctx, int k, const int32_t* imposed_accept, int32_t* accept
  * 1 = no minimum).  Errors: BPD_E_ARG. */
 int bpd_set_acceptance(bpd_ctx* ctx, int distance_eps, int min_block);
 
+/* Top-n verification (Section 5.1), applies to later bpd_step / bpd_decode calls with
+ * imposed_accept == NULL: a proposal is also accepted if it is among the n highest-scoring
+ * tokens of p_1 at its block row (ties go to the lower token id, as in the arg-max).  n = 1
+ * switches the criterion off (exact match, or whatever bpd_set_acceptance selected; the two
+ * criteria are OR-ed).  With n > 1 every step scores p_1 of the k block rows a second time with
+ * the logits kept in the workspace ([B*k, vocab] fp32), so a step costs one more pass over the
+ * embedding matrix.  Errors: BPD_E_ARG (n outside 1..vocab). */
+int bpd_set_top_n(bpd_ctx* ctx, int n);
+
 /* Repeat bpd_step until every sequence has ended (EOS accepted or max_len reached) or
  * max_steps steps were made; synchronises.
  *   schedule [host|device] int32 [max_steps, B] imposed accepted lengths, or NULL

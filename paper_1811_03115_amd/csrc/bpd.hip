@@ -43,7 +43,7 @@ struct Layout {
   void *selfK, *selfV, *crossK, *crossV;        // [n_dec][B][slots|max_src][d]
   // decoder activations (M = max_batch * k_max rows)
   float *x, *q, *h, *stats_ln, *zeros, *attn_part, *kpart; size_t n_zeros, n_kpart; void *xn, *attn, *ffh, *hn, *H, *O;
-  unsigned long long* keys;
+  unsigned long long* keys; unsigned long long* keys_h1; float* logits_h1; int* topn_ok;
   // encoder activations (max_batch * max_src rows)
   float *xe, *qe; void *xen, *ke, *ve, *attne, *ffhe, *mem;
   // state
@@ -107,13 +107,15 @@ size_t build_layout(const bpd_config& c, char* base, Layout& L) {
   L.xn = a.take(M * d * as); L.attn = a.take(M * d * as); L.ffh = a.take(M * F * as);
   L.hn = a.take(M * d * as); L.H = a.take(M * k * F * as); L.O = a.take(M * k * d * as);
   L.keys = (unsigned long long*)a.take(M * k * 8);
+  L.keys_h1 = (unsigned long long*)a.take(M * 8);
+  L.logits_h1 = vec(M * V);
   const size_t Me = B * S;
   L.xe = vec(Me * d); L.qe = vec(Me * d);
   L.xen = a.take(Me * d * as); L.ke = a.take(Me * d * as); L.ve = a.take(Me * d * as);
   L.attne = a.take(Me * d * as); L.ffhe = a.take(Me * F * as); L.mem = a.take(Me * d * as);
   auto ints = [&](size_t n) { return (int*)a.take(n * 4); };
   L.L = ints(B); L.j = ints(B); L.finished = ints(B); L.max_len = ints(B); L.src_len = ints(B);
-  L.src_ids = ints(Me); L.P = ints(B * k); L.A = ints(B * k * k); L.accepted = ints(B);
+  L.src_ids = ints(Me); L.P = ints(B * k); L.A = ints(B * k * k); L.accepted = ints(B); L.topn_ok = ints(B * k);
   L.out_ids = ints(B * (size_t)c.max_out_len); L.step_counter = ints(1); L.imposed1 = ints(B);
   L.sched = ints(B * (size_t)c.max_out_len);
   L.stats = (long long*)a.take(32 * 8);
@@ -145,7 +147,7 @@ struct bpd_ctx {
   int B = 0, S = 0;
   bool encoded = false;
   int64_t steps = 0;
-  int distance_eps = 0, min_block = 1;
+  int distance_eps = 0, min_block = 1, top_n = 1;
   int* pinned = nullptr;       // small pinned host scratch
   int prof_phase = 0;
   std::vector<hipEvent_t> prof_ev;
@@ -578,8 +580,21 @@ int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
     if (c.dtype == BPD_BF16) {
       vocab_argmax(ctx, gp(L.O, d, L.emb, c.vocab, (int)nk, c.vocab, d), L.keys, logits);
     } else {
-      hipLaunchKernelGGL(vocab_argmax_f32_kernel, dim3((unsigned)nk), dim3(256), 0, ctx->stream, (const float*)L.O,
+      hipLaunchKernelGGL(vocab_argmax_f32_kernel, dim3((unsigned)nk), dim3(256), 0, ctx->stream, (const float*)L.O, d,
                          (const float*)L.emb, (int)nk, c.vocab, d, L.keys, logits);
+    }
+    // top-n acceptance: p_1 of every block row once more with its logits kept (rows of head 1 are
+    // every k-th row of O), then the rank of each proposal among them
+    if (ctx->top_n > 1 && R == k && k > 1) {
+      fill_i32(ctx, (int*)L.keys_h1, 2L * M, 0);
+      if (c.dtype == BPD_BF16) {
+        vocab_argmax(ctx, gp(L.O, k * d, L.emb, c.vocab, M, c.vocab, d), L.keys_h1, L.logits_h1);
+      } else {
+        hipLaunchKernelGGL(vocab_argmax_f32_kernel, dim3((unsigned)M), dim3(256), 0, ctx->stream, (const float*)L.O, k * d,
+                           (const float*)L.emb, M, c.vocab, d, L.keys_h1, L.logits_h1);
+      }
+      hipLaunchKernelGGL(topn_rank_kernel, dim3(k - 1, B), dim3(256), 0, ctx->stream, (const float*)L.logits_h1, c.vocab,
+                         (const int*)L.P, c.k_max, k, ctx->top_n, L.topn_ok);
     }
   }
   LAUNCHCHK();
@@ -594,6 +609,7 @@ StateP state_params(bpd_ctx* ctx) {
   s.accepted = L.accepted; s.out_ids = L.out_ids; s.stats = L.stats; s.imposed = nullptr; s.imposed_stride = 0;
   s.kmax = ctx->cfg.k_max; s.max_out = ctx->cfg.max_out_len;
   s.eos_id = ctx->cfg.eos_id; s.distance_eps = ctx->distance_eps; s.min_block = ctx->min_block;
+  s.topn_ok = ctx->top_n > 1 ? ctx->lay.topn_ok : nullptr;
   return s;
 }
 
@@ -840,6 +856,13 @@ int bpd_set_acceptance(bpd_ctx* ctx, int distance_eps, int min_block) {
   if (!ctx) return BPD_E_ARG;
   if (distance_eps < 0 || min_block < 1 || min_block > ctx->cfg.k_max) return fail(ctx, BPD_E_ARG, "bpd_set_acceptance: out of range");
   ctx->distance_eps = distance_eps; ctx->min_block = min_block;
+  return BPD_OK;
+}
+
+int bpd_set_top_n(bpd_ctx* ctx, int n) {
+  if (!ctx) return BPD_E_ARG;
+  if (n < 1 || n > ctx->cfg.vocab) return fail(ctx, BPD_E_ARG, "bpd_set_top_n: n outside 1..vocab");
+  ctx->top_n = n;
   return BPD_OK;
 }
 

@@ -264,10 +264,10 @@ __global__ void gemm_f32_kernel(GemmP p, Epi e) {
 }
 
 // fp32 vocabulary projection: E is [V][d] row-major; one workgroup per row of O.
-__global__ __launch_bounds__(256) void vocab_argmax_f32_kernel(const float* O, const float* E, int M, int V,
+__global__ __launch_bounds__(256) void vocab_argmax_f32_kernel(const float* O, int ldo, const float* E, int M, int V,
                                                                int d, unsigned long long* keys, float* logits) {
   const int m = blockIdx.x;
-  const float* o = O + (long)m * d;
+  const float* o = O + (long)m * ldo;
   unsigned long long best = 0ull;
   for (int v = threadIdx.x; v < V; v += blockDim.x) {
     const float* ev = E + (long)v * d;
@@ -918,6 +918,7 @@ struct StateP {
   int imposed_stride;  // B for a whole schedule, 0 for a single step's vector
   int kmax, max_out, eos_id;
   int distance_eps, min_block;
+  const int* topn_ok;  // [B][kmax]: proposal i+1 is among the n best of p_1 at row i (null: criterion off)
 };
 
 __global__ void fill_u64_kernel(unsigned long long* p, long n, unsigned long long v) {
@@ -939,6 +940,26 @@ __global__ void prime_kernel(StateP s, const unsigned long long* keys, int B) {
     s.A[(b * s.kmax + 0) * s.kmax + lane] = a;
   }
   if (lane == 0) { s.L[b] = 1; s.j[b] = 0; s.finished[b] = 0; s.accepted[b] = 0; }
+}
+
+// Top-n acceptance (Section 5.1): is proposal P[b][i+1] among the n best-scoring tokens of p_1 at
+// block row i?  logits: [B*k][V] fp32, row b*k + i = head 1 at block row i.  The rank of the
+// proposal is the number of tokens that beat it in the (value, lower index first) order of the
+// arg-max keys.  Grid (k - 1, B), one workgroup per tested row.
+__global__ __launch_bounds__(256) void topn_rank_kernel(const float* logits, int V, const int* P, int kmax, int k, int n,
+                                                        int* ok) {
+  const int i = blockIdx.x, b = blockIdx.y;
+  const float* z = logits + ((long)b * k + i) * V;
+  int t = P[b * kmax + i + 1];
+  t = t < 0 ? 0 : (t >= V ? V - 1 : t);
+  const unsigned long long kt = argmax_key(z[t], (unsigned)t);
+  int cnt = 0;
+  for (int v = threadIdx.x; v < V; v += 256) cnt += argmax_key(z[v], (unsigned)v) > kt;
+  __shared__ int part[4];
+  for (int off = 32; off > 0; off >>= 1) cnt += __shfl_xor(cnt, off, 64);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = cnt;
+  __syncthreads();
+  if (threadIdx.x == 0) ok[b * kmax + i] = (part[0] + part[1] + part[2] + part[3]) < n;
 }
 
 // Verify / accept / commit for one sequence per wavefront.
@@ -967,7 +988,7 @@ __global__ __launch_bounds__(64) void accept_kernel(StateP s, const unsigned lon
   if (lane >= 1 && lane < k) {
     const int a1 = key_index(keys[(long)b * k * k + (lane - 1) * k + 0]);
     const int diff = myP > a1 ? myP - a1 : a1 - myP;
-    ok = diff <= s.distance_eps;
+    ok = diff <= s.distance_eps || (s.topn_ok && s.topn_ok[b * s.kmax + lane - 1]);
   }
   const unsigned long long lanes_k = (k >= 64) ? ~0ull : ((1ull << k) - 1ull);
   const unsigned long long bad = (~__ballot(ok)) & lanes_k;

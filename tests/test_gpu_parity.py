@@ -169,6 +169,57 @@ def test_relaxed_acceptance_on_gpu():
     ctx.bpd_set_acceptance(0, 1)
 
 
+def _topn_case(cfg, weights, ns, grows=False):
+    from oracle import accept_top_n
+    ctx = gpu_context(cfg, weights)
+    src, n = ragged_sources(cfg, 5)
+    ctx.bpd_encode(src, n)
+    ids0, len0, st0 = ctx.bpd_decode(cfg.k)
+    model = oracle_model(cfg, weights)
+    mean_blocks = []
+    for top in ns:
+        ctx.bpd_set_top_n(top)
+        ctx.bpd_encode(src, n)
+        ids, lens, st = ctx.bpd_decode(cfg.k)
+        if top == 1:
+            np.testing.assert_array_equal(ids, ids0)                     # n = 1 is exact matching
+        mean_blocks.append(st.accepted_total / max(1, st.seq_steps))
+        for b in range(cfg.batch):
+            score, block = scorers(model, src[b, :n[b]])
+            ref = blockwise_decode(score, cfg.k, cfg.max_out, cfg.eos_id, accept=accept_top_n(top), block_score=block)
+            assert ids[b, :lens[b]].tolist() == ref.tokens, (top, b)
+    ctx.bpd_set_top_n(1)
+    assert mean_blocks == sorted(mean_blocks)                            # a looser test never shortens the blocks
+    assert not grows or mean_blocks[-1] > mean_blocks[0]
+
+
+def test_top_n_acceptance_on_gpu():
+    """Top-n acceptance (Section 5.1) against the oracle's blockwise decoding with the same criterion:
+    n = 1 reproduces exact matching, larger n accepts longer blocks, tokens equal the oracle's."""
+    cfg = SMALL_F32
+    _topn_case(cfg, wl.make_weights(cfg, std=0.08), [1, 2, 3])
+    # heads that rarely agree with p_1 (exact matching accepts one token a step): the block length grows with n
+    _topn_case(cfg, wl.make_weights(cfg, std=0.2), [1, 3, 32, 128, cfg.vocab], grows=True)
+    # bf16, several row tiles, strided head-1 rows through the MFMA kernels: the criterion is monotone in
+    # n and n = 1 is exact matching (token equality with the fp64 oracle is not asserted here: a
+    # near-tie in bf16 may legitimately fall on the other side of the n-th place)
+    cfg = MID_BF16
+    ctx = gpu_context(cfg, wl.make_weights(cfg))
+    src, n = ragged_sources(cfg, 6)
+    ctx.bpd_encode(src, n)
+    ids0, len0, st0 = ctx.bpd_decode(cfg.k)
+    blocks = []
+    for top in (1, 2, 4, cfg.vocab):
+        ctx.bpd_set_top_n(top)
+        ctx.bpd_encode(src, n)
+        ids, lens, st = ctx.bpd_decode(cfg.k)
+        if top == 1:
+            np.testing.assert_array_equal(ids, ids0)
+        blocks.append(st.accepted_total / max(1, st.seq_steps))
+    assert blocks == sorted(blocks)
+    assert st.steps <= -(-cfg.max_out // cfg.k)          # n = vocab accepts every proposal: full blocks
+
+
 def test_error_codes_on_gpu():
     from paper_1811_03115_amd import binding
     cfg = SMALL_F32
