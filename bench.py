@@ -87,6 +87,32 @@ def profile_phase(ctx, phase, cfg, src, n, max_len, sched, k, steps, torch):
     return ms / max(1, launches)
 
 
+# mean accepted block size of the paper's best translation models (Table 1, column "Both") by k
+PAPER_MEAN_BLOCK = {1: 1.0, 2: 1.88, 4: 3.27, 6: 4.18, 8: 4.69, 10: 4.95}
+
+
+def k_sweep(ctx, cfg, src, n, max_len, torch, steps=100):
+    """Step latency and accepted tokens/s by block size k on the headline workload, each k under an
+    imposed schedule with the paper's mean accepted block size for that k (Section 7.4 plots
+    wall-clock speedup against exactly this quantity); speedup is relative to k = 1 (greedy)."""
+    res, base = {}, None
+    for k in (1, 2, 4, 6, 8, 10):
+        if k > cfg.k:
+            continue
+        mean = PAPER_MEAN_BLOCK[k]
+        sched = wl.make_schedule(cfg, mean, cfg.max_out, k=k) if k > 1 else np.ones((cfg.max_out, src.shape[0]), np.int32)
+        run_sessions(ctx, cfg, src, n, max_len, sched, k, 10, torch)
+        sec, acc, st = run_sessions(ctx, cfg, src, n, max_len, sched, k, steps, torch)
+        tps = acc / sec
+        base = tps if base is None else base
+        res[str(k)] = {"ms_per_step": 1e3 * sec / st, "mean_accepted": acc / st, "tokens_per_s": tps,
+                       "speedup_vs_k1": tps / base}
+    k1 = res["1"]["ms_per_step"]
+    for v in res.values():
+        v["step_cost_vs_k1"] = v["ms_per_step"] / k1
+    return res
+
+
 def other_configs(torch, binding):
     """bpd_step latency of the remaining workloads (parity-test configurations, reported for context):
     C0 and C1 over a decode session, C4 at three cache lengths (accepting one token per step so
@@ -155,6 +181,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-batch32", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true")
+    ap.add_argument("--no-k-sweep", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain 256 MiB copy kernel a few times (reference for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE scaling)")
@@ -222,6 +249,9 @@ def main():
                    "scored_positions_per_s": k / (ms_step * 1e-3), "mean_accepted": accepted / steps},
         "roofline": roofline,
     }
+
+    if not args.no_k_sweep:
+        out["k_sweep"] = k_sweep(ctx, cfg1, src, n, max_len, torch)
 
     # ---------------------------------------------------------------- batch 32
     if not args.no_batch32:
