@@ -276,6 +276,15 @@ def main():
                          "step_frac": sum(fl.values()) / (ms32 * 1e9) / MFMA_BF16_PEAK_TFLOPS},
         }
 
+        # the same workload with two-phase scoring (p_1 at all block rows, other heads at row k-hat only):
+        # same tokens, 2k - 1 instead of k^2 vocabulary-projection rows per sequence
+        ctx.bpd_set_two_phase(True)
+        run_sessions(ctx, cfg32, src32, n32, max32, sched32, k, max(4, args.warmup // 4), torch)
+        sec2, acc2, st2 = run_sessions(ctx, cfg32, src32, n32, max32, sched32, k, steps32, torch)
+        ctx.bpd_set_two_phase(False)
+        out["batch32_two_phase"] = {"value": acc2 / sec2, "unit": "tokens/s", "ms_per_step": 1e3 * sec2 / st2, "steps": st2,
+                                    "speedup_vs_full_table": (acc2 / sec2) / (acc32 / sec32)}
+
     if not args.no_other_configs:
         out["other_configs"] = other_configs(torch, binding)
 

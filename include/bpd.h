@@ -143,6 +143,16 @@ int bpd_set_acceptance(bpd_ctx* ctx, int distance_eps, int min_block);
  * embedding matrix.  Errors: BPD_E_ARG (n outside 1..vocab). */
 int bpd_set_top_n(bpd_ctx* ctx, int n);
 
+/* Two-phase scoring (a variant of the combined model of Section 4 that yields the same tokens):
+ * with on != 0 a step scores p_1 at the k block rows first, verifies, and then evaluates the
+ * heads 2..k only at block row k-hat, the one row whose proposals the next step uses: 2k - 1
+ * vocabulary-projection rows per sequence instead of k^2, at the price of a second, dependent
+ * pass over the head and embedding weights.  Pays off when the step is compute bound (large
+ * batch); applies to bf16 contexts with more than 16 block rows per step, otherwise ignored.
+ * The table returned by bpd_get_state then holds column 1 of every row and row k-hat only
+ * (other entries -1).  Default off.  Errors: BPD_E_ARG (null ctx). */
+int bpd_set_two_phase(bpd_ctx* ctx, int on);
+
 /* Repeat bpd_step until every sequence has ended (EOS accepted or max_len reached) or
  * max_steps steps were made; synchronises.
  *   schedule [host|device] int32 [max_steps, B] imposed accepted lengths, or NULL

@@ -43,7 +43,8 @@ struct Layout {
   void *selfK, *selfV, *crossK, *crossV;        // [n_dec][B][slots|max_src][d]
   // decoder activations (M = max_batch * k_max rows)
   float *x, *q, *h, *stats_ln, *zeros, *attn_part, *kpart; size_t n_zeros, n_kpart; void *xn, *attn, *ffh, *hn, *H, *O;
-  unsigned long long* keys; unsigned long long* keys_h1; float* logits_h1; int* topn_ok;
+  unsigned long long* keys; unsigned long long* keys_h1; unsigned long long* keys2; float* logits_h1; int* topn_ok;
+  void* hn2; float* h2; int* sel;
   // encoder activations (max_batch * max_src rows)
   float *xe, *qe; void *xen, *ke, *ve, *attne, *ffhe, *mem;
   // state
@@ -108,6 +109,8 @@ size_t build_layout(const bpd_config& c, char* base, Layout& L) {
   L.hn = a.take(M * d * as); L.H = a.take(M * k * F * as); L.O = a.take(M * k * d * as);
   L.keys = (unsigned long long*)a.take(M * k * 8);
   L.keys_h1 = (unsigned long long*)a.take(M * 8);
+  L.keys2 = (unsigned long long*)a.take(M * 8);
+  L.hn2 = a.take(B * d * as); L.h2 = vec(B * d);
   L.logits_h1 = vec(M * V);
   const size_t Me = B * S;
   L.xe = vec(Me * d); L.qe = vec(Me * d);
@@ -115,7 +118,7 @@ size_t build_layout(const bpd_config& c, char* base, Layout& L) {
   L.attne = a.take(Me * d * as); L.ffhe = a.take(Me * F * as); L.mem = a.take(Me * d * as);
   auto ints = [&](size_t n) { return (int*)a.take(n * 4); };
   L.L = ints(B); L.j = ints(B); L.finished = ints(B); L.max_len = ints(B); L.src_len = ints(B);
-  L.src_ids = ints(Me); L.P = ints(B * k); L.A = ints(B * k * k); L.accepted = ints(B); L.topn_ok = ints(B * k);
+  L.src_ids = ints(Me); L.P = ints(B * k); L.A = ints(B * k * k); L.accepted = ints(B); L.topn_ok = ints(B * k); L.sel = ints(B);
   L.out_ids = ints(B * (size_t)c.max_out_len); L.step_counter = ints(1); L.imposed1 = ints(B);
   L.sched = ints(B * (size_t)c.max_out_len);
   L.stats = (long long*)a.take(32 * 8);
@@ -147,7 +150,8 @@ struct bpd_ctx {
   int B = 0, S = 0;
   bool encoded = false;
   int64_t steps = 0;
-  int distance_eps = 0, min_block = 1, top_n = 1;
+  int distance_eps = 0, min_block = 1, top_n = 1, two_phase = 0;
+  const int* cur_imposed = nullptr; int cur_imposed_stride = 0, cur_imposed_step = 0;   // of the step being run
   int* pinned = nullptr;       // small pinned host scratch
   int prof_phase = 0;
   std::vector<hipEvent_t> prof_ev;
@@ -519,6 +523,53 @@ struct PhaseTimer {
 
 // ------------------------------------------------------------------------------- the model invocation
 
+StateP state_params(bpd_ctx* ctx);
+
+// Heads and vocabulary projection of one step in two dependent phases (same tokens as the k x k
+// table, fewer rows): p_1 at the k block rows -> verify -> the heads 2..k at row k-hat only, which
+// is all the accept and predict substeps read (Section 3: verification uses p_1, the next
+// proposals are row k-hat of the table).  2k - 1 rows of the vocabulary projection per sequence
+// instead of k^2.  Needs more than 16 block rows (the single-tile path keeps its fused LayerNorm).
+int heads_two_phase(bpd_ctx* ctx, int k) {
+  const bpd_config& c = ctx->cfg;
+  Layout& L = ctx->lay;
+  const int B = ctx->B, d = c.d_model, F = c.d_ff, M = B * k;
+  const size_t as = act_size(c);
+  // phase 1: head 1 (the base model's p_1) at every block row
+  layernorm(ctx, L.x, L.dec_lnf, M, L.hn, L.h);
+  gemm(ctx, gp(L.hn, d, L.hw1, c.k_max * F, M, F, d), plain(L.hb1, 1, nullptr, 0, nullptr, 0, L.H, F));
+  gemm(ctx, gp(L.H, F, L.hw2, d, M, d, F), plain(L.hb2, 0, L.h, d, nullptr, 0, L.O, d));
+  fill_i32(ctx, (int*)L.keys_h1, 2L * M, 0);
+  fill_i32(ctx, (int*)L.keys2, 2L * M, 0);
+  const bool topn = ctx->top_n > 1;
+  vocab_argmax(ctx, gp(L.O, d, L.emb, c.vocab, M, c.vocab, d), L.keys_h1, topn ? L.logits_h1 : nullptr);
+  if (topn)
+    hipLaunchKernelGGL(topn_rank_kernel, dim3(k - 1, B), dim3(256), 0, ctx->stream, (const float*)L.logits_h1, c.vocab,
+                       (const int*)L.P, c.k_max, k, ctx->top_n, L.topn_ok);
+  StateP st = state_params(ctx);
+  st.imposed = ctx->cur_imposed; st.imposed_stride = ctx->cur_imposed_stride;
+  hipLaunchKernelGGL(select_row_kernel, dim3(B), dim3(256), 0, ctx->stream, st, (const unsigned long long*)L.keys_h1, k,
+                     ctx->cur_imposed_step, (const bf16_t*)L.hn, (const float*)L.h, d, L.sel, (bf16_t*)L.hn2, L.h2);
+  // phase 2: heads 2..k at the selected row of each sequence
+  const int kh = k - 1;
+  const char* w1 = (const char*)L.hw1 + (size_t)F * d * as;          // packed by 16-column tiles: head 2 starts F columns in
+  const char* w2 = (const char*)L.hw2 + (size_t)F * d * as;
+  gemm(ctx, gp(L.hn2, d, w1, c.k_max * F, B, kh * F, d), plain(L.hb1 + F, 1, nullptr, 0, nullptr, 0, L.H, kh * F));
+  {
+    GemmP p = gp(L.H, kh * F, w2, d, B, d, F);
+    p.x_g = F; p.w_g = (long)F * d;
+    Epi e = plain(L.hb2 + d, 0, L.h2, d, nullptr, 0, L.O, kh * d);
+    e.bias_g = d; e.r_g = 0; e.ya_g = d;
+    gemm(ctx, p, e, kh);
+  }
+  vocab_argmax(ctx, gp(L.O, d, L.emb, c.vocab, B * kh, c.vocab, d), L.keys2, nullptr);
+  hipLaunchKernelGGL(assemble_keys_kernel, dim3(B), dim3(256), 0, ctx->stream, (const unsigned long long*)L.keys_h1,
+                     (const unsigned long long*)L.keys2, (const int*)L.sel, k, L.keys);
+  LAUNCHCHK();
+  if (ctx->pend_slices) return fail(ctx, BPD_E_STATE, "split-K slices were left unreduced");
+  return BPD_OK;
+}
+
 // One invocation of the combined model on R new rows per sequence (R = 1 for the first call
 // on the empty prefix, R = k afterwards) with the first k heads; fills keys[B*R*k].
 int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
@@ -557,6 +608,7 @@ int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
       gemm(ctx, gp(L.ffh, F, w.w2, d, M, d, F), residual(w.b2));
     }
   }
+  if (ctx->two_phase && R == k && k > 1 && !sp && !logits && c.dtype == BPD_BF16) return heads_two_phase(ctx, k);
   // the k residual FFN heads: final LayerNorm + hidden layers side by side (h kept in fp32
   // for the residual), then one output layer per head
   {
@@ -817,6 +869,7 @@ int bpd_encode(bpd_ctx* ctx, const int32_t* src_ids, const int32_t* src_len, con
 static int step_impl(bpd_ctx* ctx, int k, const int* imposed_dev, int imposed_stride, int imposed_step, int* accepted_dev) {
   Layout& L = ctx->lay;
   PhaseTimer whole(ctx, BPD_PHASE_STEP);
+  ctx->cur_imposed = imposed_dev; ctx->cur_imposed_stride = imposed_stride; ctx->cur_imposed_step = imposed_step;
   int rc = forward(ctx, k, k, 0, nullptr);
   if (rc) return rc;
   {
@@ -863,6 +916,12 @@ int bpd_set_top_n(bpd_ctx* ctx, int n) {
   if (!ctx) return BPD_E_ARG;
   if (n < 1 || n > ctx->cfg.vocab) return fail(ctx, BPD_E_ARG, "bpd_set_top_n: n outside 1..vocab");
   ctx->top_n = n;
+  return BPD_OK;
+}
+
+int bpd_set_two_phase(bpd_ctx* ctx, int on) {
+  if (!ctx) return BPD_E_ARG;
+  ctx->two_phase = on != 0;
   return BPD_OK;
 }
 

@@ -962,6 +962,61 @@ __global__ __launch_bounds__(256) void topn_rank_kernel(const float* logits, int
   if (threadIdx.x == 0) ok[b * kmax + i] = (part[0] + part[1] + part[2] + part[3]) < n;
 }
 
+// Verify substep for sequence b, one wavefront: lane i (1 <= i < k) holds proposal P_{i+1} in myP and
+// a1 = arg-max of p_1 at block row i; returns k-hat before the cut at EOS / max_len: the longest
+// prefix whose proposals pass the test (exact match, |P - a1| <= eps, or top-n membership), at
+// least min_block, or the imposed value.
+__device__ __forceinline__ int verified_length(const StateP& s, int b, int k, int lane, int myP, int a1, int step) {
+  bool ok = true;
+  if (lane >= 1 && lane < k) {
+    const int diff = myP > a1 ? myP - a1 : a1 - myP;
+    ok = diff <= s.distance_eps || (s.topn_ok && s.topn_ok[b * s.kmax + lane - 1]);
+  }
+  const unsigned long long lanes_k = (k >= 64) ? ~0ull : ((1ull << k) - 1ull);
+  const unsigned long long bad = (~__ballot(ok)) & lanes_k;
+  int khat = bad ? __ffsll((long long)bad) - 1 : k;
+  if (khat < s.min_block) khat = s.min_block < k ? s.min_block : k;
+  if (s.imposed) {
+    int v = s.imposed[(long)step * s.imposed_stride + b];
+    khat = v < 1 ? 1 : (v > k ? k : v);
+  }
+  return khat;
+}
+
+// Two-phase scoring, between the phases: k-hat from p_1 of the k block rows (keys_h1[b*k + i]), then
+// the block row k-hat of sequence b (bf16 LayerNorm output and its fp32 copy) is gathered for the
+// heads 2..k.  Grid B, 256 threads (the first wavefront verifies).
+__global__ __launch_bounds__(256) void select_row_kernel(StateP s, const unsigned long long* keys_h1, int k, int step,
+                                                         const bf16_t* hn, const float* h, int d, int* sel,
+                                                         bf16_t* hn2, float* h2) {
+  const int b = blockIdx.x, lane = threadIdx.x & 63;
+  __shared__ int row_s;
+  if (threadIdx.x < 64) {
+    const int myP = lane < k ? s.P[b * s.kmax + lane] : -1;
+    const int a1 = (lane >= 1 && lane < k) ? key_index(keys_h1[(long)b * k + lane - 1]) : 0;
+    const int khat = verified_length(s, b, k, lane, myP, a1, step);
+    if (lane == 0) { row_s = khat - 1; sel[b] = khat - 1; }
+  }
+  __syncthreads();
+  const long src = ((long)b * k + row_s) * d, dst = (long)b * d;
+  for (int c = threadIdx.x; c < d; c += 256) { hn2[dst + c] = hn[src + c]; h2[dst + c] = h[src + c]; }
+}
+
+// Two-phase scoring, after the second phase: the arg-max table in the layout the accept kernel reads.
+// Column 0 (head 1) of every block row comes from the first phase, columns 1..k-1 of row sel[b]
+// from the second; the other entries stay empty (key 0 reads back as token -1).  Grid B, 256 threads.
+__global__ __launch_bounds__(256) void assemble_keys_kernel(const unsigned long long* keys_h1, const unsigned long long* keys2,
+                                                            const int* sel, int k, unsigned long long* keys) {
+  const int b = blockIdx.x, r = sel[b];
+  for (int e = threadIdx.x; e < k * k; e += 256) {
+    const int ip = e / k, i = e % k;
+    unsigned long long v = 0ull;
+    if (i == 0) v = keys_h1[(long)b * k + ip];
+    else if (ip == r) v = keys2[(long)b * (k - 1) + i - 1];
+    keys[(long)b * k * k + e] = v;
+  }
+}
+
 // Verify / accept / commit for one sequence per wavefront.
 //   keys: [B][k][k] packed argmax keys of this invocation (row i', head i).
 //   verify (exact, or |P - argmax| <= eps):  lane i (1 <= i < k) tests proposal P[i] against
@@ -984,20 +1039,8 @@ __global__ __launch_bounds__(64) void accept_kernel(StateP s, const unsigned lon
     return;
   }
   const int myP = lane < k ? s.P[b * s.kmax + lane] : -1;
-  bool ok = true;
-  if (lane >= 1 && lane < k) {
-    const int a1 = key_index(keys[(long)b * k * k + (lane - 1) * k + 0]);
-    const int diff = myP > a1 ? myP - a1 : a1 - myP;
-    ok = diff <= s.distance_eps || (s.topn_ok && s.topn_ok[b * s.kmax + lane - 1]);
-  }
-  const unsigned long long lanes_k = (k >= 64) ? ~0ull : ((1ull << k) - 1ull);
-  const unsigned long long bad = (~__ballot(ok)) & lanes_k;
-  int khat = bad ? __ffsll((long long)bad) - 1 : k;
-  if (khat < s.min_block) khat = s.min_block < k ? s.min_block : k;
-  if (s.imposed) {
-    int v = s.imposed[(long)step * s.imposed_stride + b];
-    khat = v < 1 ? 1 : (v > k ? k : v);
-  }
+  const int a1 = (lane >= 1 && lane < k) ? key_index(keys[(long)b * k * k + (lane - 1) * k + 0]) : 0;
+  int khat = verified_length(s, b, k, lane, myP, a1, step);
   bool eos = false;
   if (s.eos_id >= 0) {
     const unsigned long long eb = __ballot(lane < khat && myP == s.eos_id);

@@ -220,6 +220,47 @@ def test_top_n_acceptance_on_gpu():
     assert st.steps <= -(-cfg.max_out // cfg.k)          # n = vocab accepts every proposal: full blocks
 
 
+def test_two_phase_scoring_on_gpu():
+    """Two-phase scoring (p_1 at all block rows, then the other heads at row k-hat only) yields the same
+    accepted lengths, tokens and next proposals as the k x k table, under exact matching and under an
+    imposed schedule; the reported table holds column 1 and row k-hat."""
+    cfg = MID_BF16
+    weights = wl.make_weights(cfg)
+    ctx = gpu_context(cfg, weights)
+    src, n = ragged_sources(cfg, 8)
+    B, k = cfg.batch, cfg.k
+    sched = wl.make_schedule(cfg, 3, cfg.max_out)
+    for schedule in (None, sched):
+        ctx.bpd_set_two_phase(False)
+        ctx.bpd_encode(src, n)
+        ref_states = []
+        for s in range(6):
+            ctx.bpd_step(k, None if schedule is None else schedule[s])
+            ref_states.append([np.array(x) for x in ctx.bpd_get_state()])
+        ctx.bpd_set_two_phase(True)
+        ctx.bpd_encode(src, n)
+        for s in range(6):
+            ctx.bpd_step(k, None if schedule is None else schedule[s])
+            P, A, L, fin = [np.array(x) for x in ctx.bpd_get_state()]
+            P0, A0, L0, fin0 = ref_states[s]
+            np.testing.assert_array_equal(L, L0)
+            np.testing.assert_array_equal(fin, fin0)
+            np.testing.assert_array_equal(P, P0)
+            np.testing.assert_array_equal(A[:, :, 0], A0[:, :, 0])
+            defined = A >= 0
+            np.testing.assert_array_equal(A[defined], A0[defined])
+            assert defined.sum() == B * (2 * k - 1)
+    ctx.bpd_set_two_phase(False)
+    ctx.bpd_encode(src, n)
+    ids0, len0, _ = ctx.bpd_decode(k)
+    ctx.bpd_set_two_phase(True)
+    ctx.bpd_encode(src, n)
+    ids1, len1, _ = ctx.bpd_decode(k)
+    ctx.bpd_set_two_phase(False)
+    np.testing.assert_array_equal(len0, len1)
+    np.testing.assert_array_equal(ids0, ids1)
+
+
 def test_error_codes_on_gpu():
     from paper_1811_03115_amd import binding
     cfg = SMALL_F32
