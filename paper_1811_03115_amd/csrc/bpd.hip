@@ -108,8 +108,8 @@ size_t build_layout(const bpd_config& c, char* base, Layout& L) {
   L.xn = a.take(M * d * as); L.attn = a.take(M * d * as); L.ffh = a.take(M * F * as);
   L.hn = a.take(M * d * as); L.H = a.take(M * k * F * as); L.O = a.take(M * k * d * as);
   L.keys = (unsigned long long*)a.take(M * k * 8);
-  L.keys_h1 = (unsigned long long*)a.take(M * 8);
-  L.keys2 = (unsigned long long*)a.take(M * 8);
+  L.keys_h1 = (unsigned long long*)a.take(2 * M * 8);     // [M] keys of head 1, then [M] keys of the second phase
+  L.keys2 = L.keys_h1 + M;
   L.hn2 = a.take(B * d * as); L.h2 = vec(B * d);
   L.logits_h1 = vec(M * V);
   const size_t Me = B * S;
@@ -539,8 +539,7 @@ int heads_two_phase(bpd_ctx* ctx, int k) {
   layernorm(ctx, L.x, L.dec_lnf, M, L.hn, L.h);
   gemm(ctx, gp(L.hn, d, L.hw1, c.k_max * F, M, F, d), plain(L.hb1, 1, nullptr, 0, nullptr, 0, L.H, F));
   gemm(ctx, gp(L.H, F, L.hw2, d, M, d, F), plain(L.hb2, 0, L.h, d, nullptr, 0, L.O, d));
-  fill_i32(ctx, (int*)L.keys_h1, 2L * M, 0);
-  fill_i32(ctx, (int*)L.keys2, 2L * M, 0);
+  fill_i32(ctx, (int*)L.keys_h1, 4L * M, 0);          // keys_h1 and keys2 are neighbours in the workspace
   const bool topn = ctx->top_n > 1;
   vocab_argmax(ctx, gp(L.O, d, L.emb, c.vocab, M, c.vocab, d), L.keys_h1, topn ? L.logits_h1 : nullptr);
   if (topn)
