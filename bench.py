@@ -182,6 +182,7 @@ def main():
     ap.add_argument("--no-batch32", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true")
     ap.add_argument("--no-k-sweep", action="store_true")
+    ap.add_argument("--no-peaks", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain 256 MiB copy kernel a few times (reference for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE scaling)")
@@ -234,8 +235,29 @@ def main():
     if os.path.exists(tpath):
         with open(tpath) as f:
             traffic = json.load(f).get("C2", {}).get(dom)
+    # step latency distribution (HIP events around every bpd_step of a few sessions)
+    ctx.bpd_profile_enable(binding.PHASE_STEP)
+    run_sessions(ctx, cfg1, src, n, max_len, sched, k, min(args.steps, 200), torch)
+    samples, _, _ = ctx.bpd_profile_samples(4096)
+    ctx.bpd_profile_enable(0)
+    lat = {"p50_ms": float(np.percentile(samples, 50)), "p95_ms": float(np.percentile(samples, 95)),
+           "min_ms": float(samples.min()), "n": int(samples.size)}
+    # end to end: one bpd_decode of the sentence (encoder, first invocation, all steps, host syncs)
+    ctx.bpd_encode(src, n, max_len)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ctx.bpd_encode(src, n, max_len)
+    ids_e2e, len_e2e, st_e2e = ctx.bpd_decode(k, sched)
+    torch.cuda.synchronize()
+    e2e = {"ms": 1e3 * (time.perf_counter() - t0), "tokens": int(len_e2e.sum()), "steps": int(st_e2e.steps)}
+    # the machine's own ceilings next to the published peaks
+    peaks = None
+    if not args.no_peaks:
+        peaks = {"hbm_read_GBps": binding.Context.bpd_measure_hbm_read(1 << 30, 4),
+                 "mfma_bf16_TFLOPs": binding.Context.bpd_measure_mfma_bf16(20000)}
     roofline = {"bound": "hbm", "kernel": dom, "achieved": kern[dom]["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": kern[dom]["GBps"] / HBM_PEAK_GBS, "traffic": traffic,
+                "frac_of_measured_peak": (kern[dom]["GBps"] / peaks["hbm_read_GBps"]) if peaks else None,
                 "step_achieved": total_bytes / (ms_step * 1e6), "step_frac": total_bytes / (ms_step * 1e6) / HBM_PEAK_GBS,
                 "kernels": kern}
 
@@ -248,6 +270,9 @@ def main():
                                "imposed acceptance schedule mean 5", "batch": 1, "k": k,
                    "scored_positions_per_s": k / (ms_step * 1e-3), "mean_accepted": accepted / steps},
         "roofline": roofline,
+        "step_latency": lat,
+        "end_to_end_decode": e2e,
+        "measured_peaks": peaks,
     }
 
     if not args.no_k_sweep:

@@ -192,6 +192,22 @@ int bpd_debug_step_logits(bpd_ctx* ctx, int k, float* logits);
 #define BPD_PHASE_STEP         6   /* the whole step                                              */
 int bpd_profile_enable(bpd_ctx* ctx, int phase);
 int bpd_profile_read(bpd_ctx* ctx, double* total_ms, int64_t* launches);
+/* As bpd_profile_read, and additionally copies the milliseconds of the first `capacity` launches,
+ * in launch order, to ms_out [host] (for latency percentiles).  Errors: BPD_E_ARG, BPD_E_HIP. */
+int bpd_profile_samples(bpd_ctx* ctx, float* ms_out, int64_t capacity, double* total_ms, int64_t* launches);
+
+/* Measured peaks of the machine, for roofline denominators next to the published ones (not part
+ * of the method; no context needed).  Both launch on hip_stream, synchronise it and allocate
+ * nothing.
+ *   bpd_measure_hbm_read:  `iters` streaming-read passes over buf_dev [device, bytes, a multiple
+ *       of 4096 and >= 1 MiB, contents irrelevant, not modified]; *gbps = best of two timed
+ *       repetitions.  Use a buffer larger than the 256 MB last-level cache for an HBM figure.
+ *   bpd_measure_mfma_bf16: back-to-back v_mfma_f32_16x16x32_bf16 with pseudo-random operands, two
+ *       waves per SIMD, `iters` x 16 per wave; scratch_dev [device, >= 4 bytes]; *tflops = best of
+ *       two timed repetitions.
+ * Errors: BPD_E_ARG, BPD_E_HIP. */
+int bpd_measure_hbm_read(void* buf_dev, size_t bytes, void* hip_stream, int iters, double* gbps);
+int bpd_measure_mfma_bf16(void* scratch_dev, void* hip_stream, int iters, double* tflops);
 
 const char* bpd_last_error(const bpd_ctx* ctx);
 

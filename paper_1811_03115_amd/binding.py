@@ -44,7 +44,7 @@ class bpd_stats(C.Structure):
 EXPORTS = ["bpd_workspace_bytes", "bpd_create", "bpd_destroy", "bpd_load_weights", "bpd_encode", "bpd_step",
            "bpd_set_acceptance", "bpd_set_top_n", "bpd_set_two_phase", "bpd_decode", "bpd_get_state", "bpd_get_output", "bpd_get_stats",
            "bpd_set_proposals", "bpd_debug_step_logits", "bpd_profile_enable", "bpd_profile_read",
-           "bpd_last_error"]
+           "bpd_profile_samples", "bpd_measure_hbm_read", "bpd_measure_mfma_bf16", "bpd_last_error"]
 
 _lib = None
 
@@ -76,6 +76,9 @@ def lib() -> C.CDLL:
         L.bpd_debug_step_logits.argtypes = [vp, C.c_int, vp]
         L.bpd_profile_enable.argtypes = [vp, C.c_int]
         L.bpd_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        L.bpd_profile_samples.argtypes = [vp, vp, C.c_int64, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        L.bpd_measure_hbm_read.argtypes = [vp, C.c_size_t, vp, C.c_int, C.POINTER(C.c_double)]
+        L.bpd_measure_mfma_bf16.argtypes = [vp, vp, C.c_int, C.POINTER(C.c_double)]
         L.bpd_last_error.restype = C.c_char_p
         L.bpd_last_error.argtypes = [vp]
         for name in EXPORTS:
@@ -257,3 +260,32 @@ class Context:
         ms, n = C.c_double(), C.c_int64()
         self._check(self.L.bpd_profile_read(self.h, C.byref(ms), C.byref(n)))
         return ms.value, n.value
+
+    def bpd_profile_samples(self, capacity: int):
+        """Returns (per-launch milliseconds [<= capacity] float32 numpy, total ms, launches)."""
+        out = np.zeros(capacity, dtype=np.float32)
+        ms, n = C.c_double(), C.c_int64()
+        self._check(self.L.bpd_profile_samples(self.h, _ptr(out), capacity, C.byref(ms), C.byref(n)))
+        return out[:min(capacity, n.value)], ms.value, n.value
+
+    @staticmethod
+    def bpd_measure_hbm_read(nbytes: int = 1 << 30, iters: int = 4) -> float:
+        """GB/s of a streaming read over a fresh `nbytes` device buffer on torch's current stream."""
+        import torch
+        buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        gbps = C.c_double()
+        rc = lib().bpd_measure_hbm_read(buf.data_ptr(), nbytes, torch.cuda.current_stream().cuda_stream, iters, C.byref(gbps))
+        if rc:
+            raise BpdError(rc, "bpd_measure_hbm_read")
+        return gbps.value
+
+    @staticmethod
+    def bpd_measure_mfma_bf16(iters: int = 20000) -> float:
+        """TFLOP/s of back-to-back bf16 MFMAs on torch's current stream."""
+        import torch
+        buf = torch.zeros(64, dtype=torch.float32, device="cuda")
+        tf = C.c_double()
+        rc = lib().bpd_measure_mfma_bf16(buf.data_ptr(), torch.cuda.current_stream().cuda_stream, iters, C.byref(tf))
+        if rc:
+            raise BpdError(rc, "bpd_measure_mfma_bf16")
+        return tf.value

@@ -1019,15 +1019,72 @@ int bpd_profile_enable(bpd_ctx* ctx, int phase) {
 
 int bpd_profile_read(bpd_ctx* ctx, double* total_ms, int64_t* launches) {
   if (!ctx || !total_ms || !launches) return BPD_E_ARG;
+  return bpd_profile_samples(ctx, nullptr, 0, total_ms, launches);
+}
+
+int bpd_profile_samples(bpd_ctx* ctx, float* ms_out, int64_t capacity, double* total_ms, int64_t* launches) {
+  if (!ctx || !total_ms || !launches || capacity < 0 || (capacity > 0 && !ms_out)) return BPD_E_ARG;
   HIPCHK(hipStreamSynchronize(ctx->stream));
   double tot = 0;
-  for (size_t i = 0; i + 1 < ctx->prof_used; i += 2) {
+  int64_t n = 0;
+  for (size_t i = 0; i + 1 < ctx->prof_used; i += 2, ++n) {
     float ms = 0.f;
     HIPCHK(hipEventElapsedTime(&ms, ctx->prof_ev[i], ctx->prof_ev[i + 1]));
     tot += ms;
+    if (n < capacity) ms_out[n] = ms;
   }
   *total_ms = tot; *launches = ctx->prof_launches;
   ctx->prof_used = 0; ctx->prof_launches = 0;
+  return BPD_OK;
+}
+
+// ------------------------------------------------------------------------------- machine peaks
+
+int bpd_measure_hbm_read(void* buf_dev, size_t bytes, void* hip_stream, int iters, double* gbps) {
+  if (!buf_dev || !gbps || iters < 1 || bytes < (1u << 20) || bytes % 4096 != 0) return BPD_E_ARG;
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return BPD_E_HIP;
+  const long n16 = (long)(bytes / 16);
+  double best = 0;
+  for (int rep = 0; rep < 3; ++rep) {
+    (void)hipEventRecord(e0, s);
+    for (int i = 0; i < iters; ++i)
+      hipLaunchKernelGGL(peak_read_kernel, dim3(2048), dim3(256), 0, s, (const uint4*)buf_dev, n16, (unsigned*)buf_dev);
+    (void)hipEventRecord(e1, s);
+    if (hipStreamSynchronize(s) != hipSuccess) return BPD_E_HIP;
+    float ms = 0.f;
+    (void)hipEventElapsedTime(&ms, e0, e1);
+    const double r = (double)bytes * iters / (ms * 1e6);
+    if (rep > 0 && r > best) best = r;
+  }
+  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+  *gbps = best;
+  return BPD_OK;
+}
+
+int bpd_measure_mfma_bf16(void* scratch_dev, void* hip_stream, int iters, double* tflops) {
+  if (!scratch_dev || !tflops || iters < 1) return BPD_E_ARG;
+  hipStream_t s = (hipStream_t)hip_stream;
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return BPD_E_HIP;
+  int dev = 0, cus = 0;
+  (void)hipGetDevice(&dev);
+  (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  const int wgs = 2 * cus;                     // two 4-wave workgroups per CU: two waves per SIMD
+  double best = 0;
+  for (int rep = 0; rep < 3; ++rep) {
+    (void)hipEventRecord(e0, s);
+    hipLaunchKernelGGL(peak_mfma_kernel, dim3(wgs), dim3(256), 0, s, (float*)scratch_dev, iters, 1u + rep);
+    (void)hipEventRecord(e1, s);
+    if (hipStreamSynchronize(s) != hipSuccess) return BPD_E_HIP;
+    float ms = 0.f;
+    (void)hipEventElapsedTime(&ms, e0, e1);
+    const double r = (double)wgs * 4 * iters * 16 * 16384.0 / (ms * 1e9);
+    if (rep > 0 && r > best) best = r;
+  }
+  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+  *tflops = best;
   return BPD_OK;
 }
 

@@ -1067,3 +1067,46 @@ __global__ __launch_bounds__(64) void accept_kernel(StateP s, const unsigned lon
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Machine peaks, measured the way the step's kernels use the machine (bpd_measure_*).
+// Streaming read: every thread sums 16-byte words of a buffer, grid-stride, nothing written
+// (the impossible comparison keeps the loads alive).
+__global__ __launch_bounds__(256) void peak_read_kernel(const uint4* src, long n16, unsigned* sink) {
+  unsigned acc = 0;
+  const long stride = (long)gridDim.x * 256 * 4;
+  for (long i = (long)blockIdx.x * 256 * 4 + threadIdx.x; i < n16; i += stride) {
+    uint4 v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = src[i + 256 * j < n16 ? i + 256 * j : i];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc ^= v[j].x ^ v[j].y ^ v[j].z ^ v[j].w;
+  }
+  if (acc == 0x9E3779B9u && n16 < 0) sink[0] = acc;
+}
+
+// Matrix pipe: 16 independent accumulators per wave, v_mfma_f32_16x16x32_bf16 back to back with
+// pseudo-random bf16 operands (the sustained clock depends on the data), nothing else.
+__global__ __launch_bounds__(256) void peak_mfma_kernel(float* sink, int iters, unsigned seed) {
+  f32x4 acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  bf16x8 a[4], b[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    unsigned h = (threadIdx.x * 4 + j + blockIdx.x * 1024) * 2654435761u + seed;
+    unsigned w[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) { h ^= h >> 15; h *= 2246822519u; h ^= h >> 13; w[q] = (h & 0x807F807Fu) | 0x3D003D00u | ((h >> 3) & 0x01800180u); }
+    a[j] = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+    b[j] = __builtin_bit_cast(bf16x8, make_uint4(w[4], w[5], w[6], w[7]));
+  }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i & 3], b[(i >> 2) & 3], acc[i], 0, 0, 0);
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) sum += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+  if (sum == 12345.678f) sink[0] = sum;
+}
+
