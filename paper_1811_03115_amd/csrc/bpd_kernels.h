@@ -983,8 +983,21 @@ __device__ __forceinline__ int verified_length(const StateP& s, int b, int k, in
   return khat;
 }
 
-// Two-phase scoring, between the phases: k-hat from p_1 of the k block rows (keys_h1[b*k + i]), then
-// the block row k-hat of sequence b (bf16 LayerNorm output and its fp32 copy) is gathered for the
+// Accept substep, the cut: a verified block ends at (and includes) its first EOS and never exceeds
+// the room left under max_len; `eos` tells whether the block that remains ends in EOS.
+__device__ __forceinline__ int cut_length(const StateP& s, int b, int lane, int myP, int khat, bool& eos) {
+  eos = false;
+  if (s.eos_id >= 0) {
+    const unsigned long long eb = __ballot(lane < khat && myP == s.eos_id);
+    if (eb) { khat = __ffsll((long long)eb); eos = true; }
+  }
+  const int room = s.max_len[b] - s.j[b];
+  if (khat > room) { khat = room; eos = false; }   // the EOS, if any, was beyond the budget
+  return khat;
+}
+
+// Two-phase scoring, between the phases: k-hat (verified, then cut as in the accept kernel) from
+// p_1 of the k block rows (keys_h1[b*k + i]), then the block row k-hat of sequence b (bf16 LayerNorm output and its fp32 copy) is gathered for the
 // heads 2..k.  Grid B, 256 threads (the first wavefront verifies).
 __global__ __launch_bounds__(256) void select_row_kernel(StateP s, const unsigned long long* keys_h1, int k, int step,
                                                          const bf16_t* hn, const float* h, int d, int* sel,
@@ -994,7 +1007,10 @@ __global__ __launch_bounds__(256) void select_row_kernel(StateP s, const unsigne
   if (threadIdx.x < 64) {
     const int myP = lane < k ? s.P[b * s.kmax + lane] : -1;
     const int a1 = (lane >= 1 && lane < k) ? key_index(keys_h1[(long)b * k + lane - 1]) : 0;
-    const int khat = verified_length(s, b, k, lane, myP, a1, step);
+    bool eos;
+    int khat = verified_length(s, b, k, lane, myP, a1, step);
+    khat = cut_length(s, b, lane, myP, khat, eos);   // the row the accept kernel will read
+    khat = khat < 1 ? 1 : khat;                      // (a sequence that has already ended keeps its state)
     if (lane == 0) { row_s = khat - 1; sel[b] = khat - 1; }
   }
   __syncthreads();
@@ -1042,13 +1058,8 @@ __global__ __launch_bounds__(64) void accept_kernel(StateP s, const unsigned lon
   const int a1 = (lane >= 1 && lane < k) ? key_index(keys[(long)b * k * k + (lane - 1) * k + 0]) : 0;
   int khat = verified_length(s, b, k, lane, myP, a1, step);
   bool eos = false;
-  if (s.eos_id >= 0) {
-    const unsigned long long eb = __ballot(lane < khat && myP == s.eos_id);
-    if (eb) { khat = __ffsll((long long)eb); eos = true; }
-  }
   const int j = s.j[b];
-  const int room = s.max_len[b] - j;
-  if (khat > room) { khat = room; eos = false; }   // the EOS, if any, was the last accepted token
+  khat = cut_length(s, b, lane, myP, khat, eos);
   if (lane < khat) s.out_ids[(long)b * s.max_out + j + lane] = myP;
   const int nextP = lane < k ? key_index(keys[(long)b * k * k + (khat - 1) * k + lane]) : 0;
   if (lane < k) s.P[b * s.kmax + lane] = nextP;

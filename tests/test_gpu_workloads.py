@@ -176,3 +176,80 @@ def test_c4_near_full_cache():
     ctx.bpd_step(cfg.k, full)
     _, _, j, fin = ctx.bpd_get_state()
     assert j.tolist() == [3072, 3072] and fin.all()
+
+
+def test_c3_two_phase_equals_full_table():
+    """Batch 32 at full size: two-phase scoring reproduces accepted lengths, outputs and proposals of the
+    k x k table step by step (exact matching, ragged budgets)."""
+    w, ctx = big()
+    cfg = wl.C3
+    src, n = wl.make_sources(cfg)
+    ml = wl.make_max_len(cfg, n)
+    ref = []
+    ctx.bpd_set_two_phase(False)
+    ctx.bpd_encode(src, n, ml)
+    for s in range(5):
+        ctx.bpd_step(cfg.k)
+        P, A, L, fin = [np.array(x) for x in ctx.bpd_get_state()]
+        ref.append((P, A, L, fin))
+    out_ref, len_ref = ctx.bpd_get_output()
+    ctx.bpd_set_two_phase(True)
+    try:
+        ctx.bpd_encode(src, n, ml)
+        for s in range(5):
+            ctx.bpd_step(cfg.k)
+            P, A, L, fin = [np.array(x) for x in ctx.bpd_get_state()]
+            np.testing.assert_array_equal(L, ref[s][2])
+            np.testing.assert_array_equal(fin, ref[s][3])
+            np.testing.assert_array_equal(P, ref[s][0])
+            defined = A >= 0
+            assert defined.sum() == cfg.batch * (2 * cfg.k - 1)
+            np.testing.assert_array_equal(A[defined], ref[s][1][defined])
+        out, ln = ctx.bpd_get_output()
+        np.testing.assert_array_equal(ln, len_ref)
+        np.testing.assert_array_equal(out, out_ref)
+    finally:
+        ctx.bpd_set_two_phase(False)
+
+
+def test_c2_top_n_and_profile_samples():
+    """Transformer-big at batch 1: top-n acceptance is monotone in n and n = 1 is exact matching (the
+    strided head-1 rows go through the 32768-wide projection a second time); per-step latency samples
+    come back one per step."""
+    w, ctx = big()
+    cfg = wl.C2
+    src, n = wl.make_sources(cfg)
+    ml = wl.make_max_len(cfg, n)
+    ctx.bpd_encode(src, n, ml)
+    ids0, len0, st0 = ctx.bpd_decode(cfg.k)
+    blocks = []
+    try:
+        for top in (1, 4, 64, cfg.vocab):
+            ctx.bpd_set_top_n(top)
+            ctx.bpd_encode(src, n, ml)
+            ids, lens, st = ctx.bpd_decode(cfg.k)
+            if top == 1:
+                np.testing.assert_array_equal(ids, ids0)
+            blocks.append(st.accepted_total / max(1, st.seq_steps))
+        assert blocks == sorted(blocks)
+        assert blocks[-1] > blocks[0]
+        assert st.steps == -(-int(ml[0]) // cfg.k)             # n = vocab: every block is accepted whole
+    finally:
+        ctx.bpd_set_top_n(1)
+    from paper_1811_03115_amd import binding
+    ctx.bpd_encode(src, n, ml)
+    ctx.bpd_profile_enable(binding.PHASE_STEP)
+    for s in range(7):
+        ctx.bpd_step(cfg.k)
+    samples, total, launches = ctx.bpd_profile_samples(16)
+    ctx.bpd_profile_enable(0)
+    assert launches == 7 and samples.size == 7 and abs(float(samples.sum()) - total) < 1e-3
+    assert 0.05 < float(np.median(samples)) < 5.0              # milliseconds per step, sane range
+
+
+def test_measured_peaks_are_plausible():
+    from paper_1811_03115_amd import binding
+    gbps = binding.Context.bpd_measure_hbm_read(1 << 28, 2)
+    tf = binding.Context.bpd_measure_mfma_bf16(2000)
+    assert 500 < gbps < 8000 * 1.05            # cannot beat the published HBM peak (a 256 MiB buffer may sit in the last-level cache: allow a little)
+    assert 100 < tf < 2500 * 1.05
