@@ -24,8 +24,8 @@ __device__ __forceinline__ void store_tiles(const Epi& e, int g, const f32x4 (&a
     for (int u = 0; u < NT; ++u) {
       if (nt0 + u >= ntiles) continue;
       const int n = (nt0 + u) * 16 + (lane >> 4) * 4;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) epi_store<bf16_t>(e, g, m, n + r, acc[t][u][r]);
+      const float v[4] = {acc[t][u][0], acc[t][u][1], acc[t][u][2], acc[t][u][3]};
+      epi_store4(e, g, m, n, v);
     }
   }
 }
@@ -263,8 +263,8 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
         if (logits && m < p.M) *(float4*)(logits + (long)m * p.N + n) = make_float4(sum[0], sum[1], sum[2], sum[3]);
       } else if (e.mode != 0) {
         if (m < p.M) {
-#pragma unroll
-          for (int r = 0; r < 4; ++r) epi_store<bf16_t>(e, g, m, n + r, sum[r]);
+          const float v4[4] = {sum[0], sum[1], sum[2], sum[3]};
+          epi_store4(e, g, m, n, v4);
         }
       } else {
         float4 rv = r_cur[j];

@@ -88,6 +88,43 @@ __device__ __forceinline__ void epi_store(const Epi& e, int g, int m, int n, flo
   }
 }
 
+// Four consecutive columns n .. n+3 (n % 4 == 0, all inside one 16-column tile) of row m, bf16
+// activations: the same arithmetic as epi_store with 16-byte loads and 8- / 16-byte stores.
+// Needs ldr, ldyf, ldya, dsplit and the per-group offsets to be multiples of 4 (they are model
+// dimensions, multiples of 16).
+__device__ __forceinline__ void epi_store4(const Epi& e, int g, int m, int n, const float (&acc)[4]) {
+  float v[4] = {acc[0], acc[1], acc[2], acc[3]};
+  if (e.mode == 0) {
+    if (e.bias) {
+      const float4 bs = *(const float4*)(e.bias + g * e.bias_g + n);
+      v[0] += bs.x; v[1] += bs.y; v[2] += bs.z; v[3] += bs.w;
+    }
+    if (e.relu) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) v[r] = fmaxf(v[r], 0.f);
+    }
+    if (e.R) {
+      const float4 rv = *(const float4*)(e.R + g * e.r_g + (long)m * e.ldr + n);
+      v[0] += rv.x; v[1] += rv.y; v[2] += rv.z; v[3] += rv.w;
+    }
+    if (e.Yf) *(float4*)(e.Yf + g * e.yf_g + (long)m * e.ldyf + n) = make_float4(v[0], v[1], v[2], v[3]);
+    if (e.Ya) *(uint2*)((bf16_t*)e.Ya + g * e.ya_g + (long)m * e.ldya + n) =
+                  make_uint2((unsigned)f2bf(v[0]) | ((unsigned)f2bf(v[1]) << 16), (unsigned)f2bf(v[2]) | ((unsigned)f2bf(v[3]) << 16));
+  } else {
+    const int c = n / e.dsplit + e.chunk0;
+    const int col = n % e.dsplit;
+    if (c == 0) {
+      *(float4*)(e.Qf + (long)m * e.dsplit + col) = make_float4(v[0], v[1], v[2], v[3]);
+    } else {
+      const int b = m / e.rows_per_seq, i = m % e.rows_per_seq;
+      const long row = (long)b * e.cap + (e.base ? e.base[b] : 0) + i;
+      bf16_t* dst = (bf16_t*)(c == 1 ? e.Ka : e.Va);
+      *(uint2*)(dst + row * e.dsplit + col) =
+          make_uint2((unsigned)f2bf(v[0]) | ((unsigned)f2bf(v[1]) << 16), (unsigned)f2bf(v[2]) | ((unsigned)f2bf(v[3]) << 16));
+    }
+  }
+}
+
 struct GemmP {
   const void* X; int ldx; long x_g;    // activations [M][K] (act type), per-group offset
   const void* W; long w_g;             // bf16: packed tiles;  fp32: row-major [K][ldw]
