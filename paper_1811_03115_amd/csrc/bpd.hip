@@ -314,7 +314,6 @@ void pick_tile(int M, int N, int K, long zdim, bool argmax, int& mt, int& nt) {
     const long cols = (N / 16 + 4 * n - 1) / (4 * n);
     for (int m : mts) {
       if (n == 1 && m > 3) continue;
-      if (n == 4 && m == 8 && !argmax) continue;     // its epilogue does not fit the register budget
       const long bm = 16 * m, mblocks = (M + bm - 1) / bm, pad = mblocks * bm;
       if (mblocks * cols * zdim < LDSX_MIN_WGS) continue;
       const long area = (long)m * n;                  // compared as area * M / pad: padded rows are wasted work
