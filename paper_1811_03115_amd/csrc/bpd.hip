@@ -305,6 +305,7 @@ void launch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* 
 // With nt = 1 at most 48 rows, so that the two 256-deep staging buffers leave room for three
 // workgroups per CU.  If nothing qualifies the smallest tile spreads the work furthest.
 constexpr long LDSX_MIN_WGS = 448;
+constexpr long LDSX_MIN_WGS_LONGK = 320;   // K >= 2048: a workgroup lives long enough that 1.25 per CU suffice
 void pick_tile(int M, int N, int K, long zdim, bool argmax, int& mt, int& nt) {
   const int mts[7] = {8, 7, 5, 4, 3, 2, 1};
   long best_area = 0, best_pad = 0;
@@ -315,7 +316,7 @@ void pick_tile(int M, int N, int K, long zdim, bool argmax, int& mt, int& nt) {
     for (int m : mts) {
       if (n == 1 && m > 3) continue;
       const long bm = 16 * m, mblocks = (M + bm - 1) / bm, pad = mblocks * bm;
-      if (mblocks * cols * zdim < LDSX_MIN_WGS) continue;
+      if (mblocks * cols * zdim < (K >= 2048 ? LDSX_MIN_WGS_LONGK : LDSX_MIN_WGS)) continue;
       const long area = (long)m * n;                  // compared as area * M / pad: padded rows are wasted work
       if (best_area == 0 || area * best_pad > best_area * pad || (area * best_pad == best_area * pad && pad < best_pad)) {
         best_area = area; best_pad = pad; mt = m; nt = n;
