@@ -189,7 +189,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every box here has one); "
-              "use --gpus 1.  How the path would shard is described in DESIGN.md.", file=sys.stderr)
+              "use --gpus 1.  The path shards by sequence (every GPU holds all weights and its slice of the batch).", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -10,7 +10,7 @@ LIB = os.path.join(HERE, "libbpd.so")
 SOURCES = [os.path.join(HERE, "csrc", "bpd.hip")]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
-    # packed-fp32 code generation is kept off on purpose (build flags)
+    # packed-fp32 code generation is kept off on purpose: some packed forms have given wrong results on this hardware
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-result",
 ]
