@@ -296,7 +296,15 @@ __global__ void gemm_f32_kernel(GemmP p, Epi e) {
   const float* X = (const float*)p.X + g * p.x_g + (long)m * p.ldx;
   const float* W = (const float*)p.W + g * p.w_g + n;
   float acc = 0.f;
-  for (int k = 0; k < p.K; ++k) acc = fmaf(X[k], W[(long)k * p.ldw], acc);
+  int k = 0;
+  for (; k + 8 <= p.K; k += 8) {               // eight loads in flight, then the same sequential sum as the tail loop
+    float xv[8], wv[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { xv[j] = X[k + j]; wv[j] = W[(long)(k + j) * p.ldw]; }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc = fmaf(xv[j], wv[j], acc);
+  }
+  for (; k < p.K; ++k) acc = fmaf(X[k], W[(long)k * p.ldw], acc);
   epi_store<float>(e, g, m, n, acc);
 }
 
@@ -309,7 +317,15 @@ __global__ __launch_bounds__(256) void vocab_argmax_f32_kernel(const float* O, i
   for (int v = threadIdx.x; v < V; v += blockDim.x) {
     const float* ev = E + (long)v * d;
     float acc = 0.f;
-    for (int c = 0; c < d; ++c) acc = fmaf(o[c], ev[c], acc);
+    int c = 0;
+    for (; c + 8 <= d; c += 8) {
+      float ov[8], wv[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { ov[j] = o[c + j]; wv[j] = ev[c + j]; }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc = fmaf(ov[j], wv[j], acc);
+    }
+    for (; c < d; ++c) acc = fmaf(o[c], ev[c], acc);
     if (logits) logits[(long)m * V + v] = acc;
     const unsigned long long key = argmax_key(acc, (unsigned)v);
     best = key > best ? key : best;
