@@ -273,8 +273,12 @@ void launch_skinny_cfg(const bpd_ctx* ctx, const GemmP& p, const Epi& e_in, cons
 template <int NT, bool XLN, bool ARGMAX>
 void launch_skinny(const bpd_ctx* ctx, const GemmP& p, const Epi& e, const LnP& ln, unsigned long long* keys, float* logits,
                    int groups) {
-  if (XLN) launch_skinny_cfg<1, NT, XLN, ARGMAX, 8, 4, 2>(ctx, p, e, ln, keys, logits, groups);            // K <= 1024
+  // waves x k-steps per wave cover K / 32 without idle slots (an idle slot still costs its clamped load)
+  if (XLN && p.K <= 512) launch_skinny_cfg<1, NT, XLN, ARGMAX, 4, 4, 2>(ctx, p, e, ln, keys, logits, groups);
+  else if (XLN) launch_skinny_cfg<1, NT, XLN, ARGMAX, 8, 4, 2>(ctx, p, e, ln, keys, logits, groups);       // K <= 1024
+  else if (p.K <= 512) launch_skinny_cfg<1, NT, false, ARGMAX, 4, 4, 2>(ctx, p, e, ln, keys, logits, groups);
   else if (p.K <= 1024) launch_skinny_cfg<1, NT, false, ARGMAX, 4, 8, 2>(ctx, p, e, ln, keys, logits, groups);
+  else if (p.K <= 2048) launch_skinny_cfg<1, NT, false, ARGMAX, 8, 8, 1>(ctx, p, e, ln, keys, logits, groups);
   else launch_skinny_cfg<1, NT, false, ARGMAX, 8, 16, 1>(ctx, p, e, ln, keys, logits, groups);             // K <= 4096
 }
 
