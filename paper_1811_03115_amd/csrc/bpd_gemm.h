@@ -62,16 +62,17 @@ __device__ __forceinline__ void argmax_tiles(const f32x4 (&acc)[MT][NT], int m0,
 // new values; a consumer adds the d/16 partials of a row in a fixed order.  This removes the
 // LayerNorm kernels and any cross-lane reduction over a whole row from the latency chain.
 //   stats[(tile * 16 + row) * 2 + {0,1}],  tile < K/16 <= 64, row < 16.
-__device__ __forceinline__ void row_stats(const float* stats, int K, float eps, int lane, float& mu, float& rstd) {
+__device__ __forceinline__ void row_stats_load(const float* stats, int K, int lane, float2 (&v)[16]) {
   const int m = lane & 15, part = lane >> 4, slots = K >> 4;
   // branch-free on purpose: conditional loads make the compiler wait for each one in turn
-  float2 v[16];
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
     const int t = part + 4 * i;
     v[i] = ((const float2*)stats)[(t < slots ? t : 0) * 16 + m];
   }
-  __builtin_amdgcn_sched_barrier(0);
+}
+__device__ __forceinline__ void row_stats_reduce(const float2 (&v)[16], int K, float eps, int lane, float& mu, float& rstd) {
+  const int part = lane >> 4, slots = K >> 4;
   float s = 0.f, q = 0.f;
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
@@ -83,6 +84,12 @@ __device__ __forceinline__ void row_stats(const float* stats, int K, float eps, 
   mu = s / K;
   const float var = fmaxf(q / K - mu * mu, 0.f);
   rstd = 1.0f / sqrtf(var + eps);
+}
+__device__ __forceinline__ void row_stats(const float* stats, int K, float eps, int lane, float& mu, float& rstd) {
+  float2 v[16];
+  row_stats_load(stats, K, lane, v);
+  __builtin_amdgcn_sched_barrier(0);
+  row_stats_reduce(v, K, eps, lane, mu, rstd);
 }
 
 struct LnP {
@@ -117,6 +124,18 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
   constexpr int TILES = MT * NT, OWN = (TILES + WAVES - 1) / WAVES;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   f32x4* red = (f32x4*)smem_raw;               // [2][WAVES][TILES][64]
+  // XLN: LayerNorm gain and bias (K <= 1024 floats each) reach the lanes through LDS: one 16-byte
+  // global load per thread instead of sixteen per lane (the address unit is the busy one here)
+  constexpr int GBL = (2 * 1024 / 4 + WAVES * 64 - 1) / (WAVES * 64);      // float4 loads per thread
+  __shared__ __attribute__((aligned(16))) float gb_s[XLN ? 2 * 1024 : 4];
+  static_assert(GBL <= 2, "gain/bias staging");
+  float4 gb0 = make_float4(0.f, 0.f, 0.f, 0.f), gb1 = gb0;   // (named scalars: an indexed array would live in scratch)
+  if (XLN) {
+    const int nv = p.K >> 2;                   // float4 per vector; thread index 0 .. 2*nv-1: gain then bias
+    const int i0 = threadIdx.x, i1 = threadIdx.x + WAVES * 64;
+    gb0 = ((const float4*)(i0 < nv ? ln.g : ln.b))[i0 < nv ? i0 : (i0 < 2 * nv ? i0 - nv : 0)];
+    if (GBL > 1) gb1 = ((const float4*)(i1 < nv ? ln.g : ln.b))[i1 < nv ? i1 : (i1 < 2 * nv ? i1 - nv : 0)];
+  }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = blockIdx.z;
   const int ntiles = p.N >> 4, ksteps = p.K >> 5;
@@ -173,15 +192,30 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
       const int ks = wave + WAVES * i;
       const int col = (ks < ksteps ? ks : 0) * 32 + lk;
 #pragma unroll
+      for (int hh = 0; hh < 2; ++hh) xv[i][hh] = *(const float4*)(ln.x + (long)mrow * p.K + col + 4 * hh);
+    }
+    float2 sv[16];
+    row_stats_load(ln.stats, p.K, lane, sv);
+    __builtin_amdgcn_sched_barrier(0);
+    {                                          // gain / bias were requested first, so they arrive first
+      const int nv = p.K >> 2;
+      const int i0 = threadIdx.x, i1 = threadIdx.x + WAVES * 64;
+      if (i0 < 2 * nv) *(float4*)&gb_s[i0 < nv ? 4 * i0 : 1024 + 4 * (i0 - nv)] = gb0;
+      if (GBL > 1 && i1 < 2 * nv) *(float4*)&gb_s[i1 < nv ? 4 * i1 : 1024 + 4 * (i1 - nv)] = gb1;
+    }
+    __syncthreads();
+    float mu, rstd;
+    row_stats_reduce(sv, p.K, ln.eps, lane, mu, rstd);
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      const int ks = wave + WAVES * i;
+      const int col = (ks < ksteps ? ks : 0) * 32 + lk;
+#pragma unroll
       for (int hh = 0; hh < 2; ++hh) {
-        xv[i][hh] = *(const float4*)(ln.x + (long)mrow * p.K + col + 4 * hh);
-        gv[i][hh] = *(const float4*)(ln.g + col + 4 * hh);
-        bv[i][hh] = *(const float4*)(ln.b + col + 4 * hh);
+        gv[i][hh] = *(const float4*)&gb_s[col + 4 * hh];
+        bv[i][hh] = *(const float4*)&gb_s[1024 + col + 4 * hh];
       }
     }
-    __builtin_amdgcn_sched_barrier(0);
-    float mu, rstd;
-    row_stats(ln.stats, p.K, ln.eps, lane, mu, rstd);
 #pragma unroll
     for (int i = 0; i < U; ++i) {
       float y[8];
