@@ -128,6 +128,7 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
   // global load per thread instead of sixteen per lane (the address unit is the busy one here)
   constexpr int GBL = (2 * 1024 / 4 + WAVES * 64 - 1) / (WAVES * 64);      // float4 loads per thread
   __shared__ __attribute__((aligned(16))) float gb_s[XLN ? 2 * 1024 : 4];
+  __shared__ __attribute__((aligned(16))) float st_s[XLN ? 64 * 16 * 2 : 4];     // the producer's partial statistics, same layout
   static_assert(GBL <= 2, "gain/bias staging");
   float4 gb0 = make_float4(0.f, 0.f, 0.f, 0.f), gb1 = gb0;   // (named scalars: an indexed array would live in scratch)
   if (XLN) {
@@ -135,6 +136,13 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
     const int i0 = threadIdx.x, i1 = threadIdx.x + WAVES * 64;
     gb0 = ((const float4*)(i0 < nv ? ln.g : ln.b))[i0 < nv ? i0 : (i0 < 2 * nv ? i0 - nv : 0)];
     if (GBL > 1) gb1 = ((const float4*)(i1 < nv ? ln.g : ln.b))[i1 < nv ? i1 : (i1 < 2 * nv ? i1 - nv : 0)];
+  }
+  float4 st0 = make_float4(0.f, 0.f, 0.f, 0.f), st1 = st0;   // statistics: (K/16) * 8 float4 in all
+  if (XLN) {
+    const int ns4 = (p.K >> 4) * 8;
+    const int i0 = threadIdx.x, i1 = threadIdx.x + WAVES * 64;
+    st0 = ((const float4*)ln.stats)[i0 < ns4 ? i0 : 0];
+    if (GBL > 1) st1 = ((const float4*)ln.stats)[i1 < ns4 ? i1 : 0];
   }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = blockIdx.z;
@@ -194,16 +202,19 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh) xv[i][hh] = *(const float4*)(ln.x + (long)mrow * p.K + col + 4 * hh);
     }
-    float2 sv[16];
-    row_stats_load(ln.stats, p.K, lane, sv);
     __builtin_amdgcn_sched_barrier(0);
     {                                          // gain / bias were requested first, so they arrive first
       const int nv = p.K >> 2;
       const int i0 = threadIdx.x, i1 = threadIdx.x + WAVES * 64;
       if (i0 < 2 * nv) *(float4*)&gb_s[i0 < nv ? 4 * i0 : 1024 + 4 * (i0 - nv)] = gb0;
       if (GBL > 1 && i1 < 2 * nv) *(float4*)&gb_s[i1 < nv ? 4 * i1 : 1024 + 4 * (i1 - nv)] = gb1;
+      const int ns4 = (p.K >> 4) * 8;
+      if (i0 < ns4) *(float4*)&st_s[4 * i0] = st0;
+      if (GBL > 1 && i1 < ns4) *(float4*)&st_s[4 * i1] = st1;
     }
     __syncthreads();
+    float2 sv[16];
+    row_stats_load(st_s, p.K, lane, sv);       // from LDS now
     float mu, rstd;
     row_stats_reduce(sv, p.K, ln.eps, lane, mu, rstd);
 #pragma unroll
