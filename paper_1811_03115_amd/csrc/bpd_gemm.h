@@ -128,7 +128,9 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
   // global load per thread instead of sixteen per lane (the address unit is the busy one here)
   constexpr int GBL = (2 * 1024 / 4 + WAVES * 64 - 1) / (WAVES * 64);      // float4 loads per thread
   __shared__ __attribute__((aligned(16))) float gb_s[XLN ? 2 * 1024 : 4];
-  __shared__ __attribute__((aligned(16))) float st_s[XLN ? 64 * 16 * 2 : 4];     // the producer's partial statistics, same layout
+  // partial LayerNorm statistics of the residual stream (XLN: of the input; otherwise of the epilogue's LayerNorm-ed
+  // residual operand, if any), same layout as in global memory
+  __shared__ __attribute__((aligned(16))) float st_s[(XLN || !ARGMAX) ? 64 * 16 * 2 : 4];
   static_assert(GBL <= 2, "gain/bias staging");
   float4 gb0 = make_float4(0.f, 0.f, 0.f, 0.f), gb1 = gb0;   // (named scalars: an indexed array would live in scratch)
   if (XLN) {
@@ -138,11 +140,13 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
     if (GBL > 1) gb1 = ((const float4*)(i1 < nv ? ln.g : ln.b))[i1 < nv ? i1 : (i1 < 2 * nv ? i1 - nv : 0)];
   }
   float4 st0 = make_float4(0.f, 0.f, 0.f, 0.f), st1 = st0;   // statistics: (K/16) * 8 float4 in all
-  if (XLN) {
-    const int ns4 = (p.K >> 4) * 8;
+  const bool epi_ln = !XLN && !ARGMAX && e.mode == 0 && e.lnR_stats != nullptr;
+  if (XLN || epi_ln) {
+    const float* sp_ = XLN ? ln.stats : e.lnR_stats;
+    const int ns4 = ((XLN ? p.K : e.lnR_K) >> 4) * 8;
     const int i0 = threadIdx.x, i1 = threadIdx.x + WAVES * 64;
-    st0 = ((const float4*)ln.stats)[i0 < ns4 ? i0 : 0];
-    if (GBL > 1) st1 = ((const float4*)ln.stats)[i1 < ns4 ? i1 : 0];
+    st0 = ((const float4*)sp_)[i0 < ns4 ? i0 : 0];
+    if (GBL > 1) st1 = ((const float4*)sp_)[i1 < ns4 ? i1 : 0];
   }
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = blockIdx.z;
@@ -253,6 +257,12 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
       }
     }
     __builtin_amdgcn_sched_barrier(0);
+    if (epi_ln) {                              // read back after the barrier that follows the first group's MFMAs
+      const int ns4 = (e.lnR_K >> 4) * 8;
+      const int i0 = threadIdx.x, i1 = threadIdx.x + WAVES * 64;
+      if (i0 < ns4) *(float4*)&st_s[4 * i0] = st0;
+      if (GBL > 1 && i1 < ns4) *(float4*)&st_s[4 * i1] = st1;
+    }
   }
 
   unsigned long long best_run[OWN];
@@ -285,7 +295,10 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
       for (int u = 0; u < NT; ++u) rb[(wave * TILES + t * NT + u) * 64 + lane] = acc[t][u];
     __syncthreads();
     float mu = 0.f, rstd = 1.f;
-    if (plain_epi && e.lnR_stats && wave < TILES) row_stats(e.lnR_stats, e.lnR_K, e.lnR_eps, lane, mu, rstd);
+    if (plain_epi && e.lnR_stats && wave < TILES) {
+      if (XLN) row_stats(e.lnR_stats, e.lnR_K, e.lnR_eps, lane, mu, rstd);
+      else row_stats(st_s, e.lnR_K, e.lnR_eps, lane, mu, rstd);
+    }
 #pragma unroll
     for (int j = 0; j < OWN; ++j) {
       const int id = wave + WAVES * j;
