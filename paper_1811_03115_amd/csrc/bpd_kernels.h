@@ -780,7 +780,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p) {
   const int lr = lane & 15, lq = lane >> 4;
   const bf16_t* Kb = (const bf16_t*)p.Kc + b * p.kv_seq_stride + h * DH;
   const bf16_t* Vb = (const bf16_t*)p.Vc + b * p.kv_seq_stride + h * DH;
-  // first chunk: K fragments (4 key tiles x 2 halves of the head dimension) and this thread's V row
+  // first chunk: K fragments (4 key tiles x 2 halves of the head dimension) and this thread's 8 pieces of V rows
   uint4 kf[4][2], vraw[8];
 #define BPD_LOAD_KV(c0)                                                                         \
   {                                                                                             \
@@ -790,10 +790,11 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p) {
       const bf16_t* kp = Kb + (long)key * p.d + 8 * lq;                                         \
       kf[kt][0] = *(const uint4*)kp; kf[kt][1] = *(const uint4*)(kp + 32);                      \
     }                                                                                           \
-    int vkey = (c0) + tid;                                                                      \
-    vkey = vkey < p.cap ? vkey : p.cap - 1;                                                     \
-    const uint4* vp = (const uint4*)(Vb + (long)vkey * p.d);                                    \
-    _Pragma("unroll") for (int x = 0; x < 8; ++x) vraw[x] = vp[x];                              \
+    _Pragma("unroll") for (int x = 0; x < 8; ++x) {       /* 8 lanes per V row: a wave-load covers 8 whole rows */ \
+      int vkey = (c0) + (tid >> 3) + 32 * x;                                                    \
+      vkey = vkey < p.cap ? vkey : p.cap - 1;                                                   \
+      vraw[x] = *(const uint4*)(Vb + (long)vkey * p.d + 8 * (tid & 7));                         \
+    }                                                                                           \
   }
   BPD_LOAD_KV(first)
   // queries: row lr (clamped), head dimensions 32s + 8*lq .. +8, scaled, as bf16 hi + lo
@@ -843,12 +844,12 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p) {
       *(float4*)&sc[lr][kl] = o;
     }
     {
-      const bool live = c0 + tid < nkeys;
 #pragma unroll
       for (int x = 0; x < 8; ++x) {
-        const uint4 v = live ? vraw[x] : make_uint4(0, 0, 0, 0);
-        *(uint2*)&vs[tid][8 * x] = make_uint2(v.x, v.y);
-        *(uint2*)&vs[tid][8 * x + 4] = make_uint2(v.z, v.w);
+        const int kl = (tid >> 3) + 32 * x;                   // chunk-local key of this piece
+        const uint4 v = c0 + kl < nkeys ? vraw[x] : make_uint4(0, 0, 0, 0);
+        *(uint2*)&vs[kl][8 * (tid & 7)] = make_uint2(v.x, v.y);
+        *(uint2*)&vs[kl][8 * (tid & 7) + 4] = make_uint2(v.z, v.w);
       }
     }
     __syncthreads();
