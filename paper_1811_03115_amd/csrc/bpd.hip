@@ -390,8 +390,10 @@ void layernorm(bpd_ctx* ctx, float* x, LnW w, int M, void* ya, float* yf);
 // Y = epilogue(LayerNorm(x) W).  Block of <= 16 rows: LayerNorm is applied inside the skinny
 // kernel from the partial statistics the producer of x left in L.stats_ln.  Otherwise a
 // LayerNorm kernel (into `xn`, and `yf` in fp32 if given) followed by the GEMM.
-void gemm_ln(bpd_ctx* ctx, float* x, LnW w, void* xn, float* yf, GemmP p, const Epi& e) {
-  if (stats_path(ctx, p.M) && p.K == ctx->cfg.d_model) {
+void gemm_ln(bpd_ctx* ctx, float* x, LnW w, void* xn, float* yf, GemmP p, const Epi& e, bool with_stats) {
+  // with_stats: the producer of x left its partial LayerNorm statistics in L.stats_ln (decoder block of one
+  // row tile only; the encoder's kernels do not write them)
+  if (with_stats && stats_path(ctx, p.M) && p.K == ctx->cfg.d_model) {
     LnP ln{x, w.g, w.b, ctx->lay.stats_ln, ctx->cfg.ln_eps};
     if (p.N / 16 >= 2048) launch_skinny<2, true, false>(ctx, p, e, ln, nullptr, nullptr, 1);
     else launch_skinny<1, true, false>(ctx, p, e, ln, nullptr, nullptr, 1);
@@ -599,15 +601,15 @@ int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
       char* cK = (char*)L.crossK + (size_t)l * c.max_batch * c.max_src_len * d * as;
       char* cV = (char*)L.crossV + (size_t)l * c.max_batch * c.max_src_len * d * as;
       // self-attention sublayer: K/V of the block rows go straight into the cache at L_b + i'
-      gemm_ln(ctx, L.x, w.ln1, L.xn, nullptr, gp(L.xn, d, w.wqkv, 3 * d, M, 3 * d, d), split(L.q, Kl, Vl, d, 0, R, slots, L.L));
+      gemm_ln(ctx, L.x, w.ln1, L.xn, nullptr, gp(L.xn, d, w.wqkv, 3 * d, M, 3 * d, d), split(L.q, Kl, Vl, d, 0, R, slots, L.L), sp);
       attention(ctx, L.q, Kl, Vl, L.attn, slots, B, R, L.L, 1);
       gemm(ctx, gp(L.attn, d, w.wo, d, M, d, d), residual(nullptr));
       // cross-attention sublayer over the encoder memory
-      gemm_ln(ctx, L.x, w.ln2, L.xn, nullptr, gp(L.xn, d, w.cq, d, M, d, d), plain(nullptr, 0, nullptr, 0, L.q, d, nullptr, 0));
+      gemm_ln(ctx, L.x, w.ln2, L.xn, nullptr, gp(L.xn, d, w.cq, d, M, d, d), plain(nullptr, 0, nullptr, 0, L.q, d, nullptr, 0), sp);
       attention(ctx, L.q, cK, cV, L.attn, c.max_src_len, B, R, L.src_len, 0);
       gemm(ctx, gp(L.attn, d, w.co, d, M, d, d), residual(nullptr));
       // feed-forward sublayer
-      gemm_ln(ctx, L.x, w.ln3, L.xn, nullptr, gp(L.xn, d, w.w1, F, M, F, d), plain(w.b1, 1, nullptr, 0, nullptr, 0, L.ffh, F));
+      gemm_ln(ctx, L.x, w.ln3, L.xn, nullptr, gp(L.xn, d, w.w1, F, M, F, d), plain(w.b1, 1, nullptr, 0, nullptr, 0, L.ffh, F), sp);
       gemm(ctx, gp(L.ffh, F, w.w2, d, M, d, F), residual(w.b2));
     }
   }
@@ -617,7 +619,7 @@ int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
   {
     PhaseTimer t(ctx, BPD_PHASE_HEAD_HIDDEN);
     gemm_ln(ctx, L.x, L.dec_lnf, L.hn, L.h, gp(L.hn, d, L.hw1, c.k_max * F, M, k * F, d),
-            plain(L.hb1, 1, nullptr, 0, nullptr, 0, L.H, k * F));
+            plain(L.hb1, 1, nullptr, 0, nullptr, 0, L.H, k * F), sp);
   }
   {
     PhaseTimer t(ctx, BPD_PHASE_HEAD_OUT);
@@ -676,10 +678,10 @@ int encoder(bpd_ctx* ctx) {
   embed(ctx, L.src_ids, S, nullptr, S, M, L.pos_src, L.xe, 0);
   for (int l = 0; l < c.n_enc_layers; ++l) {
     EncL& w = L.enc[l];
-    gemm_ln(ctx, L.xe, w.ln1, L.xen, nullptr, gp(L.xen, d, w.wqkv, 3 * d, M, 3 * d, d), split(L.qe, L.ke, L.ve, d, 0, S, S, nullptr));
+    gemm_ln(ctx, L.xe, w.ln1, L.xen, nullptr, gp(L.xen, d, w.wqkv, 3 * d, M, 3 * d, d), split(L.qe, L.ke, L.ve, d, 0, S, S, nullptr), false);
     attention(ctx, L.qe, L.ke, L.ve, L.attne, S, B, S, L.src_len, 0);
     gemm(ctx, gp(L.attne, d, w.wo, d, M, d, d), plain(nullptr, 0, L.xe, d, L.xe, d, nullptr, 0));
-    gemm_ln(ctx, L.xe, w.ln2, L.xen, nullptr, gp(L.xen, d, w.w1, F, M, F, d), plain(w.b1, 1, nullptr, 0, nullptr, 0, L.ffhe, F));
+    gemm_ln(ctx, L.xe, w.ln2, L.xen, nullptr, gp(L.xen, d, w.w1, F, M, F, d), plain(w.b1, 1, nullptr, 0, nullptr, 0, L.ffhe, F), false);
     gemm(ctx, gp(L.ffhe, F, w.w2, d, M, d, F), plain(w.b2, 0, L.xe, d, L.xe, d, nullptr, 0));
   }
   layernorm(ctx, L.xe, L.enc_lnf, M, L.mem, nullptr);

@@ -331,3 +331,37 @@ def test_degenerate_shapes():
     for _ in range(5):
         if not ls.done[0]:
             assert ls.step().tolist() == [1]
+
+
+# Odd shapes: row counts on both sides of one MFMA tile, K that is not a multiple of 64 / 128 / 256 (the
+# GEMM falls back to other tiles or kernels), 16-wide heads in bf16, the largest k, a vocabulary that is
+# not a multiple of the column tile, a single source token.
+ODD_SHAPES = [
+    wl.Config("odd-d192", 21, 1, 2, 192, 3, 96, 1008, 5, 4, 9, 20, "bf16", 2, src_len_kind="lognormal"),
+    wl.Config("odd-d320", 22, 1, 1, 320, 5, 640, 4112, 7, 9, 14, 21, "bf16", 2, src_len_kind="lognormal"),
+    wl.Config("odd-dh16", 23, 2, 2, 128, 8, 256, 528, 3, 2, 7, 12, "bf16", 2, src_len_kind="lognormal"),
+    wl.Config("odd-k16", 24, 1, 1, 512, 8, 2048, 1024, 16, 1, 11, 40, "bf16", 2),
+    wl.Config("odd-b17", 25, 1, 1, 64, 1, 2112, 272, 1, 17, 5, 6, "bf16", 2, src_len_kind="lognormal"),
+]
+
+
+@pytest.mark.parametrize("cfg", ODD_SHAPES, ids=lambda c: c.name)
+def test_lockstep_odd_shapes(cfg):
+    weights = wl.make_weights(cfg, std=0.02)
+    ctx = gpu_context(cfg, weights)
+    src, n = ragged_sources(cfg, 9)
+    max_len = np.array([max(1, cfg.max_out - 2 * b) for b in range(cfg.batch)], dtype=np.int32)
+    ls = LockStep(cfg, weights, ctx, src, n, max_len)
+    sched = wl.make_schedule(cfg, min(2.0, cfg.k), 16, seed=4)
+    for s in range(4):
+        ls.step(imposed=sched[s])
+    for s in range(3):
+        ls.step(imposed=None)
+    for s in range(cfg.max_out):
+        if all(ls.done.values()):
+            break
+        ls.step(imposed=np.full(cfg.batch, cfg.k, dtype=np.int32), check_logits=False)
+    assert all(ls.done.values())
+    st = ctx.bpd_get_stats()
+    assert st.finished == cfg.batch and st.accepted_total == sum(len(p) for p in ls.prefix.values())
+    print(cfg.name, "max logit err", ls.max_logit_err, "bit-identical argmax fraction", np.mean(ls.match))
