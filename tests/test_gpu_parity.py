@@ -220,11 +220,12 @@ def test_top_n_acceptance_on_gpu():
     assert st.steps <= -(-cfg.max_out // cfg.k)          # n = vocab accepts every proposal: full blocks
 
 
-def test_two_phase_scoring_on_gpu():
+@pytest.mark.parametrize("which", ["M-bf16", "odd-d320", "odd-d192"])
+def test_two_phase_scoring_on_gpu(which):
     """Two-phase scoring (p_1 at all block rows, then the other heads at row k-hat only) yields the same
     accepted lengths, tokens and next proposals as the k x k table, under exact matching and under an
     imposed schedule; the reported table holds column 1 and row k-hat."""
-    cfg = MID_BF16
+    cfg = {c.name: c for c in [MID_BF16] + ODD_SHAPES}[which]
     weights = wl.make_weights(cfg)
     ctx = gpu_context(cfg, weights)
     src, n = ragged_sources(cfg, 8)
