@@ -122,8 +122,11 @@ size_t build_layout(const bpd_config& c, char* base, Layout& L) {
   L.out_ids = ints(B * (size_t)c.max_out_len); L.step_counter = ints(1); L.imposed1 = ints(B);
   L.sched = ints(B * (size_t)c.max_out_len);
   L.stats = (long long*)a.take(32 * 8);
-  size_t biggest = V * d;
+  size_t biggest = V * d;                    // largest tensor a bpd_load_weights call may stage (elements)
   if (k * d * F > biggest) biggest = k * d * F;
+  if (slots * d > biggest) biggest = slots * d;
+  if (S * d > biggest) biggest = S * d;
+  if (3 * d * d > biggest) biggest = 3 * d * d;
   L.staging_bytes = biggest * 4;
   L.staging = a.take(L.staging_bytes);
   L.total = (a.off + ALIGN - 1) / ALIGN * ALIGN;

@@ -253,3 +253,23 @@ def test_measured_peaks_are_plausible():
     tf = binding.Context.bpd_measure_mfma_bf16(2000)
     assert 500 < gbps < 8000 * 1.05            # cannot beat the published HBM peak (a 256 MiB buffer may sit in the last-level cache: allow a little)
     assert 100 < tf < 2500 * 1.05
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_long_cache_with_16_wide_heads(dtype):
+    """The scalar attention kernel (16-wide heads) over a cache of several 256-key chunks dealt to
+    several workgroups per head and merged by the combine kernel, fixed-length decoding."""
+    cfg = wl.Config("long-dh16-" + dtype, 31, 1, 2, 64, 4, 128, 272, 4, 2, 6, 900, dtype, -1, src_kind="uniform0")
+    weights = wl.make_weights(cfg, std=0.08 if dtype == "f32" else 0.02)
+    ctx = gpu_context(cfg, weights)
+    model = oracle_model(cfg, weights)
+    src, n = wl.make_sources(cfg)
+    ctx.bpd_encode(src, n)
+    full = np.full(cfg.batch, cfg.k, np.int32)
+    for target in (300, 700, 880):
+        while int(ctx.bpd_get_state()[2][0]) + cfg.k <= target:
+            ctx.bpd_step(cfg.k, full)
+        err = check_state_against_oracle(ctx, cfg, model, src, n, 1, cfg.k)
+        print(cfg.name, "j =", int(ctx.bpd_get_state()[2][1]), "logit err", err)
+    out_ids, out_len, st = ctx.bpd_decode(cfg.k)
+    assert (out_len == 900).all() and st.finished == cfg.batch
