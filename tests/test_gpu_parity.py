@@ -366,3 +366,40 @@ def test_lockstep_odd_shapes(cfg):
     st = ctx.bpd_get_stats()
     assert st.finished == cfg.batch and st.accepted_total == sum(len(p) for p in ls.prefix.values())
     print(cfg.name, "max logit err", ls.max_logit_err, "bit-identical argmax fraction", np.mean(ls.match))
+
+
+def random_config(seed):
+    """A small model with randomly drawn dimensions inside what bpd_create accepts."""
+    rng = np.random.default_rng(1000 + seed)
+    dtype = "f32" if seed % 4 == 3 else "bf16"
+    dh = 16 if (dtype == "f32" or rng.random() < 0.3) else 64
+    heads = int(rng.integers(1, 9 if dh == 16 else 6))
+    d = dh * heads
+    if d % 32:
+        heads += 1
+        d = dh * heads
+    F = 32 * int(rng.integers(1, 34))
+    V = 16 * int(rng.integers(2, 160))
+    k = int(rng.integers(1, 17))
+    B = int(rng.integers(1, 21))
+    return wl.Config(f"rnd{seed}-{dtype}-d{d}-h{heads}-F{F}-V{V}-k{k}-B{B}", 40 + seed, int(rng.integers(1, 3)), int(rng.integers(1, 3)),
+                     d, heads, F, V, k, B, int(rng.integers(1, 21)), int(rng.integers(5, 41)), dtype, 2,
+                     src_kind="uniform3", src_len_kind="lognormal")
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_lockstep_random_shapes(seed):
+    cfg = random_config(seed)
+    weights = wl.make_weights(cfg, std=0.08 if cfg.dtype == "f32" else 0.02)
+    ctx = gpu_context(cfg, weights)
+    src, n = ragged_sources(cfg, 11 + seed)
+    rng = np.random.default_rng(seed)
+    max_len = rng.integers(1, cfg.max_out + 1, size=cfg.batch).astype(np.int32)
+    sample = sorted(set(rng.integers(0, cfg.batch, size=3).tolist()))
+    ls = LockStep(cfg, weights, ctx, src, n, max_len, sample=sample)
+    sched = wl.make_schedule(cfg, min(2.0, cfg.k), 8, seed=seed)
+    for s in range(3):
+        ls.step(imposed=sched[s])
+    for s in range(2):
+        ls.step(imposed=None)
+    print(cfg.name, "max logit err", ls.max_logit_err, "bit-identical argmax fraction", np.mean(ls.match))
