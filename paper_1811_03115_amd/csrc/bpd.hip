@@ -154,6 +154,7 @@ struct bpd_ctx {
   bool encoded = false;
   int64_t steps = 0;
   int distance_eps = 0, min_block = 1, top_n = 1, two_phase = 0;
+  bool weights_exceed_llc = false;     // decoder-side weights read per step > 192 MB (the Infinity Cache holds 256 MB)
   const int* cur_imposed = nullptr; int cur_imposed_stride = 0, cur_imposed_step = 0;   // of the step being run
   int* pinned = nullptr;       // small pinned host scratch
   int prof_phase = 0;
@@ -247,7 +248,7 @@ void launch_gemm_bf16(const GemmP& p, const Epi& e, int groups, hipStream_t s) {
 }
 
 // ---- skinny path: M <= 16 -------------------------------------------------------------
-template <int MT, int NT, bool XLN, bool ARGMAX, int WAVES, int U, int DEPTH>
+template <int MT, int NT, bool XLN, bool ARGMAX, int WAVES, int U, int DEPTH, bool STREAM>
 void launch_skinny_cfg(const bpd_ctx* ctx, const GemmP& p, const Epi& e_in, const LnP& ln, unsigned long long* keys,
                        float* logits, int groups, int cap = 512) {
   hipStream_t s = ctx->stream;
@@ -260,12 +261,12 @@ void launch_skinny_cfg(const bpd_ctx* ctx, const GemmP& p, const Epi& e_in, cons
   dim3 grid(gx, (p.M + 16 * MT - 1) / (16 * MT), groups);
   const size_t lds = (size_t)2 * WAVES * MT * NT * 1024;
   if (ngroups > gx) {
-    auto k = skinny_gemm_kernel<MT, NT, XLN, ARGMAX, WAVES, U, DEPTH>;
+    auto k = skinny_gemm_kernel<MT, NT, XLN, ARGMAX, WAVES, U, DEPTH, STREAM>;
     static bool attr = false;
     if (!attr) { (void)hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); attr = true; }
     hipLaunchKernelGGL(k, grid, dim3(64 * WAVES), lds, s, p, e, ln, keys, logits);
   } else {
-    auto k = skinny_gemm_kernel<MT, NT, XLN, ARGMAX, WAVES, U, 0>;
+    auto k = skinny_gemm_kernel<MT, NT, XLN, ARGMAX, WAVES, U, 0, STREAM>;
     static bool attr = false;
     if (!attr) { (void)hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); attr = true; }
     hipLaunchKernelGGL(k, grid, dim3(64 * WAVES), lds, s, p, e, ln, keys, logits);
@@ -273,16 +274,24 @@ void launch_skinny_cfg(const bpd_ctx* ctx, const GemmP& p, const Epi& e_in, cons
 }
 
 // One 16-row tile (M <= 16): K split over the waves so that each wave holds all its k-steps.
+template <int NT, bool XLN, bool ARGMAX, bool STREAM>
+void launch_skinny_s(const bpd_ctx* ctx, const GemmP& p, const Epi& e, const LnP& ln, unsigned long long* keys, float* logits,
+                     int groups) {
+  // waves x k-steps per wave cover K / 32 without idle slots (an idle slot still costs its clamped load)
+  if (XLN && p.K <= 512) launch_skinny_cfg<1, NT, XLN, ARGMAX, 4, 4, 2, STREAM>(ctx, p, e, ln, keys, logits, groups);
+  else if (XLN) launch_skinny_cfg<1, NT, XLN, ARGMAX, 8, 4, 2, STREAM>(ctx, p, e, ln, keys, logits, groups);       // K <= 1024
+  else if (p.K <= 512) launch_skinny_cfg<1, NT, false, ARGMAX, 4, 4, 2, STREAM>(ctx, p, e, ln, keys, logits, groups);
+  else if (p.K <= 1024) launch_skinny_cfg<1, NT, false, ARGMAX, 4, 8, 2, STREAM>(ctx, p, e, ln, keys, logits, groups);
+  else if (p.K <= 2048) launch_skinny_cfg<1, NT, false, ARGMAX, 8, 8, 1, STREAM>(ctx, p, e, ln, keys, logits, groups);
+  else launch_skinny_cfg<1, NT, false, ARGMAX, 8, 16, 1, STREAM>(ctx, p, e, ln, keys, logits, groups);             // K <= 4096
+}
+// Streams of at least 32 MB in a model whose per-step weights exceed the last-level cache bypass it.
 template <int NT, bool XLN, bool ARGMAX>
 void launch_skinny(const bpd_ctx* ctx, const GemmP& p, const Epi& e, const LnP& ln, unsigned long long* keys, float* logits,
                    int groups) {
-  // waves x k-steps per wave cover K / 32 without idle slots (an idle slot still costs its clamped load)
-  if (XLN && p.K <= 512) launch_skinny_cfg<1, NT, XLN, ARGMAX, 4, 4, 2>(ctx, p, e, ln, keys, logits, groups);
-  else if (XLN) launch_skinny_cfg<1, NT, XLN, ARGMAX, 8, 4, 2>(ctx, p, e, ln, keys, logits, groups);       // K <= 1024
-  else if (p.K <= 512) launch_skinny_cfg<1, NT, false, ARGMAX, 4, 4, 2>(ctx, p, e, ln, keys, logits, groups);
-  else if (p.K <= 1024) launch_skinny_cfg<1, NT, false, ARGMAX, 4, 8, 2>(ctx, p, e, ln, keys, logits, groups);
-  else if (p.K <= 2048) launch_skinny_cfg<1, NT, false, ARGMAX, 8, 8, 1>(ctx, p, e, ln, keys, logits, groups);
-  else launch_skinny_cfg<1, NT, false, ARGMAX, 8, 16, 1>(ctx, p, e, ln, keys, logits, groups);             // K <= 4096
+  const size_t wbytes = (size_t)p.K * p.N * groups * 2;
+  if (ctx->weights_exceed_llc && wbytes >= ((size_t)32 << 20)) launch_skinny_s<NT, XLN, ARGMAX, true>(ctx, p, e, ln, keys, logits, groups);
+  else launch_skinny_s<NT, XLN, ARGMAX, false>(ctx, p, e, ln, keys, logits, groups);
 }
 
 bool skinny_ok(const bpd_ctx* ctx, const GemmP& p) { return ctx->cfg.dtype == BPD_BF16 && p.M <= 16 && p.K <= 4096; }
@@ -735,6 +744,11 @@ int bpd_create(const bpd_config* cfg, void* workspace, size_t workspace_bytes, v
   ctx->stream = (hipStream_t)hip_stream;
   build_layout(*cfg, (char*)workspace, ctx->lay);
   build_table(ctx);
+  {
+    const size_t d = cfg->d_model, F = cfg->d_ff, V = cfg->vocab, k = cfg->k_max;
+    const size_t step_weights = ((size_t)cfg->n_dec_layers * (6 * d * d + 2 * d * F) + 2 * k * d * F + V * d) * act_size(*cfg);
+    ctx->weights_exceed_llc = step_weights > ((size_t)192 << 20);
+  }
   (void)hipMemsetAsync(ctx->lay.zeros, 0, ctx->lay.n_zeros * 4, ctx->stream);
   (void)hipMemsetAsync(ctx->lay.stats_ln, 0, 64 * 16 * 2 * 4, ctx->stream);
   if (hipHostMalloc((void**)&ctx->pinned, 64 * sizeof(int), hipHostMallocDefault) != hipSuccess) {

@@ -118,7 +118,11 @@ __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) { return (unsi
 // Epilogue (mode 0) additionally supports: R = LayerNorm(R) via e.lnR_* (the heads' residual
 // is the normalised decoder output), and writing partial LayerNorm statistics of the result.
 // Dynamic LDS: 2 * WAVES * MT * NT * 1024 bytes.
-template <int MT, int NT, bool XLN, bool ARGMAX, int WAVES, int U, int DEPTH>
+typedef unsigned int u32x4_nt __attribute__((ext_vector_type(4)));
+// STREAM: the weight tiles are fetched with non-temporal loads.  A weight matrix that is read once
+// per step and does not fit the last-level cache together with the rest of the model (the heads of
+// Transformer-big) would otherwise evict the decoder layers' weights from it every step.
+template <int MT, int NT, bool XLN, bool ARGMAX, int WAVES, int U, int DEPTH, bool STREAM>
 __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e, LnP ln, unsigned long long* keys,
                                                                   float* logits) {
   constexpr int TILES = MT * NT, OWN = (TILES + WAVES - 1) / WAVES;
@@ -167,7 +171,8 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
     const int ksc_ = ks_ < ksteps ? ks_ : ksteps - 1;                                       \
     _Pragma("unroll") for (int u = 0; u < NT; ++u) {                                        \
       int t_ = (tile0) + u; t_ = t_ < ntiles ? t_ : ntiles - 1;                             \
-      dst[i][u] = W[((long)t_ * ksteps + ksc_) * 64];                                       \
+      if (STREAM) dst[i][u] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_nt*)&W[((long)t_ * ksteps + ksc_) * 64])); \
+      else dst[i][u] = W[((long)t_ * ksteps + ksc_) * 64];                                  \
     }                                                                                       \
   }
   BPD_LOAD_A(a[0], nt0)                         // weights first: they do not depend on the producer kernel
