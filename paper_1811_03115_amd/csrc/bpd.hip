@@ -484,7 +484,10 @@ void attention(bpd_ctx* ctx, const float* Q, const void* Kc, const void* Vc, voi
   dim3 grid(c.n_heads, B, tiles * nsplit), cgrid(c.n_heads, B, tiles);
   if (c.dtype == BPD_BF16) {
     if (dh == 64) {
-      hipLaunchKernelGGL(attention_mfma_kernel, grid, dim3(256), 0, ctx->stream, p);
+      // a K/V buffer beyond half the last-level cache is streamed past it
+      const size_t kv_bytes = (size_t)2 * c.n_dec_layers * B * cap * c.d_model * 2;
+      if (causal && kv_bytes > ((size_t)128 << 20)) hipLaunchKernelGGL(attention_mfma_kernel<true>, grid, dim3(256), 0, ctx->stream, p);
+      else hipLaunchKernelGGL(attention_mfma_kernel<false>, grid, dim3(256), 0, ctx->stream, p);
       if (nsplit > 1) hipLaunchKernelGGL((attention_combine_kernel<bf16_t, 64>), cgrid, dim3(256), 0, ctx->stream, p);
     } else {
       hipLaunchKernelGGL((attention_kernel<bf16_t, 16>), grid, dim3(256), 0, ctx->stream, p);

@@ -767,6 +767,10 @@ __device__ __forceinline__ void split_bf16x8(const float (&v)[8], bf16x8& hi, bf
   lo = __builtin_bit_cast(bf16x8, make_uint4(l[0], l[1], l[2], l[3]));
 }
 
+// KVNT: K and V are fetched with non-temporal loads (a cache too large for the last-level cache is a
+// stream that should not evict the weights).
+typedef unsigned int u32x4_kv __attribute__((ext_vector_type(4)));
+template <bool KVNT>
 __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p) {
   constexpr int RT = 16, CH = 256, DH = 64, SLD = CH + 4, VLD = DH + 4;
   __shared__ __attribute__((aligned(16))) float sc[RT][SLD];
@@ -788,12 +792,19 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p) {
       int key = (c0) + wave * 64 + kt * 16 + lr;                                                \
       key = key < p.cap ? key : p.cap - 1;                                                      \
       const bf16_t* kp = Kb + (long)key * p.d + 8 * lq;                                         \
-      kf[kt][0] = *(const uint4*)kp; kf[kt][1] = *(const uint4*)(kp + 32);                      \
+      if (KVNT) {                                                                               \
+        kf[kt][0] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_kv*)kp));     \
+        kf[kt][1] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_kv*)(kp + 32))); \
+      } else {                                                                                  \
+        kf[kt][0] = *(const uint4*)kp; kf[kt][1] = *(const uint4*)(kp + 32);                    \
+      }                                                                                         \
     }                                                                                           \
     _Pragma("unroll") for (int x = 0; x < 8; ++x) {       /* 8 lanes per V row: a wave-load covers 8 whole rows */ \
       int vkey = (c0) + (tid >> 3) + 32 * x;                                                    \
       vkey = vkey < p.cap ? vkey : p.cap - 1;                                                   \
-      vraw[x] = *(const uint4*)(Vb + (long)vkey * p.d + 8 * (tid & 7));                         \
+      const bf16_t* vp_ = Vb + (long)vkey * p.d + 8 * (tid & 7);                                \
+      if (KVNT) vraw[x] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_kv*)vp_)); \
+      else vraw[x] = *(const uint4*)vp_;                                                        \
     }                                                                                           \
   }
   BPD_LOAD_KV(first)
