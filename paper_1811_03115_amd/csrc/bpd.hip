@@ -154,6 +154,7 @@ struct bpd_ctx {
   bool encoded = false;
   int64_t steps = 0;
   int distance_eps = 0, min_block = 1, top_n = 1, two_phase = 0;
+  int num_cus = 256;                   // compute units of the device the context was created on
   bool weights_exceed_llc = false;     // decoder-side weights read per step > 192 MB (the Infinity Cache holds 256 MB)
   const int* cur_imposed = nullptr; int cur_imposed_stride = 0, cur_imposed_step = 0;   // of the step being run
   int* pinned = nullptr;       // small pinned host scratch
@@ -295,6 +296,38 @@ void launch_skinny(const bpd_ctx* ctx, const GemmP& p, const Epi& e, const LnP& 
 }
 
 bool skinny_ok(const bpd_ctx* ctx, const GemmP& p) { return ctx->cfg.dtype == BPD_BF16 && p.M <= 16 && p.K <= 4096; }
+
+// ---- streaming path: M <= 16, K = 2048 / 4096, several column tiles per CU ---------------------
+// (the heads' output layers at batch 1).  One workgroup per CU walks a contiguous range of at most
+// 8 column tiles of one group.
+constexpr int STREAM_TILES_MAX = 8;
+size_t stream_lds_bytes(const GemmP& p) { return (size_t)16384 + 8192 + 1536 + (size_t)p.M * (p.K + 8) * 2; }
+bool stream_ok(const bpd_ctx* ctx, const GemmP& p, const Epi& e, int groups) {
+  return skinny_ok(ctx, p) && p.M >= 1 && e.mode == 0 && !e.stats_out && (p.K == 2048 || p.K == 4096) && p.N % 16 == 0 &&
+         2L * groups * (p.N / 16) >= 3L * ctx->num_cus && stream_lds_bytes(p) <= (size_t)160 * 1024;
+}
+template <int U, bool STREAM>
+void launch_stream_cfg(const bpd_ctx* ctx, const GemmP& p, const Epi& e_in, int groups) {
+  Epi e = e_in;                                 // bias and residual are loaded unconditionally
+  if (!e.bias) { e.bias = ctx->lay.zeros; e.bias_g = 0; }
+  if (!e.R) { e.R = ctx->lay.zeros; e.ldr = 0; e.r_g = 0; }
+  const int ntiles = p.N / 16;
+  int gx = ctx->num_cus / groups;
+  const int gx_min = (ntiles + STREAM_TILES_MAX - 1) / STREAM_TILES_MAX;
+  gx = gx < gx_min ? gx_min : gx;
+  gx = gx > ntiles ? ntiles : gx;
+  const size_t lds = stream_lds_bytes(p);
+  auto k = stream_gemm_kernel<U, STREAM>;
+  static size_t attr = 0;                       // per instantiation: allow more than 64 KiB of LDS
+  if (attr < lds) { (void)hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); attr = lds; }
+  hipLaunchKernelGGL(k, dim3(gx, 1, groups), dim3(512), lds, ctx->stream, p, e);
+}
+void launch_stream(const bpd_ctx* ctx, const GemmP& p, const Epi& e, int groups) {
+  const size_t wbytes = (size_t)p.K * p.N * groups * 2;
+  const bool nt = ctx->weights_exceed_llc && wbytes >= ((size_t)32 << 20);
+  if (p.K == 4096) { if (nt) launch_stream_cfg<16, true>(ctx, p, e, groups); else launch_stream_cfg<16, false>(ctx, p, e, groups); }
+  else { if (nt) launch_stream_cfg<8, true>(ctx, p, e, groups); else launch_stream_cfg<8, false>(ctx, p, e, groups); }
+}
 // LayerNorm statistics ride along with the residual stream when the whole block is one MFMA row tile
 bool stats_path(const bpd_ctx* ctx, int M) {
   return ctx->cfg.dtype == BPD_BF16 && M <= 16 && ctx->cfg.d_model <= 1024;
@@ -363,7 +396,9 @@ void gemm(bpd_ctx* ctx, const GemmP& p, const Epi& e, int groups = 1) {
     return;
   }
   LnP none{};
-  if (skinny_ok(ctx, p)) {
+  if (stream_ok(ctx, p, e, groups)) {
+    launch_stream(ctx, p, e, groups);
+  } else if (skinny_ok(ctx, p)) {
     if (p.N / 16 >= 2048) launch_skinny<2, false, false>(ctx, p, e, none, nullptr, nullptr, groups);
     else launch_skinny<1, false, false>(ctx, p, e, none, nullptr, nullptr, groups);
   } else if (p.K % 64 == 0) {
@@ -745,6 +780,11 @@ int bpd_create(const bpd_config* cfg, void* workspace, size_t workspace_bytes, v
   bpd_ctx* ctx = new bpd_ctx();
   ctx->cfg = *cfg;
   ctx->stream = (hipStream_t)hip_stream;
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+      ctx->num_cus = cus;
+  }
   build_layout(*cfg, (char*)workspace, ctx->lay);
   build_table(ctx);
   {

@@ -385,6 +385,165 @@ __global__ __launch_bounds__(WAVES * 64) void skinny_gemm_kernel(GemmP p, Epi e,
 }
 
 // ---------------------------------------------------------------------------------------
+// Streaming skinny GEMM for a long-K weight stream that gives every CU several column tiles (the
+// heads' output layers at batch 1: 640 tiles of 4096 x 16).  One 16-row block, K == 256 * U, mode-0
+// epilogue without statistics output.  Grid (GX, 1, groups), 512 threads, one workgroup per CU.
+// A workgroup owns the contiguous column tiles [t0, t1) of its group (at most 8):
+//   * X (M rows x K, bf16) goes global -> LDS once (direct loads, rows padded by 16 bytes so that the
+//     MFMA operand reads of a wave spread over all banks); the skinny kernel re-reads X per tile
+//   * K is split over the 8 waves as in the skinny kernel (wave w takes k-steps w, w+8, ...: the same
+//     summation order, so both kernels give the same bits); the 16 weight loads of the next tile are
+//     issued before the current tile is multiplied, and the previous tile is finished (partials of
+//     the 8 waves added by one wave, in turn) after that, so a wave always has 16-32 KiB in flight
+//   * bias, residual rows and the LayerNorm vectors of the epilogue for all owned columns are
+//     fetched once (one 16-byte load per thread) and read from LDS when a tile is finished
+// Dynamic LDS: 16 KiB (partials, double buffered; the LayerNorm statistics pass through the
+// second half before it is first used) + 8 KiB (residual rows) + 1.5 KiB (vectors) + M*(K+8)*2.
+template <int U, bool STREAM>
+__global__ __launch_bounds__(512) void stream_gemm_kernel(GemmP p, Epi e) {
+  constexpr int WAVES = 8, TW = 8, EC = 16 * TW;      // EC: columns a workgroup may own
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  f32x4* red = (f32x4*)smem_raw;              // [2][WAVES][64]
+  float* st_s = (float*)(smem_raw + 8192);    // [64][16][2], dead before red[1] is first written
+  float* r_s = (float*)(smem_raw + 16384);    // [16][EC]
+  float* v_s = r_s + 16 * EC;                 // [3][EC]
+  bf16_t* xs = (bf16_t*)(v_s + 3 * EC);
+  const int ldxs = p.K + 8;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lr = lane & 15, lq = lane >> 4;
+  const int g = blockIdx.z;
+  const int ntiles = p.N >> 4, ksteps = p.K >> 5;
+  const int t0 = (int)(blockIdx.x * (unsigned)ntiles / gridDim.x), t1 = (int)((blockIdx.x + 1) * (unsigned)ntiles / gridDim.x);
+  if (t0 >= t1) return;
+  {   // X: global -> LDS directly, whole wave-loads of 64 pieces inside one row
+    const int segs = p.K >> 3;                 // 16-byte pieces per row
+    const bf16_t* xg = (const bf16_t*)p.X + g * p.x_g;
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      const int q0 = i * 512 + wave * 64;
+      const int row = (unsigned)q0 / (unsigned)segs, seg0 = q0 - row * segs;
+      if (row < p.M)
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(xg + (long)row * p.ldx + (seg0 + lane) * 8),
+                                         (void __attribute__((address_space(3)))*)(xs + row * ldxs + seg0 * 8), 16, 0, 0);
+    }
+  }
+  const bool has_ln = e.lnR_stats != nullptr;
+  // small operands: statistics of the epilogue's LayerNorm, residual rows and the per-column vectors of this workgroup's columns
+  float4 st0, st1, rr, vv;
+  {
+    const float* sp_ = has_ln ? e.lnR_stats : e.bias;
+    const int ns4 = has_ln ? (e.lnR_K >> 4) * 8 : 1;
+    st0 = ((const float4*)sp_)[tid < ns4 ? tid : 0];
+    st1 = ((const float4*)sp_)[tid + 512 < ns4 ? tid + 512 : 0];
+    const int nc4 = (t1 - t0) * 4;             // float4 per row of this workgroup's columns
+    const int row = tid >> 5, c4 = tid & 31;
+    const int c4c = c4 < nc4 ? c4 : 0;
+    rr = *(const float4*)(e.R + g * e.r_g + (long)(row < p.M ? row : p.M - 1) * e.ldr + t0 * 16 + c4c * 4);
+    const float* vp_ = row == 1 && has_ln ? e.lnR_g : (row == 2 && has_ln ? e.lnR_b : e.bias + g * e.bias_g);
+    vv = *(const float4*)(vp_ + t0 * 16 + c4c * 4);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  const char* Wg = (const char*)((const bf16_t*)p.W + g * p.w_g);      // wave-uniform; the lane adds 16 * lane
+  const unsigned loff = lane * 16;
+  uint4 a_cur[U], a_nxt[U];
+#define ST_LOADW(dst, tile)                                                                     \
+  _Pragma("unroll") for (int i = 0; i < U; ++i) {                                               \
+    const char* wp_ = Wg + ((long)(tile) * ksteps + wave + WAVES * i) * 1024;                   \
+    if (STREAM) dst[i] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_nt*)(wp_ + loff))); \
+    else dst[i] = *(const uint4*)(wp_ + loff);                                                  \
+  }
+#define ST_SMALL_TO_LDS()                                                                       \
+  {                                                                                             \
+    const int ns4 = has_ln ? (e.lnR_K >> 4) * 8 : 0;                                            \
+    if (tid < ns4) *(float4*)&st_s[4 * tid] = st0;                                              \
+    if (tid + 512 < ns4) *(float4*)&st_s[4 * (tid + 512)] = st1;                                \
+    *(float4*)&r_s[(tid >> 5) * EC + (tid & 31) * 4] = rr;                                      \
+    if (tid < 96) *(float4*)&v_s[(tid >> 5) * EC + (tid & 31) * 4] = vv;                        \
+  }
+  const bf16_t* xrow = xs + (lr < p.M ? lr : p.M - 1) * ldxs + lq * 8;
+  float mu = 0.f, rstd = 1.f;
+  int it = 0;
+#define ST_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (7 << 4) | (15 << 8) | (((n) >> 4) << 14))
+#define ST_FINISH(tile, itv)                                                                    \
+  if (wave == ((itv) & 7)) {                                                                    \
+    const f32x4* rb_ = red + ((itv) & 1) * (WAVES * 64);                                        \
+    f32x4 sum = rb_[lane];                                                                      \
+    _Pragma("unroll") for (int w = 1; w < WAVES; ++w) sum += rb_[w * 64 + lane];                \
+    const int lc_ = ((tile) - t0) * 16 + lq * 4;                                                \
+    float4 rv = *(const float4*)&r_s[lr * EC + lc_];                                            \
+    const float4 bs_ = *(const float4*)&v_s[lc_];                                               \
+    if (has_ln) {                                                                               \
+      const float4 gg_ = *(const float4*)&v_s[EC + lc_], hh_ = *(const float4*)&v_s[2 * EC + lc_]; \
+      rv.x = (rv.x - mu) * rstd * gg_.x + hh_.x; rv.y = (rv.y - mu) * rstd * gg_.y + hh_.y;     \
+      rv.z = (rv.z - mu) * rstd * gg_.z + hh_.z; rv.w = (rv.w - mu) * rstd * gg_.w + hh_.w;     \
+    }                                                                                           \
+    float v[4] = {sum[0] + bs_.x, sum[1] + bs_.y, sum[2] + bs_.z, sum[3] + bs_.w};              \
+    if (e.relu) { _Pragma("unroll") for (int r = 0; r < 4; ++r) v[r] = fmaxf(v[r], 0.f); }      \
+    v[0] += rv.x; v[1] += rv.y; v[2] += rv.z; v[3] += rv.w;                                     \
+    const int n = (tile) * 16 + lq * 4;                                                         \
+    if (lr < p.M) {                                                                             \
+      if (e.Yf) *(float4*)(e.Yf + g * e.yf_g + (long)lr * e.ldyf + n) = make_float4(v[0], v[1], v[2], v[3]); \
+      if (e.Ya) *(uint2*)((bf16_t*)e.Ya + g * e.ya_g + (long)lr * e.ldya + n) = make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])); \
+    }                                                                                           \
+  }
+#define ST_MULT(A)                                                                              \
+  {                                                                                             \
+    f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};                                                      \
+    __builtin_amdgcn_sched_barrier(0);                                                          \
+    _Pragma("unroll") for (int i0 = 0; i0 < U; i0 += 4) {      /* four operand reads at a time: registers */ \
+      uint4 bb_[4];                                                                             \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i) bb_[i] = *(const uint4*)(xrow + (wave + WAVES * (i0 + i)) * 32); \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i)                                             \
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[i0 + i]), __builtin_bit_cast(bf16x8, bb_[i]), acc, 0, 0, 0); \
+      __builtin_amdgcn_sched_barrier(0);                                                        \
+    }                                                                                           \
+    red[(it & 1) * (WAVES * 64) + wave * 64 + lane] = acc;                                      \
+  }
+  // state "X holds tile t": its weights are in flight or here, the partial sums of tile t - 1 (if any) wait in
+  // red[(it - 1) & 1].  The first pass (it == 0) also moves the small operands to LDS; X and the small operands were
+  // requested before any weights, so they are complete once at most the weight loads issued since are outstanding.
+#define ST_ENTER(younger)                                                                       \
+    if (it == 0) { ST_WAIT_VM(younger); ST_SMALL_TO_LDS() }                                     \
+    __syncthreads();                                                                            \
+    if (it == 0) { if (has_ln) row_stats(st_s, e.lnR_K, e.lnR_eps, lane, mu, rstd); }           \
+    else ST_FINISH(t - 1, it - 1)
+#define ST_STEP(X, Y)                                                                           \
+  {                                                                                             \
+    ST_LOADW(Y, t + 1)                                                                          \
+    ST_ENTER(32)                                                                                \
+    ST_MULT(X)                                                                                  \
+    ++it; ++t;                                                                                  \
+  }
+#define ST_LAST(X)                                                                              \
+  {                                                                                             \
+    ST_ENTER(16)                                                                                \
+    ST_MULT(X)                                                                                  \
+    __syncthreads();                                                                            \
+    ST_FINISH(t, it)                                                                            \
+  }
+  int t = t0;
+  ST_LOADW(a_cur, t0)
+  while (t + 2 < t1) {
+    ST_STEP(a_cur, a_nxt)
+    ST_STEP(a_nxt, a_cur)
+  }
+  if (t + 1 == t1) {
+    ST_LAST(a_cur)
+  } else {
+    ST_STEP(a_cur, a_nxt)
+    ST_LAST(a_nxt)
+  }
+#undef ST_ENTER
+#undef ST_STEP
+#undef ST_LAST
+#undef ST_MULT
+#undef ST_FINISH
+#undef ST_WAIT_VM
+#undef ST_SMALL_TO_LDS
+#undef ST_LOADW
+}
+
+// ---------------------------------------------------------------------------------------
 // "ldsx" GEMM: BM = 16*MT rows x BN = 64*NT columns per workgroup, K walked in chunks of KC.
 // Wave w owns column tiles (4*blockIdx.x + w)*NT .. +NT and streams their weight tiles from
 // global memory into registers one chunk ahead (KC/32 * NT fragments in flight per wave).  The

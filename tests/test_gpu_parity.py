@@ -343,6 +343,10 @@ ODD_SHAPES = [
     wl.Config("odd-dh16", 23, 2, 2, 128, 8, 256, 528, 3, 2, 7, 12, "bf16", 2, src_len_kind="lognormal"),
     wl.Config("odd-k16", 24, 1, 1, 512, 8, 2048, 1024, 16, 1, 11, 40, "bf16", 2),
     wl.Config("odd-b17", 25, 1, 1, 64, 1, 2112, 272, 1, 17, 5, 6, "bf16", 2, src_len_kind="lognormal"),
+    # heads' output layers on the streaming kernel (K = 2048, several column tiles per workgroup): 9 rows with one or
+    # two tiles per workgroup; 16 rows with four tiles per workgroup
+    wl.Config("odd-stream9", 26, 1, 1, 768, 12, 2048, 1040, 9, 1, 7, 20, "bf16", 2, src_len_kind="lognormal"),
+    wl.Config("odd-stream16", 27, 1, 1, 1024, 16, 2048, 528, 16, 1, 6, 36, "bf16", 2),
 ]
 
 
