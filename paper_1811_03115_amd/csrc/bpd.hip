@@ -251,14 +251,17 @@ void launch_gemm_bf16(const GemmP& p, const Epi& e, int groups, hipStream_t s) {
 // ---- skinny path: M <= 16 -------------------------------------------------------------
 template <int MT, int NT, bool XLN, bool ARGMAX, int WAVES, int U, int DEPTH, bool STREAM>
 void launch_skinny_cfg(const bpd_ctx* ctx, const GemmP& p, const Epi& e_in, const LnP& ln, unsigned long long* keys,
-                       float* logits, int groups, int cap = 512) {
+                       float* logits, int groups) {
   hipStream_t s = ctx->stream;
   Epi e = e_in;                                 // the kernel loads bias and residual unconditionally
   if (!e.bias) { e.bias = ctx->lay.zeros; e.bias_g = 0; }
   if (!e.R) { e.R = ctx->lay.zeros; e.ldr = 0; e.r_g = 0; }
   const int ntiles = p.N / 16;
   const int ngroups = (ntiles + NT - 1) / NT;
-  const int gx = ngroups > cap ? cap : ngroups;  // beyond `cap` each workgroup walks several column-tile groups
+  // more column-tile groups than CUs: one workgroup per CU walks several of them (a second workgroup on a CU would only
+  // start once the first has finished: the kernel fills the register file)
+  const int cap = ctx->num_cus;
+  const int gx = ngroups > cap ? cap : ngroups;
   dim3 grid(gx, (p.M + 16 * MT - 1) / (16 * MT), groups);
   const size_t lds = (size_t)2 * WAVES * MT * NT * 1024;
   if (ngroups > gx) {
@@ -338,7 +341,7 @@ template <int MT, int NT, int KC, bool ARGMAX>
 void launch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* logits, int groups, hipStream_t s) {
   const int ntiles = p.N / 16;
   dim3 grid((ntiles + 4 * NT - 1) / (4 * NT), (p.M + 16 * MT - 1) / (16 * MT), groups);
-  const size_t lds = (size_t)2 * ((16 * MT * (KC / 8) + 255) / 256) * 4096;
+  const size_t lds = ldsx_lds_bytes<MT, NT, KC>();
   static bool attr_set = false;                 // per instantiation: allow more than 64 KiB of LDS
   if (!attr_set) {
     (void)hipFuncSetAttribute((const void*)gemm_ldsx_kernel<MT, NT, KC, ARGMAX>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

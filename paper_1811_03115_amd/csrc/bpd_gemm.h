@@ -551,7 +551,7 @@ __global__ __launch_bounds__(512) void stream_gemm_kernel(GemmP p, Epi e) {
 // registers), double buffered.  Such a load writes 64 consecutive 16-byte slots per wave, so
 // rows cannot be padded; instead the 16-byte segment index within a row is XOR-ed with
 // (row & 7), which spreads the MFMA operand reads of a wave evenly over the LDS banks.
-// Requires K % KC == 0, KC % 64 == 0.  Dynamic LDS: 2 * XI * 4096 bytes.
+// Requires K % KC == 0, KC % 64 == 0.  Dynamic LDS: ldsx_lds_bytes() (2 or 3 buffers of XI * 4096 bytes).
 // Two workgroups share a CU whenever the accumulators (4*MT*NT registers), the two weight chunks
 // (8*NT*KC/32) and the operand fragments (4*MT) leave room for it in half the register file: the
 // second wave per SIMD covers the LDS and memory latencies of the first.
@@ -561,6 +561,14 @@ template <int MT, int NT, int KC>
 constexpr int ldsx_waves_min() { return ldsx_regs<MT, NT, KC>() <= 272 ? 2 : 1; }
 template <int MT, int NT, int KC>
 constexpr int ldsx_waves_max() { return ldsx_regs<MT, NT, KC>() <= 168 ? 4 : ldsx_waves_min<MT, NT, KC>(); }
+
+// Two weight buffers take turns (2) unless the tile has no registers to spare for two code copies of the chunk (1).  A
+// third buffer (weights and activations two chunks ahead) was measured: it halves the workgroups per CU of the small
+// tiles and made every workload slower.
+template <int MT, int NT, int KC>
+constexpr int ldsx_ring() { return ldsx_regs<MT, NT, KC>() <= 210 ? 2 : 1; }
+template <int MT, int NT, int KC>
+constexpr size_t ldsx_lds_bytes() { return (size_t)2 * ((16 * MT * (KC / 8) + 255) / 256) * 4096; }
 
 template <int MT, int NT, int KC, bool ARGMAX>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_min<MT, NT, KC>(), ldsx_waves_max<MT, NT, KC>()))) void gemm_ldsx_kernel(GemmP p, Epi e, unsigned long long* keys, float* logits) {
@@ -610,52 +618,69 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
   _Pragma("unroll") for (int i = 0; i < XI; ++i)                                            \
     __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(X + xoff[i] + (chunk) * KC), \
                                      (void __attribute__((address_space(3)))*)((buf) + (i * 256 + wave * 64) * 8), 16, 0, 0);
-  uint4 a_cur[KS][NT], a_nxt[KS][NT];
+  // The chunk being multiplied and the next one are in use / in flight: weights in two register buffers, activations in
+  // two LDS buffers.  RING == 2: the register buffers take turns; RING == 1: a register copy per chunk.
+  constexpr int RING = ldsx_ring<MT, NT, KC>();
+  uint4 a0[KS][NT], a1[KS][NT];
   f32x4 acc[MT][NT];
 #pragma unroll
   for (int t = 0; t < MT; ++t)
 #pragma unroll
     for (int u = 0; u < NT; ++u) acc[t][u] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int s = 0; s < KS; ++s)
-#pragma unroll
-    for (int u = 0; u < NT; ++u) a_cur[s][u] = wt[u][(long)(cbase * KS + s) * 64];
+#define BPD_LOAD_W(dst, chunk)                                                               \
+  _Pragma("unroll") for (int s = 0; s < KS; ++s)                                            \
+    _Pragma("unroll") for (int u = 0; u < NT; ++u) dst[s][u] = wt[u][(long)((chunk) * KS + s) * 64];
+  // vmcnt <= n, other counters untouched.  Loads complete in issue order: once at most the loads issued after an
+  // activation chunk (its own weights) are outstanding, this wave's part of that chunk has reached LDS.
+#define BPD_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (7 << 4) | (15 << 8) | (((n) >> 4) << 14))
+  constexpr int YOUNGER = KS * NT;
+  static_assert(YOUNGER <= 63, "vmcnt range");
   BPD_X_TO_LDS(xs0, cbase)
-  __builtin_amdgcn_s_waitcnt(0);
+  BPD_LOAD_W(a0, cbase)
+  BPD_WAIT_VM(YOUNGER);
   __syncthreads();
-  for (int c = 0; c < nchunks; ++c) {
-    // next chunk in flight while this one is multiplied (the last iteration re-requests its own
-    // chunk so that the code stays branch-free)
-    const int cn = cbase + (c + 1 < nchunks ? c + 1 : c);
-    bf16_t* xn = (c & 1) ? xs0 : xs1;
-    BPD_X_TO_LDS(xn, cn)
-#pragma unroll
-    for (int s = 0; s < KS; ++s)
-#pragma unroll
-      for (int u = 0; u < NT; ++u) a_nxt[s][u] = wt[u][(long)(cn * KS + s) * 64];
-    __builtin_amdgcn_sched_barrier(0);
-    const bf16_t* xb = (c & 1) ? xs1 : xs0;
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      uint4 b[MT];
-#pragma unroll
-      for (int t = 0; t < MT; ++t)
-        b[t] = *(const uint4*)(xb + (t * 16 + lr) * KC + (((s * 4 + lq) ^ (lr & 7)) * 8));
-#pragma unroll
-      for (int t = 0; t < MT; ++t)
-#pragma unroll
-        for (int u = 0; u < NT; ++u)
-          acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_cur[s][u]),
-                                                              __builtin_bit_cast(bf16x8, b[t]), acc[t][u], 0, 0, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int s = 0; s < KS; ++s)
-#pragma unroll
-      for (int u = 0; u < NT; ++u) a_cur[s][u] = a_nxt[s][u];
-    __builtin_amdgcn_s_waitcnt(0);              // the direct-to-LDS loads are not tracked by the compiler
-    __syncthreads();
+  // One chunk c (weights in AC, activations in xc): chunk c + 1 starts moving into AL / xl, chunk c is multiplied, then the
+  // workgroup meets once activation chunk c + 1 has landed.  The weights requested after that chunk stay in flight across
+  // the barrier, so the memory pipe never drains.  The last chunk re-requests itself (branch-free).
+#define BPD_CHUNK(AC, AL, xc, xl, c)                                                         \
+  {                                                                                          \
+    const int cl = cbase + ((c) + 1 < nchunks ? (c) + 1 : nchunks - 1);                      \
+    BPD_X_TO_LDS(xl, cl)                                                                     \
+    BPD_LOAD_W(AL, cl)                                                                       \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
+    _Pragma("unroll") for (int s = 0; s < KS; ++s) {                                         \
+      uint4 b[MT];                                                                           \
+      _Pragma("unroll") for (int t = 0; t < MT; ++t)                                         \
+        b[t] = *(const uint4*)((xc) + (t * 16 + lr) * KC + (((s * 4 + lq) ^ (lr & 7)) * 8)); \
+      _Pragma("unroll") for (int t = 0; t < MT; ++t)                                         \
+        _Pragma("unroll") for (int u = 0; u < NT; ++u)                                       \
+          acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, AC[s][u]), \
+                                                              __builtin_bit_cast(bf16x8, b[t]), acc[t][u], 0, 0, 0); \
+    }                                                                                        \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
+    BPD_WAIT_VM(YOUNGER);                                                                    \
+    __syncthreads();                                                                         \
   }
+  if constexpr (RING == 2) {
+    for (int c = 0; c < nchunks; c += 2) {
+      BPD_CHUNK(a0, a1, xs0, xs1, c)
+      if (c + 1 >= nchunks) break;
+      BPD_CHUNK(a1, a0, xs1, xs0, c + 1)
+    }
+  } else {
+    for (int c = 0; c < nchunks; ++c) {
+      const bf16_t* xc = (c & 1) ? xs1 : xs0;
+      bf16_t* xl = (c & 1) ? xs0 : xs1;
+      BPD_CHUNK(a0, a1, xc, xl, c)
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+#pragma unroll
+        for (int u = 0; u < NT; ++u) a0[s][u] = a1[s][u];        // waits for the next weights
+    }
+  }
+#undef BPD_CHUNK
+#undef BPD_WAIT_VM
+#undef BPD_LOAD_W
 #undef BPD_X_TO_LDS
   if (ARGMAX) {
     // per-row best of each wave -> LDS -> one atomic per row and workgroup
