@@ -455,11 +455,40 @@ void gemm_ln(bpd_ctx* ctx, float* x, LnW w, void* xn, float* yf, GemmP p, const 
 }
 
 // Vocabulary projection with fused arg-max (bf16 mode).
+// ---- streaming vocabulary projection: 17 .. 128 rows, K = 512 / 1024, at least one column tile per wave ----
+size_t stream_vocab_lds_bytes(const GemmP& p) {
+  const int rows = p.M < 64 ? p.M : 64;
+  return (size_t)8 * 64 * 8 + (size_t)rows * (p.K + 8) * 2;
+}
+int stream_vocab_gx(const bpd_ctx* ctx, const GemmP& p) {
+  const int rb = (p.M + 63) / 64;
+  const int gx = ctx->num_cus / rb;
+  return gx < 1 ? 1 : gx;
+}
+bool stream_vocab_ok(const bpd_ctx* ctx, const GemmP& p) {
+  return ctx->cfg.dtype == BPD_BF16 && p.M > 16 && p.M <= 128 && (p.K == 512 || p.K == 1024) && p.N % 16 == 0 &&
+         p.ldx % 8 == 0 && p.N / 16 >= 8 * stream_vocab_gx(ctx, p) && stream_vocab_lds_bytes(p) <= (size_t)160 * 1024;
+}
+template <int KH, bool STREAM>
+void launch_stream_vocab_cfg(const bpd_ctx* ctx, const GemmP& p, unsigned long long* keys, float* logits) {
+  const size_t lds = stream_vocab_lds_bytes(p);
+  auto k = stream_vocab_kernel<4, KH, STREAM>;
+  static size_t attr = 0;                       // per instantiation: allow more than 64 KiB of LDS
+  if (attr < lds) { (void)hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); attr = lds; }
+  hipLaunchKernelGGL(k, dim3(stream_vocab_gx(ctx, p), (p.M + 63) / 64), dim3(512), lds, ctx->stream, p, keys, logits);
+}
+void launch_stream_vocab(const bpd_ctx* ctx, const GemmP& p, unsigned long long* keys, float* logits) {
+  // (non-temporal loads measured slower here: the second row block reads the same weights out of L2)
+  if (p.K == 1024) launch_stream_vocab_cfg<2, false>(ctx, p, keys, logits);
+  else launch_stream_vocab_cfg<1, false>(ctx, p, keys, logits);
+}
+
 void vocab_argmax(bpd_ctx* ctx, const GemmP& p, unsigned long long* keys, float* logits) {
   hipStream_t s = ctx->stream;
   Epi none{};
   LnP noln{};
   if (skinny_ok(ctx, p)) launch_skinny<2, false, true>(ctx, p, none, noln, keys, logits, 1);
+  else if (stream_vocab_ok(ctx, p)) launch_stream_vocab(ctx, p, keys, logits);
   else if (p.K % 64 == 0) dispatch_ldsx<true>(p, none, keys, logits, 1, s);
   else {
     const int ntiles = p.N / 16;

@@ -347,6 +347,10 @@ ODD_SHAPES = [
     # two tiles per workgroup; 16 rows with four tiles per workgroup
     wl.Config("odd-stream9", 26, 1, 1, 768, 12, 2048, 1040, 9, 1, 7, 20, "bf16", 2, src_len_kind="lognormal"),
     wl.Config("odd-stream16", 27, 1, 1, 1024, 16, 2048, 528, 16, 1, 6, 36, "bf16", 2),
+    # vocabulary projection on the streaming kernel (17 .. 128 score rows, at least one column tile per wave): 81 rows in two
+    # row blocks with K = 512; 25 rows with K = 1024; column tiles that do not divide evenly among the workgroups
+    wl.Config("odd-vocab81", 28, 1, 1, 512, 8, 1024, 16400, 9, 1, 6, 20, "bf16", 2, src_len_kind="lognormal"),
+    wl.Config("odd-vocab25", 29, 1, 1, 1024, 16, 1024, 32784, 5, 1, 5, 12, "bf16", 2),
 ]
 
 
