@@ -469,18 +469,19 @@ bool stream_vocab_ok(const bpd_ctx* ctx, const GemmP& p) {
   return ctx->cfg.dtype == BPD_BF16 && p.M > 16 && p.M <= 128 && (p.K == 512 || p.K == 1024) && p.N % 16 == 0 &&
          p.ldx % 8 == 0 && p.N / 16 >= 8 * stream_vocab_gx(ctx, p) && stream_vocab_lds_bytes(p) <= (size_t)160 * 1024;
 }
-template <int KH, bool STREAM>
+template <int NT, int UPT>
 void launch_stream_vocab_cfg(const bpd_ctx* ctx, const GemmP& p, unsigned long long* keys, float* logits) {
   const size_t lds = stream_vocab_lds_bytes(p);
-  auto k = stream_vocab_kernel<4, KH, STREAM>;
+  auto k = stream_vocab_kernel<4, NT, UPT, false>;
   static size_t attr = 0;                       // per instantiation: allow more than 64 KiB of LDS
   if (attr < lds) { (void)hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); attr = lds; }
   hipLaunchKernelGGL(k, dim3(stream_vocab_gx(ctx, p), (p.M + 63) / 64), dim3(512), lds, ctx->stream, p, keys, logits);
 }
 void launch_stream_vocab(const bpd_ctx* ctx, const GemmP& p, unsigned long long* keys, float* logits) {
-  // (non-temporal loads measured slower here: the second row block reads the same weights out of L2)
-  if (p.K == 1024) launch_stream_vocab_cfg<2, false>(ctx, p, keys, logits);
-  else launch_stream_vocab_cfg<1, false>(ctx, p, keys, logits);
+  // one column tile at a time.  Two at a time (NT = 2: one LDS read feeds two MFMAs) measured slower, 20.2 vs 18.5 us at
+  // 100 x 1024 x 32768, and so did non-temporal loads (the second row block reads the same weights out of L2).
+  if (p.K == 1024) launch_stream_vocab_cfg<1, 2>(ctx, p, keys, logits);
+  else launch_stream_vocab_cfg<1, 1>(ctx, p, keys, logits);
 }
 
 void vocab_argmax(bpd_ctx* ctx, const GemmP& p, unsigned long long* keys, float* logits) {

@@ -545,38 +545,41 @@ __global__ __launch_bounds__(512) void stream_gemm_kernel(GemmP p, Epi e) {
 
 // ---------------------------------------------------------------------------------------
 // Streaming vocabulary projection + arg-max for a block of 17 .. 128 rows (the k x k score rows of one
-// sentence): K = 512 * KH (KH = 1, 2), N a multiple of 16.  Grid (GX, row blocks of 64), 512 threads,
-// one workgroup per CU.
+// sentence): K = 512 or 1024, N a multiple of 16.  Grid (GX, row blocks of 64), 512 threads, one
+// workgroup per CU.
 //   * the workgroup's rows of X (up to 16 * MT = 64, bf16) go global -> LDS once (direct loads,
 //     rows padded by 16 bytes against bank conflicts)
 //   * a workgroup owns the contiguous column tiles [t0, t1); its 8 waves take them in turn (wave w:
-//     t0 + w, t0 + w + 8, ...).  A wave multiplies a whole column tile by itself (no partial sums,
-//     no barrier after the prologue): it streams the tile's weights in units of 16 k-steps through
-//     two register buffers that take turns, the next unit in flight while one is multiplied
-//     against the MT row tiles read from LDS; k ascends within one accumulator, as in the
-//     LDS-staged GEMM, so both give the same bits
+//     t0 + w, t0 + w + 8, ...), NT at a time.  A wave multiplies whole column tiles by itself (no
+//     partial sums, no barrier after the prologue): it streams their weights in units of 16 loads
+//     (16 / NT k-steps of NT tiles) through two register buffers that take turns, the next unit
+//     in flight while one is multiplied against the MT row tiles read from LDS (with NT = 2 one
+//     LDS read feeds two MFMAs: half the LDS traffic); k ascends within one accumulator, as in the
+//     LDS-staged GEMM, so both give the same bits.  UPT = K / 32 * NT / 16 units per group of NT tiles.
+//     A wave with an odd number of tiles repeats its last tile as the partner (same keys again).
 //   * each wave keeps a running best key per row; the waves' keys meet in LDS at the end and
 //     one 64-bit atomic max per row and workgroup goes to keys[]
-// Dynamic LDS: rows * (K + 8) * 2 bytes (X) + 8 * 16 * MT * 8 bytes (keys).
-template <int MT, int KH, bool STREAM>
+// Dynamic LDS: 8 * 16 * MT * 8 bytes (keys) + rows * (K + 8) * 2 bytes (X).
+template <int MT, int NT, int UPT, bool STREAM>
 __global__ __launch_bounds__(512) void stream_vocab_kernel(GemmP p, unsigned long long* keys, float* logits) {
-  constexpr int WAVES = 8, BM = 16 * MT, UK = 16;          // UK k-steps per unit
+  constexpr int WAVES = 8, BM = 16 * MT, UK = 16 / NT;      // UK k-steps per unit
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   unsigned long long* wb = (unsigned long long*)smem_raw;  // [WAVES][BM]
   bf16_t* xs = (bf16_t*)(smem_raw + WAVES * BM * 8);
   const int ldxs = p.K + 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lr = lane & 15, lq = lane >> 4;
-  const int ntiles = p.N >> 4, ksteps = p.K >> 5;
+  const int ntiles = p.N >> 4, ksteps = p.K >> 5;          // ksteps == UK * UPT
   const int m0 = blockIdx.y * BM;
   const int nrows = min(BM, p.M - m0);
   const int t0 = (int)(blockIdx.x * (unsigned)ntiles / gridDim.x), t1 = (int)((blockIdx.x + 1) * (unsigned)ntiles / gridDim.x);
   {   // X: whole wave-loads of 64 pieces (512 columns) inside one row
     const bf16_t* xg = (const bf16_t*)p.X + (long)m0 * p.ldx;
+    const int parts = p.K >> 9;                            // 512-column parts per row
 #pragma unroll
-    for (int i = 0; i < 2 * MT * KH; ++i) {
-      const int wl = i * WAVES + wave;                     // wave-load index: row = wl / KH, 512-column part = wl % KH
-      const int row = wl / KH, part = wl % KH;
+    for (int i = 0; i < 4 * MT; ++i) {                     // 16 * MT rows * (at most) 2 parts / 8 waves
+      const int wl = i * WAVES + wave;
+      const int row = wl / parts, part = wl % parts;
       if (row < nrows)
         __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(xg + (long)row * p.ldx + part * 512 + lane * 8),
                                          (void __attribute__((address_space(3)))*)(xs + row * ldxs + part * 512), 16, 0, 0);
@@ -584,23 +587,23 @@ __global__ __launch_bounds__(512) void stream_vocab_kernel(GemmP p, unsigned lon
   }
   const char* Wg = (const char*)p.W;
   const unsigned loff = lane * 16;
-  // this wave's units: tile t0 + wave + 8 * (u / KH), k-steps 16 * (u % KH) .. + 16
+  // this wave's tiles: t0 + wave + 8 * j, j < ntw, in groups of NT; unit u = (group u / UPT, k-steps UK * (u % UPT) .. + UK)
   const int ntw = t0 + wave < t1 ? (t1 - t0 - wave + WAVES - 1) / WAVES : 0;
-  const int NU = ntw * KH;
-  uint4 a0[UK], a1[UK];
+  const int NU = (ntw + NT - 1) / NT * UPT;
+  uint4 a0[16], a1[16];
+#define SV_TILE(u, n) (t0 + wave + WAVES * (((u) / UPT) * NT + (n) < ntw ? ((u) / UPT) * NT + (n) : ntw - 1))
 #define SV_LOADU(dst, u)                                                                        \
-  {                                                                                             \
-    const int tile_ = t0 + wave + WAVES * ((u) / KH);                                           \
-    const char* wp_ = Wg + ((long)tile_ * ksteps + UK * ((u) % KH)) * 1024;                     \
+  _Pragma("unroll") for (int n = 0; n < NT; ++n) {                                              \
+    const char* wp_ = Wg + ((long)SV_TILE(u, n) * ksteps + UK * ((u) % UPT)) * 1024;            \
     _Pragma("unroll") for (int i = 0; i < UK; ++i) {                                            \
-      if (STREAM) dst[i] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_nt*)(wp_ + i * 1024 + loff))); \
-      else dst[i] = *(const uint4*)(wp_ + i * 1024 + loff);                                     \
+      if (STREAM) dst[n * UK + i] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_nt*)(wp_ + i * 1024 + loff))); \
+      else dst[n * UK + i] = *(const uint4*)(wp_ + i * 1024 + loff);                            \
     }                                                                                           \
   }
 #define SV_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (7 << 4) | (15 << 8) | (((n) >> 4) << 14))
   if (NU > 0) {
     SV_LOADU(a0, 0)
-    SV_WAIT_VM(UK);                              // X was requested before the 16 weight loads
+    SV_WAIT_VM(16);                              // X was requested before the 16 weight loads
   } else {
     SV_WAIT_VM(0);
   }
@@ -611,34 +614,40 @@ __global__ __launch_bounds__(512) void stream_vocab_kernel(GemmP p, unsigned lon
     const int r = t * 16 + lr;
     xrow[t] = xs + (r < nrows ? r : nrows - 1) * ldxs + lq * 8;
   }
-  f32x4 acc[MT];
+  f32x4 acc[MT][NT];
   unsigned long long best[MT];
 #pragma unroll
   for (int t = 0; t < MT; ++t) best[t] = 0ull;
-  // one unit: 16 k-steps of one column tile against the MT row tiles
+  // one unit: UK k-steps of NT column tiles against the MT row tiles
 #define SV_MULT(A, u)                                                                           \
   {                                                                                             \
-    const int half_ = (u) % KH;                                                                 \
-    if (half_ == 0) { _Pragma("unroll") for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f}; } \
+    const int part_ = (u) % UPT;                                                                \
+    if (part_ == 0) {                                                                           \
+      _Pragma("unroll") for (int t = 0; t < MT; ++t)                                            \
+        _Pragma("unroll") for (int n = 0; n < NT; ++n) acc[t][n] = f32x4{0.f, 0.f, 0.f, 0.f};   \
+    }                                                                                           \
     __builtin_amdgcn_sched_barrier(0);                                                          \
     _Pragma("unroll") for (int i0 = 0; i0 < UK; i0 += 2) {                                      \
       uint4 bb_[2][MT];                                                                         \
       _Pragma("unroll") for (int i = 0; i < 2; ++i)                                             \
-        _Pragma("unroll") for (int t = 0; t < MT; ++t) bb_[i][t] = *(const uint4*)(xrow[t] + (half_ * UK + i0 + i) * 32); \
+        _Pragma("unroll") for (int t = 0; t < MT; ++t) bb_[i][t] = *(const uint4*)(xrow[t] + (part_ * UK + i0 + i) * 32); \
       _Pragma("unroll") for (int i = 0; i < 2; ++i)                                             \
         _Pragma("unroll") for (int t = 0; t < MT; ++t)                                          \
-          acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[i0 + i]), __builtin_bit_cast(bf16x8, bb_[i][t]), acc[t], 0, 0, 0); \
+          _Pragma("unroll") for (int n = 0; n < NT; ++n)                                        \
+            acc[t][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A[n * UK + i0 + i]), __builtin_bit_cast(bf16x8, bb_[i][t]), acc[t][n], 0, 0, 0); \
       __builtin_amdgcn_sched_barrier(0);                                                        \
     }                                                                                           \
-    if (half_ == KH - 1) {                                                                      \
-      const int n_ = (t0 + wave + WAVES * ((u) / KH)) * 16 + lq * 4;                            \
-      _Pragma("unroll") for (int t = 0; t < MT; ++t) {                                          \
-        _Pragma("unroll") for (int r = 0; r < 4; ++r) {                                         \
-          const unsigned long long key_ = argmax_key(acc[t][r], (unsigned)(n_ + r));            \
-          best[t] = key_ > best[t] ? key_ : best[t];                                            \
+    if (part_ == UPT - 1) {                                                                     \
+      _Pragma("unroll") for (int n = 0; n < NT; ++n) {                                          \
+        const int n_ = SV_TILE(u, n) * 16 + lq * 4;                                             \
+        _Pragma("unroll") for (int t = 0; t < MT; ++t) {                                        \
+          _Pragma("unroll") for (int r = 0; r < 4; ++r) {                                       \
+            const unsigned long long key_ = argmax_key(acc[t][n][r], (unsigned)(n_ + r));       \
+            best[t] = key_ > best[t] ? key_ : best[t];                                          \
+          }                                                                                     \
+          const int m_ = m0 + t * 16 + lr;                                                      \
+          if (logits && m_ < p.M) *(float4*)(logits + (long)m_ * p.N + n_) = make_float4(acc[t][n][0], acc[t][n][1], acc[t][n][2], acc[t][n][3]); \
         }                                                                                       \
-        const int m_ = m0 + t * 16 + lr;                                                        \
-        if (logits && m_ < p.M) *(float4*)(logits + (long)m_ * p.N + n_) = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]); \
       }                                                                                         \
     }                                                                                           \
   }
@@ -660,6 +669,7 @@ __global__ __launch_bounds__(512) void stream_vocab_kernel(GemmP p, unsigned lon
 #undef SV_MULT
 #undef SV_WAIT_VM
 #undef SV_LOADU
+#undef SV_TILE
   // lanes l, l^16, l^32, l^48 hold the same rows
 #pragma unroll
   for (int t = 0; t < MT; ++t) {
