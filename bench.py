@@ -227,6 +227,11 @@ def main():
                         ("vocab", binding.PHASE_VOCAB), ("layers", binding.PHASE_LAYERS)):
         ms = profile_phase(ctx, phase, cfg1, src, n, max_len, sched, k, min(args.steps, 60), torch)
         kern[name] = {"ms": ms, "GBps": nbytes[name] / ms / 1e6}
+    # what two events with nothing between them read on this stream: the part of every figure above that is the bracketing,
+    # not the kernel (rocprofv3 reports kernel durations without it); `achieved` below keeps the raw event figure
+    bracket_ms = profile_phase(ctx, binding.PHASE_EMPTY, cfg1, src, n, max_len, sched, k, min(args.steps, 60), torch)
+    for name in ("head_hidden", "head_out", "vocab"):
+        kern[name]["ms_minus_empty_bracket"] = kern[name]["ms"] - bracket_ms
     dom = max(("head_hidden", "head_out", "vocab"), key=lambda q: kern[q]["ms"])
     # HBM bytes per launch of that kernel measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by
     # a copy kernel of known size); recorded by hand from the runs summarised under profiles/
@@ -265,7 +270,7 @@ def main():
                 "frac": kern[dom]["GBps"] / HBM_PEAK_GBS, "traffic": traffic,
                 "frac_of_measured_peak": (kern[dom]["GBps"] / peaks["hbm_read_GBps"]) if peaks else None,
                 "step_achieved": total_bytes / (ms_step * 1e6), "step_frac": total_bytes / (ms_step * 1e6) / HBM_PEAK_GBS,
-                "kernels": kern}
+                "kernels": kern, "empty_event_bracket_ms": bracket_ms}
 
     out = {
         "metric": "accepted tokens/s (bpd_step, Transformer-big k=10, batch 1)",

@@ -190,6 +190,7 @@ int bpd_debug_step_logits(bpd_ctx* ctx, int k, float* logits);
 #define BPD_PHASE_VOCAB        4   /* vocabulary projection + argmax: one kernel                  */
 #define BPD_PHASE_ACCEPT       5   /* verify / accept / commit                                    */
 #define BPD_PHASE_STEP         6   /* the whole step                                              */
+#define BPD_PHASE_EMPTY        7   /* nothing: two events back to back, what the bracketing itself costs */
 int bpd_profile_enable(bpd_ctx* ctx, int phase);
 int bpd_profile_read(bpd_ctx* ctx, double* total_ms, int64_t* launches);
 /* As bpd_profile_read, and additionally copies the milliseconds of the first `capacity` launches,

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbpd.so")
 
 BPD_F32, BPD_BF16 = 0, 1
-PHASE_NONE, PHASE_LAYERS, PHASE_HEAD_HIDDEN, PHASE_HEAD_OUT, PHASE_VOCAB, PHASE_ACCEPT, PHASE_STEP = range(7)
+PHASE_NONE, PHASE_LAYERS, PHASE_HEAD_HIDDEN, PHASE_HEAD_OUT, PHASE_VOCAB, PHASE_ACCEPT, PHASE_STEP, PHASE_EMPTY = range(8)
 ERRORS = {-1: "BPD_E_ARG", -2: "BPD_E_STATE", -3: "BPD_E_CAPACITY", -4: "BPD_E_WEIGHTS", -5: "BPD_E_HIP"}
 
 

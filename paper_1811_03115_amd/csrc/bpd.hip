@@ -696,6 +696,7 @@ int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
       gemm(ctx, gp(L.ffh, F, w.w2, d, M, d, F), residual(w.b2));
     }
   }
+  { PhaseTimer t(ctx, BPD_PHASE_EMPTY); }       // calibration of the event bracketing itself
   if (ctx->two_phase && R == k && k > 1 && !sp && !logits && c.dtype == BPD_BF16) return heads_two_phase(ctx, k);
   // the k residual FFN heads: final LayerNorm + hidden layers side by side (h kept in fp32
   // for the residual), then one output layer per head
@@ -1110,7 +1111,7 @@ int bpd_debug_step_logits(bpd_ctx* ctx, int k, float* logits) {
 }
 
 int bpd_profile_enable(bpd_ctx* ctx, int phase) {
-  if (!ctx || phase < 0 || phase > BPD_PHASE_STEP) return BPD_E_ARG;
+  if (!ctx || phase < 0 || phase > BPD_PHASE_EMPTY) return BPD_E_ARG;
   (void)hipStreamSynchronize(ctx->stream);
   ctx->prof_phase = phase; ctx->prof_used = 0; ctx->prof_launches = 0;
   return BPD_OK;
