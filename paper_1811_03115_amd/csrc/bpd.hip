@@ -42,7 +42,7 @@ struct Layout {
   // caches
   void *selfK, *selfV, *crossK, *crossV;        // [n_dec][B][slots|max_src][d]
   // decoder activations (M = max_batch * k_max rows)
-  float *x, *q, *h, *stats_ln, *zeros, *attn_part, *kpart; size_t n_zeros, n_kpart; void *xn, *attn, *ffh, *hn, *H, *O;
+  float *x, *q, *h, *stats_ln, *stats_big, *zeros, *attn_part, *kpart; size_t n_zeros, n_kpart; void *xn, *attn, *ffh, *hn, *H, *O;
   unsigned long long* keys; unsigned long long* keys_h1; unsigned long long* keys2; float* logits_h1; int* topn_ok;
   void* hn2; float* h2; int* sel;
   // encoder activations (max_batch * max_src rows)
@@ -113,6 +113,7 @@ size_t build_layout(const bpd_config& c, char* base, Layout& L) {
   L.hn2 = a.take(B * d * as); L.h2 = vec(B * d);
   L.logits_h1 = vec(M * V);
   const size_t Me = B * S;
+  L.stats_big = vec((size_t)(d / 16 + 1) * (M > Me ? M : Me) * 2);   // per 16-column tile and row: sum, sum of squares
   L.xe = vec(Me * d); L.qe = vec(Me * d);
   L.xen = a.take(Me * d * as); L.ke = a.take(Me * d * as); L.ve = a.take(Me * d * as);
   L.attne = a.take(Me * d * as); L.ffhe = a.take(Me * F * as); L.mem = a.take(Me * d * as);
@@ -337,17 +338,18 @@ bool stats_path(const bpd_ctx* ctx, int M) {
 }
 
 // ---- ldsx path: many rows ---------------------------------------------------------------
-template <int MT, int NT, int KC, bool ARGMAX>
-void launch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* logits, int groups, hipStream_t s) {
+template <int MT, int NT, int KC, bool ARGMAX, bool XLN = false, bool STATS = false>
+void launch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* logits, int groups, hipStream_t s,
+                 const LnP& ln = LnP{}) {
   const int ntiles = p.N / 16;
   dim3 grid((ntiles + 4 * NT - 1) / (4 * NT), (p.M + 16 * MT - 1) / (16 * MT), groups);
   const size_t lds = ldsx_lds_bytes<MT, NT, KC>();
   static bool attr_set = false;                 // per instantiation: allow more than 64 KiB of LDS
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)gemm_ldsx_kernel<MT, NT, KC, ARGMAX>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute((const void*)gemm_ldsx_kernel<MT, NT, KC, ARGMAX, XLN, STATS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_ldsx_kernel<MT, NT, KC, ARGMAX>), grid, dim3(256), lds, s, p, e, keys, logits);
+  hipLaunchKernelGGL((gemm_ldsx_kernel<MT, NT, KC, ARGMAX, XLN, STATS>), grid, dim3(256), lds, s, p, e, keys, logits, ln);
 }
 
 // Tile of the LDS-staged GEMM: 16*mt rows x 64*nt columns per workgroup, K walked in chunks of
@@ -356,9 +358,11 @@ void launch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* 
 // slices and groups); ties go to less row padding, then to the narrower tile (longer chunks).
 // With nt = 1 at most 48 rows, so that the two 256-deep staging buffers leave room for three
 // workgroups per CU.  If nothing qualifies the smallest tile spreads the work furthest.
+constexpr int LDSX_LN_MT_MAX = 3;      // LayerNorm-fused consumers and statistics-writing producers: tiles of at most 48 rows
+constexpr int LDSX_LN_M_MAX = 128;     // and blocks of at most 128 rows
 constexpr long LDSX_MIN_WGS = 448;
 constexpr long LDSX_MIN_WGS_LONGK = 320;   // K >= 2048: a workgroup lives long enough that 1.25 per CU suffice
-void pick_tile(int M, int N, int K, long zdim, bool argmax, int& mt, int& nt) {
+void pick_tile(int M, int N, int K, long zdim, bool argmax, int& mt, int& nt, int mt_max = 8) {
   const int mts[7] = {8, 7, 5, 4, 3, 2, 1};
   long best_area = 0, best_pad = 0;
   mt = 1; nt = (K % 256 == 0) ? 1 : 4;
@@ -366,7 +370,7 @@ void pick_tile(int M, int N, int K, long zdim, bool argmax, int& mt, int& nt) {
     if (K % (256 / n) != 0) continue;
     const long cols = (N / 16 + 4 * n - 1) / (4 * n);
     for (int m : mts) {
-      if (n == 1 && m > 3) continue;
+      if ((n == 1 && m > 3) || m > mt_max) continue;
       const long bm = 16 * m, mblocks = (M + bm - 1) / bm, pad = mblocks * bm;
       if (mblocks * cols * zdim < (K >= 2048 ? LDSX_MIN_WGS_LONGK : LDSX_MIN_WGS)) continue;
       const long area = (long)m * n;                  // compared as area * M / pad: padded rows are wasted work
@@ -377,26 +381,57 @@ void pick_tile(int M, int N, int K, long zdim, bool argmax, int& mt, int& nt) {
   }
 }
 
+// e.stats_out (mode 0, one group, no split over K): the kernel also writes the LayerNorm statistics of its output, which
+// only the tiles of at most 48 rows are built for.  Returns whether it did.
 template <bool ARGMAX>
-void dispatch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* logits, int groups, hipStream_t s) {
+bool dispatch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* logits, int groups, hipStream_t s) {
   int mt, nt;
   const int kslice = p.ksplit > 1 ? p.K / p.ksplit : p.K;
-  pick_tile(p.M, p.N, kslice, groups, ARGMAX, mt, nt);       // groups = K slices for a split-K launch
-#define BPD_CASE(MT_, NT_, KC_) if (mt == MT_ && nt == NT_) { launch_ldsx<MT_, NT_, KC_, ARGMAX>(p, e, keys, logits, groups, s); return; }
+  const bool stats = !ARGMAX && e.mode == 0 && e.stats_out != nullptr && groups == 1 && p.ksplit <= 1;
+  pick_tile(p.M, p.N, kslice, groups, ARGMAX, mt, nt, stats ? LDSX_LN_MT_MAX : 8);       // groups = K slices for a split-K launch
+  if constexpr (!ARGMAX) {
+    if (stats) {
+#define BPD_CASE(MT_, NT_, KC_) if (mt == MT_ && nt == NT_) { launch_ldsx<MT_, NT_, KC_, false, false, true>(p, e, keys, logits, groups, s); return true; }
+      BPD_CASE(3, 1, 256) BPD_CASE(2, 1, 256) BPD_CASE(1, 1, 256)
+      BPD_CASE(3, 2, 128) BPD_CASE(2, 2, 128) BPD_CASE(1, 2, 128)
+      BPD_CASE(3, 4, 64) BPD_CASE(2, 4, 64) BPD_CASE(1, 4, 64)
+#undef BPD_CASE
+    }
+  }
+#define BPD_CASE(MT_, NT_, KC_) if (mt == MT_ && nt == NT_) { launch_ldsx<MT_, NT_, KC_, ARGMAX>(p, e, keys, logits, groups, s); return false; }
   BPD_CASE(3, 1, 256) BPD_CASE(2, 1, 256) BPD_CASE(1, 1, 256)
   BPD_CASE(8, 2, 128) BPD_CASE(7, 2, 128) BPD_CASE(5, 2, 128) BPD_CASE(4, 2, 128) BPD_CASE(3, 2, 128) BPD_CASE(2, 2, 128) BPD_CASE(1, 2, 128)
   BPD_CASE(8, 4, 64) BPD_CASE(7, 4, 64) BPD_CASE(5, 4, 64) BPD_CASE(4, 4, 64) BPD_CASE(3, 4, 64) BPD_CASE(2, 4, 64) BPD_CASE(1, 4, 64)
 #undef BPD_CASE
+  return false;
+}
+
+// Y = epilogue(LayerNorm(ln.x) W) on more than 16 rows with the LayerNorm applied while the activations are staged
+// (tiles of at most 48 rows: the staging registers).
+void dispatch_ldsx_ln(const GemmP& p, const Epi& e, const LnP& ln, hipStream_t s) {
+  int mt, nt;
+  pick_tile(p.M, p.N, p.K, 1, false, mt, nt, LDSX_LN_MT_MAX);
+#define BPD_CASE(MT_, NT_, KC_) if (mt == MT_ && nt == NT_) { launch_ldsx<MT_, NT_, KC_, false, true>(p, e, nullptr, nullptr, 1, s, ln); return; }
+  BPD_CASE(3, 1, 256) BPD_CASE(2, 1, 256) BPD_CASE(1, 1, 256)
+  BPD_CASE(3, 2, 128) BPD_CASE(2, 2, 128) BPD_CASE(1, 2, 128)
+  BPD_CASE(3, 4, 64) BPD_CASE(2, 4, 64) BPD_CASE(1, 4, 64)
+#undef BPD_CASE
+}
+bool ldsx_ln_ok(const bpd_ctx* ctx, const GemmP& p) {
+  return ctx->cfg.dtype == BPD_BF16 && p.M > 16 && p.K == ctx->cfg.d_model && p.K % 64 == 0 && p.K <= 1024 && p.N % 16 == 0;
 }
 
 // Y = epilogue(X W).  bf16 mode: M <= 16 -> skinny kernel; otherwise the LDS-staged kernel
 // (K % 64 == 0) or the plain MFMA kernel.  fp32 mode: one thread per output.
-void gemm(bpd_ctx* ctx, const GemmP& p, const Epi& e, int groups = 1) {
+// Returns true if the kernel left the per-tile LayerNorm statistics of its output in e.stats_out in the layout of the
+// LDS-staged kernel (more than 16 rows, no split over K).
+bool gemm(bpd_ctx* ctx, const GemmP& p, const Epi& e_in, int groups = 1) {
   hipStream_t s = ctx->stream;
+  Epi e = e_in;
   if (ctx->cfg.dtype != BPD_BF16) {
     dim3 grid((p.N + 127) / 128, p.M, groups);
     hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(128), 0, s, p, e);
-    return;
+    return false;
   }
   LnP none{};
   if (stream_ok(ctx, p, e, groups)) {
@@ -407,7 +442,7 @@ void gemm(bpd_ctx* ctx, const GemmP& p, const Epi& e, int groups = 1) {
   } else if (p.K % 64 == 0) {
     // In-place residual update with a long K and few output tiles: split K over workgroups.  The
     // slices are added, in a fixed order, by the LayerNorm kernel that reads the residual next.
-    if (groups == 1 && e.mode == 0 && e.R && e.R == e.Yf && !e.Ya && !e.relu && !e.stats_out && !e.lnR_stats &&
+    if (groups == 1 && e.mode == 0 && e.R && e.R == e.Yf && !e.Ya && !e.relu && !e.lnR_stats &&
         e.ldr == p.N && e.ldyf == p.N && p.N == ctx->cfg.d_model && p.K >= 2048) {
       // fewest slices with which a tile of at least 48 rows still fills the chip; if no slicing gets
       // there, the most slices allowed (each at least 256 deep)
@@ -423,16 +458,19 @@ void gemm(bpd_ctx* ctx, const GemmP& p, const Epi& e, int groups = 1) {
       if (ns > 1) {
         GemmP q = p;
         q.ksplit = ns; q.part = ctx->lay.kpart;
+        e.stats_out = nullptr;                     // the slices are raw products: no statistics of the sum yet
         dispatch_ldsx<false>(q, e, nullptr, nullptr, ns, s);
         ctx->pend_slices = ns; ctx->pend_bias = e.bias ? e.bias : ctx->lay.zeros; ctx->pend_x = e.Yf;
-        return;
+        return false;
       }
     }
-    dispatch_ldsx<false>(p, e, nullptr, nullptr, groups, s);
+    return dispatch_ldsx<false>(p, e, nullptr, nullptr, groups, s);
   } else {
+    e.stats_out = nullptr;
     if (p.M > 64) launch_gemm_bf16<8, 1, 4>(p, e, groups, s);
     else launch_gemm_bf16<4, 1, 4>(p, e, groups, s);
   }
+  return false;
 }
 
 void layernorm(bpd_ctx* ctx, float* x, LnW w, int M, void* ya, float* yf);
@@ -440,13 +478,19 @@ void layernorm(bpd_ctx* ctx, float* x, LnW w, int M, void* ya, float* yf);
 // Y = epilogue(LayerNorm(x) W).  Block of <= 16 rows: LayerNorm is applied inside the skinny
 // kernel from the partial statistics the producer of x left in L.stats_ln.  Otherwise a
 // LayerNorm kernel (into `xn`, and `yf` in fp32 if given) followed by the GEMM.
-void gemm_ln(bpd_ctx* ctx, float* x, LnW w, void* xn, float* yf, GemmP p, const Epi& e, bool with_stats) {
+void gemm_ln(bpd_ctx* ctx, float* x, LnW w, void* xn, float* yf, GemmP p, const Epi& e, bool with_stats, bool big_stats = false) {
   // with_stats: the producer of x left its partial LayerNorm statistics in L.stats_ln (decoder block of one
   // row tile only; the encoder's kernels do not write them)
   if (with_stats && stats_path(ctx, p.M) && p.K == ctx->cfg.d_model) {
     LnP ln{x, w.g, w.b, ctx->lay.stats_ln, ctx->cfg.ln_eps};
     if (p.N / 16 >= 2048) launch_skinny<2, true, false>(ctx, p, e, ln, nullptr, nullptr, 1);
     else launch_skinny<1, true, false>(ctx, p, e, ln, nullptr, nullptr, 1);
+    return;
+  }
+  // big_stats: more than 16 rows and the GEMM that produced x left per-tile statistics in L.stats_big
+  if (big_stats && !yf && ldsx_ln_ok(ctx, p)) {
+    LnP ln{x, w.g, w.b, ctx->lay.stats_big, ctx->cfg.ln_eps};
+    dispatch_ldsx_ln(p, e, ln, ctx->stream);
     return;
   }
   layernorm(ctx, x, w, p.M, xn, yf);
@@ -669,11 +713,16 @@ int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
   const long nk = (long)M * k;
   const bool sp = stats_path(ctx, M);
   // residual update x += ...; on the statistics path the kernel also leaves LayerNorm partial sums
+  // with more rows the LDS-staged kernel leaves them per tile in L.stats_big for the LayerNorm-fused GEMM that follows
+  // (up to 128 rows: with more, every column block repeating the normalisation of its rows costs more than the kernel saved)
+  const bool bigs = !sp && c.dtype == BPD_BF16 && M > 16 && M <= LDSX_LN_M_MAX && d % 64 == 0 && d <= 1024;
   auto residual = [&](const float* bias) {
     Epi e = plain(bias, 0, L.x, d, L.x, d, nullptr, 0);
     if (sp) e.stats_out = L.stats_ln;
+    else if (bigs) e.stats_out = L.stats_big;
     return e;
   };
+  bool xs = false;      // L.stats_big describes the current L.x
   {
     PhaseTimer t(ctx, BPD_PHASE_LAYERS);
     embed(ctx, L.P, c.k_max, L.L, R, M, L.pos_tgt, L.x, zero_input, L.keys, (int)nk);
@@ -684,16 +733,16 @@ int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
       char* cK = (char*)L.crossK + (size_t)l * c.max_batch * c.max_src_len * d * as;
       char* cV = (char*)L.crossV + (size_t)l * c.max_batch * c.max_src_len * d * as;
       // self-attention sublayer: K/V of the block rows go straight into the cache at L_b + i'
-      gemm_ln(ctx, L.x, w.ln1, L.xn, nullptr, gp(L.xn, d, w.wqkv, 3 * d, M, 3 * d, d), split(L.q, Kl, Vl, d, 0, R, slots, L.L), sp);
+      gemm_ln(ctx, L.x, w.ln1, L.xn, nullptr, gp(L.xn, d, w.wqkv, 3 * d, M, 3 * d, d), split(L.q, Kl, Vl, d, 0, R, slots, L.L), sp, xs);
       attention(ctx, L.q, Kl, Vl, L.attn, slots, B, R, L.L, 1);
-      gemm(ctx, gp(L.attn, d, w.wo, d, M, d, d), residual(nullptr));
+      xs = gemm(ctx, gp(L.attn, d, w.wo, d, M, d, d), residual(nullptr));
       // cross-attention sublayer over the encoder memory
-      gemm_ln(ctx, L.x, w.ln2, L.xn, nullptr, gp(L.xn, d, w.cq, d, M, d, d), plain(nullptr, 0, nullptr, 0, L.q, d, nullptr, 0), sp);
+      gemm_ln(ctx, L.x, w.ln2, L.xn, nullptr, gp(L.xn, d, w.cq, d, M, d, d), plain(nullptr, 0, nullptr, 0, L.q, d, nullptr, 0), sp, xs);
       attention(ctx, L.q, cK, cV, L.attn, c.max_src_len, B, R, L.src_len, 0);
-      gemm(ctx, gp(L.attn, d, w.co, d, M, d, d), residual(nullptr));
+      xs = gemm(ctx, gp(L.attn, d, w.co, d, M, d, d), residual(nullptr));
       // feed-forward sublayer
-      gemm_ln(ctx, L.x, w.ln3, L.xn, nullptr, gp(L.xn, d, w.w1, F, M, F, d), plain(w.b1, 1, nullptr, 0, nullptr, 0, L.ffh, F), sp);
-      gemm(ctx, gp(L.ffh, F, w.w2, d, M, d, F), residual(w.b2));
+      gemm_ln(ctx, L.x, w.ln3, L.xn, nullptr, gp(L.xn, d, w.w1, F, M, F, d), plain(w.b1, 1, nullptr, 0, nullptr, 0, L.ffh, F), sp, xs);
+      xs = gemm(ctx, gp(L.ffh, F, w.w2, d, M, d, F), residual(w.b2));
     }
   }
   { PhaseTimer t(ctx, BPD_PHASE_EMPTY); }       // calibration of the event bracketing itself

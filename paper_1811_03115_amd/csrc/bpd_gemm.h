@@ -13,19 +13,29 @@
 //     tile), activations are staged through LDS where all 4 waves reuse them.
 #pragma once
 
-template <int MT, int NT>
+// With e.stats_out (mode 0): per 16-column tile and row the sum and the sum of squares of the stored values go to
+// stats_out[(tile * M + row) * 2 + {0, 1}], for the LayerNorm that the next GEMM applies while it stages its activations.
+template <int MT, int NT, bool STATS>
 __device__ __forceinline__ void store_tiles(const Epi& e, int g, const f32x4 (&acc)[MT][NT], int m0, int nt0,
                                             int ntiles, int M, int lane) {
+  const bool stats = STATS && e.mode == 0 && e.stats_out != nullptr;
 #pragma unroll
   for (int t = 0; t < MT; ++t) {
     const int m = m0 + t * 16 + (lane & 15);
-    if (m >= M) continue;
 #pragma unroll
     for (int u = 0; u < NT; ++u) {
-      if (nt0 + u >= ntiles) continue;
+      if (nt0 + u >= ntiles) continue;            // the same for the whole wave
       const int n = (nt0 + u) * 16 + (lane >> 4) * 4;
       const float v[4] = {acc[t][u][0], acc[t][u][1], acc[t][u][2], acc[t][u][3]};
-      epi_store4(e, g, m, n, v);
+      float fin[4] = {0.f, 0.f, 0.f, 0.f};
+      if (m < M) epi_store4f(e, g, m, n, v, fin);
+      if (stats) {
+        float sv = (fin[0] + fin[1]) + (fin[2] + fin[3]);
+        float qv = (fin[0] * fin[0] + fin[1] * fin[1]) + (fin[2] * fin[2] + fin[3] * fin[3]);
+        sv += __shfl_xor(sv, 16, 64); sv += __shfl_xor(sv, 32, 64);
+        qv += __shfl_xor(qv, 16, 64); qv += __shfl_xor(qv, 32, 64);
+        if (lane < 16 && m < M) ((float2*)e.stats_out)[(long)(nt0 + u) * M + m] = make_float2(sv, qv);
+      }
     }
   }
 }
@@ -714,8 +724,13 @@ constexpr int ldsx_ring() { return ldsx_regs<MT, NT, KC>() <= 210 ? 2 : 1; }
 template <int MT, int NT, int KC>
 constexpr size_t ldsx_lds_bytes() { return (size_t)2 * ((16 * MT * (KC / 8) + 255) / 256) * 4096; }
 
-template <int MT, int NT, int KC, bool ARGMAX>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_min<MT, NT, KC>(), ldsx_waves_max<MT, NT, KC>()))) void gemm_ldsx_kernel(GemmP p, Epi e, unsigned long long* keys, float* logits) {
+// XLN (one group, no split-K, K <= 1024): X = LayerNorm(ln.x) of the fp32 residual stream.  The producer of ln.x left per
+// 16-column tile and row the sum and sum of squares of its values in ln.stats[(tile * M + row) * 2] (store_tiles); the
+// workgroup adds them for its rows, and every activation chunk goes global (fp32) -> registers -> normalised -> bf16 ->
+// LDS, in the layout the direct loads would have produced.  Saves the LayerNorm kernel and its round trip through memory.
+// STATS: store_tiles also writes the LayerNorm statistics of the output (e.stats_out).
+template <int MT, int NT, int KC, bool ARGMAX, bool XLN, bool STATS>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_min<MT, NT, KC>(), ldsx_waves_max<MT, NT, KC>()))) void gemm_ldsx_kernel(GemmP p, Epi e, unsigned long long* keys, float* logits, LnP ln) {
   constexpr int BM = 16 * MT, KS = KC / 32, SEG = KC / 8;
   constexpr int XI = (BM * SEG + 255) / 256;       // direct-to-LDS loads per thread per chunk
   constexpr int BUF = XI * 256 * 8;                // bf16 elements per buffer (whole wave-loads)
@@ -762,6 +777,121 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
   _Pragma("unroll") for (int i = 0; i < XI; ++i)                                            \
     __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(X + xoff[i] + (chunk) * KC), \
                                      (void __attribute__((address_space(3)))*)((buf) + (i * 256 + wave * 64) * 8), 16, 0, 0);
+  if constexpr (XLN) {
+    // ---- LayerNorm-fused variant: activations through registers
+    static_assert(256 % SEG == 0, "a thread keeps its 16-byte segment across its rows");
+    __shared__ float2 part_s[4][64];
+    __shared__ float2 ms_s[BM];
+    static_assert(BM <= 64, "one pass of the statistics reduction");
+    constexpr int RPI = 256 / SEG;               // rows between a thread's consecutive slots
+    const int seg = tid % SEG, rbase = tid / SEG;
+    const float* xp[XI];
+    int lo[XI], rcl[XI];
+#pragma unroll
+    for (int i = 0; i < XI; ++i) {
+      const int r = rbase + RPI * i;             // may pass BM when BM * SEG is not a multiple of 256: never read back
+      rcl[i] = r < BM ? r : BM - 1;
+      int row = m0 + rcl[i]; row = row < p.M ? row : p.M - 1;
+      xp[i] = ln.x + (long)row * p.K + seg * 8;
+      lo[i] = (r * SEG + (seg ^ (r & 7))) * 8;
+    }
+    uint4 a0[KS][NT], a1[KS][NT];
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+      for (int u = 0; u < NT; ++u) acc[t][u] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float4 xa[XI][2], ga[2], ba[2];
+#define BPD_LOAD_X(chunk)                                                                    \
+    {                                                                                        \
+      _Pragma("unroll") for (int i = 0; i < XI; ++i) {                                       \
+        xa[i][0] = *(const float4*)(xp[i] + (chunk) * KC); xa[i][1] = *(const float4*)(xp[i] + (chunk) * KC + 4); \
+      }                                                                                      \
+      ga[0] = *(const float4*)(ln.g + (chunk) * KC + seg * 8); ga[1] = *(const float4*)(ln.g + (chunk) * KC + seg * 8 + 4); \
+      ba[0] = *(const float4*)(ln.b + (chunk) * KC + seg * 8); ba[1] = *(const float4*)(ln.b + (chunk) * KC + seg * 8 + 4); \
+    }
+#define BPD_NORM1(v, gq, bq, i) ((v - mu[i]) * rs[i] * gq + bq)
+#define BPD_NORM_STORE(buf)                                                                  \
+    _Pragma("unroll") for (int i = 0; i < XI; ++i) {                                         \
+      const unsigned w0 = pack_bf16(BPD_NORM1(xa[i][0].x, ga[0].x, ba[0].x, i), BPD_NORM1(xa[i][0].y, ga[0].y, ba[0].y, i)); \
+      const unsigned w1 = pack_bf16(BPD_NORM1(xa[i][0].z, ga[0].z, ba[0].z, i), BPD_NORM1(xa[i][0].w, ga[0].w, ba[0].w, i)); \
+      const unsigned w2 = pack_bf16(BPD_NORM1(xa[i][1].x, ga[1].x, ba[1].x, i), BPD_NORM1(xa[i][1].y, ga[1].y, ba[1].y, i)); \
+      const unsigned w3 = pack_bf16(BPD_NORM1(xa[i][1].z, ga[1].z, ba[1].z, i), BPD_NORM1(xa[i][1].w, ga[1].w, ba[1].w, i)); \
+      *(uint4*)((buf) + lo[i]) = make_uint4(w0, w1, w2, w3);                                 \
+    }
+#define BPD_LOAD_WX(dst, chunk)                                                              \
+    _Pragma("unroll") for (int s = 0; s < KS; ++s)                                           \
+      _Pragma("unroll") for (int u = 0; u < NT; ++u) dst[s][u] = wt[u][(long)((chunk) * KS + s) * 64];
+    // activations are requested before the weights: waiting for them leaves the weights in flight
+#define BPD_CHUNK_X(AC, AL, xc, xl, c)                                                       \
+    {                                                                                        \
+      const int cl = (c) + 1 < nchunks ? (c) + 1 : nchunks - 1;                              \
+      BPD_LOAD_X(cl)                                                                         \
+      BPD_LOAD_WX(AL, cl)                                                                    \
+      __builtin_amdgcn_sched_barrier(0);                                                     \
+      _Pragma("unroll") for (int s = 0; s < KS; ++s) {                                       \
+        uint4 b[MT];                                                                         \
+        _Pragma("unroll") for (int t = 0; t < MT; ++t)                                       \
+          b[t] = *(const uint4*)((xc) + (t * 16 + lr) * KC + (((s * 4 + lq) ^ (lr & 7)) * 8)); \
+        _Pragma("unroll") for (int t = 0; t < MT; ++t)                                       \
+          _Pragma("unroll") for (int u = 0; u < NT; ++u)                                     \
+            acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, AC[s][u]), \
+                                                                __builtin_bit_cast(bf16x8, b[t]), acc[t][u], 0, 0, 0); \
+      }                                                                                      \
+      __builtin_amdgcn_sched_barrier(0);                                                     \
+      BPD_NORM_STORE(xl)                                                                     \
+      __syncthreads();                                                                       \
+    }
+    // one round trip for everything the first chunk needs: the statistics, the first activations and weights
+    float mu[XI], rs[XI];
+    {
+      const int tiles = p.K >> 4;                // <= 64
+      int row = m0 + lane; row = row < p.M ? row : p.M - 1;
+      float2 pv[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {             // branch-free: all loads in flight together
+        const int t = wave + 4 * i;
+        pv[i] = ((const float2*)ln.stats)[(long)(t < tiles ? t : 0) * p.M + row];
+      }
+      BPD_LOAD_X(0)
+      BPD_LOAD_WX(a0, 0)
+      __builtin_amdgcn_sched_barrier(0);
+      float sq = 0.f, qq = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const float w = (wave + 4 * i) < tiles ? 1.f : 0.f;
+        sq = fmaf(w, pv[i].x, sq); qq = fmaf(w, pv[i].y, qq);
+      }
+      part_s[wave][lane] = make_float2(sq, qq);
+      __syncthreads();
+      if (tid < BM) {
+        float S = part_s[0][tid].x, Q = part_s[0][tid].y;
+#pragma unroll
+        for (int w = 1; w < 4; ++w) { S += part_s[w][tid].x; Q += part_s[w][tid].y; }
+        const float mean = S / p.K;
+        const float var = fmaxf(Q / p.K - mean * mean, 0.f);
+        ms_s[tid] = make_float2(mean, 1.0f / sqrtf(var + ln.eps));
+      }
+      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < XI; ++i) { const float2 ms = ms_s[rcl[i]]; mu[i] = ms.x; rs[i] = ms.y; }
+    }
+    BPD_NORM_STORE(xs0)
+    __syncthreads();
+    for (int c = 0; c < nchunks; c += 2) {
+      BPD_CHUNK_X(a0, a1, xs0, xs1, c)
+      if (c + 1 >= nchunks) break;
+      BPD_CHUNK_X(a1, a0, xs1, xs0, c + 1)
+    }
+#undef BPD_CHUNK_X
+#undef BPD_LOAD_WX
+#undef BPD_NORM_STORE
+#undef BPD_NORM1
+#undef BPD_LOAD_X
+    if (nt0 >= ntiles) return;
+    store_tiles<MT, NT, STATS>(e, g, acc, m0, nt0, ntiles, p.M, lane);
+    return;
+  }
   // The chunk being multiplied and the next one are in use / in flight: weights in two register buffers, activations in
   // two LDS buffers.  RING == 2: the register buffers take turns; RING == 1: a register copy per chunk.
   constexpr int RING = ldsx_ring<MT, NT, KC>();
@@ -873,5 +1003,5 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
     }
     return;
   }
-  store_tiles<MT, NT>(e, g, acc, m0, nt0, ntiles, p.M, lane);
+  store_tiles<MT, NT, STATS>(e, g, acc, m0, nt0, ntiles, p.M, lane);
 }

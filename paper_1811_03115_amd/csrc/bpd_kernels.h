@@ -57,7 +57,8 @@ struct Epi {
   void* Ya;        int ldya;
   long bias_g, r_g, yf_g, ya_g;      // per-group (blockIdx.z) element offsets
   // skinny kernels only: the residual operand is LayerNorm(R) computed from partial statistics,
-  // and/or partial LayerNorm statistics of the result are written (see bpd_gemm.h)
+  // and/or partial LayerNorm statistics of the result are written (see bpd_gemm.h; the LDS-staged kernel writes them
+  // too, with the row count as the stride between column tiles)
   const float* lnR_stats; const float* lnR_g; const float* lnR_b; int lnR_K; float lnR_eps;
   float* stats_out;
   // mode 1
@@ -92,7 +93,8 @@ __device__ __forceinline__ void epi_store(const Epi& e, int g, int m, int n, flo
 // activations: the same arithmetic as epi_store with 16-byte loads and 8- / 16-byte stores.
 // Needs ldr, ldyf, ldya, dsplit and the per-group offsets to be multiples of 4 (they are model
 // dimensions, multiples of 16).
-__device__ __forceinline__ void epi_store4(const Epi& e, int g, int m, int n, const float (&acc)[4]) {
+// `fin` receives the stored values (mode 0).
+__device__ __forceinline__ void epi_store4f(const Epi& e, int g, int m, int n, const float (&acc)[4], float (&fin)[4]) {
   float v[4] = {acc[0], acc[1], acc[2], acc[3]};
   if (e.mode == 0) {
     if (e.bias) {
@@ -110,6 +112,7 @@ __device__ __forceinline__ void epi_store4(const Epi& e, int g, int m, int n, co
     if (e.Yf) *(float4*)(e.Yf + g * e.yf_g + (long)m * e.ldyf + n) = make_float4(v[0], v[1], v[2], v[3]);
     if (e.Ya) *(uint2*)((bf16_t*)e.Ya + g * e.ya_g + (long)m * e.ldya + n) =
                   make_uint2((unsigned)f2bf(v[0]) | ((unsigned)f2bf(v[1]) << 16), (unsigned)f2bf(v[2]) | ((unsigned)f2bf(v[3]) << 16));
+    fin[0] = v[0]; fin[1] = v[1]; fin[2] = v[2]; fin[3] = v[3];
   } else {
     const int c = n / e.dsplit + e.chunk0;
     const int col = n % e.dsplit;
@@ -123,6 +126,11 @@ __device__ __forceinline__ void epi_store4(const Epi& e, int g, int m, int n, co
           make_uint2((unsigned)f2bf(v[0]) | ((unsigned)f2bf(v[1]) << 16), (unsigned)f2bf(v[2]) | ((unsigned)f2bf(v[3]) << 16));
     }
   }
+}
+
+__device__ __forceinline__ void epi_store4(const Epi& e, int g, int m, int n, const float (&acc)[4]) {
+  float fin[4];
+  epi_store4f(e, g, m, n, acc, fin);
 }
 
 struct GemmP {
