@@ -809,13 +809,21 @@ int encoder(bpd_ctx* ctx) {
   const int B = ctx->B, S = ctx->S, d = c.d_model, F = c.d_ff, M = B * S;
   const size_t as = act_size(c);
   embed(ctx, L.src_ids, S, nullptr, S, M, L.pos_src, L.xe, 0);
+  // 17 .. 128 source rows: the residual GEMMs leave LayerNorm statistics for the LayerNorm-fused GEMM that follows
+  const bool bigs = c.dtype == BPD_BF16 && M > 16 && M <= LDSX_LN_M_MAX && d % 64 == 0 && d <= 1024;
+  auto residual = [&](const float* bias) {
+    Epi e = plain(bias, 0, L.xe, d, L.xe, d, nullptr, 0);
+    if (bigs) e.stats_out = L.stats_big;
+    return e;
+  };
+  bool xs = false;      // L.stats_big describes the current L.xe
   for (int l = 0; l < c.n_enc_layers; ++l) {
     EncL& w = L.enc[l];
-    gemm_ln(ctx, L.xe, w.ln1, L.xen, nullptr, gp(L.xen, d, w.wqkv, 3 * d, M, 3 * d, d), split(L.qe, L.ke, L.ve, d, 0, S, S, nullptr), false);
+    gemm_ln(ctx, L.xe, w.ln1, L.xen, nullptr, gp(L.xen, d, w.wqkv, 3 * d, M, 3 * d, d), split(L.qe, L.ke, L.ve, d, 0, S, S, nullptr), false, xs);
     attention(ctx, L.qe, L.ke, L.ve, L.attne, S, B, S, L.src_len, 0);
-    gemm(ctx, gp(L.attne, d, w.wo, d, M, d, d), plain(nullptr, 0, L.xe, d, L.xe, d, nullptr, 0));
-    gemm_ln(ctx, L.xe, w.ln2, L.xen, nullptr, gp(L.xen, d, w.w1, F, M, F, d), plain(w.b1, 1, nullptr, 0, nullptr, 0, L.ffhe, F), false);
-    gemm(ctx, gp(L.ffhe, F, w.w2, d, M, d, F), plain(w.b2, 0, L.xe, d, L.xe, d, nullptr, 0));
+    xs = gemm(ctx, gp(L.attne, d, w.wo, d, M, d, d), residual(nullptr));
+    gemm_ln(ctx, L.xe, w.ln2, L.xen, nullptr, gp(L.xen, d, w.w1, F, M, F, d), plain(w.b1, 1, nullptr, 0, nullptr, 0, L.ffhe, F), false, xs);
+    xs = gemm(ctx, gp(L.ffhe, F, w.w2, d, M, d, F), residual(w.b2));
   }
   layernorm(ctx, L.xe, L.enc_lnf, M, L.mem, nullptr);
   for (int l = 0; l < c.n_dec_layers; ++l) {
