@@ -751,17 +751,21 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnP p) {
   }
 }
 
-// bf16, 64-wide heads: the same computation on the matrix cores.  Per 256-key chunk
-//   scores^T = K Q^T     keys are the 16-wide "feature" side of the MFMA, the <= 16 query rows the
-//                        other; K fragments come straight from the cache (a key row is contiguous
-//                        along the contracted head dimension), wave w takes keys 64w .. 64w+63;
-//   softmax              running (max, sum) per row as in attention_kernel, probabilities in LDS;
-//   out^T  = V^T P^T     contracted over keys: wave w owns head dimensions 16w .. 16w+15 and gathers
-//                        its V^T fragments from the chunk of V rows staged in LDS (row stride 68
-//                        elements, so the four key groups of a fragment read disjoint banks).
-// fp32 operands (Q, the probabilities) are fed as a bf16 pair hi + lo, which keeps them to ~2^-17:
-// the result matches the scalar kernel to fp32 rounding.  Same arguments, grid and partial-result
-// layout as attention_kernel.
+// bf16, 64-wide heads: the same computation on the matrix cores, one barrier per workgroup.  The four waves split
+// the keys: of every 256-key chunk wave w takes keys 64w .. 64w+63 and keeps its own running maximum, sum and weighted
+// values in registers; the waves' results meet once, in LDS, at the end.  Per chunk and wave
+//   scores^T = K Q^T     keys are the 16-wide "feature" side of the MFMA, the <= 16 query rows the other; K fragments
+//                        come straight from the cache (a key row is contiguous along the contracted head dimension);
+//                        a lane then holds, for its query row, the scores of 4 keys of each of the 4 key tiles
+//   softmax              maximum and sum over the wave's 64 keys: in the lane, then across the 4 lanes of a row;
+//                        the probabilities stay in registers: the scores of two key tiles are, as they lie, the
+//                        second MFMA operand for a contraction over those 32 keys (in a permuted key order)
+//   out^T += V^T P^T     contracted over keys, 64 head dimensions = 4 output tiles; the V^T fragments (same key
+//                        order) are gathered from the wave's own 64 V rows staged in LDS (row stride 68 elements,
+//                        so the four key groups of a fragment read disjoint banks; no barrier: a wave's LDS
+//                        accesses execute in order)
+// fp32 operands (Q, the probabilities) are fed as a bf16 pair hi + lo, which keeps them to ~2^-17: the result matches
+// the scalar kernel to fp32 rounding.  Same arguments, grid and partial-result layout as attention_kernel.
 __device__ __forceinline__ void split_bf16x8(const float (&v)[8], bf16x8& hi, bf16x8& lo) {
   unsigned h[4], l[4];
 #pragma unroll
@@ -780,10 +784,10 @@ __device__ __forceinline__ void split_bf16x8(const float (&v)[8], bf16x8& hi, bf
 typedef unsigned int u32x4_kv __attribute__((ext_vector_type(4)));
 template <bool KVNT>
 __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p) {
-  constexpr int RT = 16, CH = 256, DH = 64, SLD = CH + 4, VLD = DH + 4;
-  __shared__ __attribute__((aligned(16))) float sc[RT][SLD];
-  __shared__ __attribute__((aligned(16))) bf16_t vs[CH][VLD];
-  __shared__ float m_s[RT], l_s[RT], alpha_s[RT];
+  constexpr int RT = 16, CH = 256, DH = 64, WK = 64, VLD = DH + 4;
+  __shared__ __attribute__((aligned(16))) bf16_t vs[4][WK][VLD];     // per wave: its 64 V rows of the chunk
+  __shared__ f32x4 o_s[4][4][64];                                    // per wave and output tile: un-normalised out^T
+  __shared__ float m_s[4][RT], l_s[4][RT];                           // per wave: running maximum and sum per query row
   const int h = blockIdx.x, b = blockIdx.y;
   const int split = blockIdx.z % p.nsplit, tile = blockIdx.z / p.nsplit, r0 = tile * RT;
   const int first = split * CH, hop = p.nsplit * CH;
@@ -792,12 +796,12 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p) {
   const int lr = lane & 15, lq = lane >> 4;
   const bf16_t* Kb = (const bf16_t*)p.Kc + b * p.kv_seq_stride + h * DH;
   const bf16_t* Vb = (const bf16_t*)p.Vc + b * p.kv_seq_stride + h * DH;
-  // first chunk: K fragments (4 key tiles x 2 halves of the head dimension) and this thread's 8 pieces of V rows
+  // K fragments (4 key tiles x 2 halves of the head dimension) and this lane's 8 pieces of the wave's V rows
   uint4 kf[4][2], vraw[8];
 #define BPD_LOAD_KV(c0)                                                                         \
   {                                                                                             \
     _Pragma("unroll") for (int kt = 0; kt < 4; ++kt) {                                          \
-      int key = (c0) + wave * 64 + kt * 16 + lr;                                                \
+      int key = (c0) + wave * WK + kt * 16 + lr;                                                \
       key = key < p.cap ? key : p.cap - 1;                                                      \
       const bf16_t* kp = Kb + (long)key * p.d + 8 * lq;                                         \
       if (KVNT) {                                                                               \
@@ -808,9 +812,9 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p) {
       }                                                                                         \
     }                                                                                           \
     _Pragma("unroll") for (int x = 0; x < 8; ++x) {       /* 8 lanes per V row: a wave-load covers 8 whole rows */ \
-      int vkey = (c0) + (tid >> 3) + 32 * x;                                                    \
+      int vkey = (c0) + wave * WK + 8 * x + (lane >> 3);                                        \
       vkey = vkey < p.cap ? vkey : p.cap - 1;                                                   \
-      const bf16_t* vp_ = Vb + (long)vkey * p.d + 8 * (tid & 7);                                \
+      const bf16_t* vp_ = Vb + (long)vkey * p.d + 8 * (lane & 7);                               \
       if (KVNT) vraw[x] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_kv*)vp_)); \
       else vraw[x] = *(const uint4*)vp_;                                                        \
     }                                                                                           \
@@ -839,107 +843,112 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p) {
   int nkeys = p.causal ? lim + r0 + nrows : lim;
   nkeys = nkeys < p.cap ? nkeys : p.cap;
   const int nvis = lr < nrows ? (p.causal ? lim + r0 + lr + 1 : lim) : 0;     // keys row lr may see
-  if (tid < RT) { m_s[tid] = -INFINITY; l_s[tid] = 0.f; alpha_s[tid] = 1.f; }
-  f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};         // out^T: head dimensions 16*wave + 4*lq + r, row lr
-  __syncthreads();
+  float m_run = -INFINITY, l_run = 0.f;          // of query row lr over this wave's keys (the 4 lanes of a row agree)
+  f32x4 acc[4];                                  // out^T tile dt: head dimensions 16*dt + 4*lq + r, row lr
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
   for (int c0 = first; c0 < nkeys; c0 += hop) {
     if (c0 != first) BPD_LOAD_KV(c0)
-    // scores of this wave's 64 keys
+    const int k0 = c0 + wave * WK;               // first key of this wave in this chunk
+    // V rows of the wave -> LDS (rows past the last key as zeros: their probabilities are zero, their bits unknown)
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+      const int kl = 8 * x + (lane >> 3);
+      const uint4 v = k0 + kl < nkeys ? vraw[x] : make_uint4(0, 0, 0, 0);
+      *(uint2*)&vs[wave][kl][8 * (lane & 7)] = make_uint2(v.x, v.y);
+      *(uint2*)&vs[wave][kl][8 * (lane & 7) + 4] = make_uint2(v.z, v.w);
+    }
+    // scores of the wave's 64 keys: sacc[kt][r] = key k0 + 16*kt + 4*lq + r against query row lr
+    f32x4 sacc[4];
+    float mx = -INFINITY;
 #pragma unroll
     for (int kt = 0; kt < 4; ++kt) {
-      f32x4 sacc = f32x4{0.f, 0.f, 0.f, 0.f};
+      f32x4 a = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
         const bf16x8 ka = __builtin_bit_cast(bf16x8, kf[kt][s2]);
-        sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qhi[s2], sacc, 0, 0, 0);
-        sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qlo[s2], sacc, 0, 0, 0);
+        a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qhi[s2], a, 0, 0, 0);
+        a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qlo[s2], a, 0, 0, 0);
       }
-      const int kl = wave * 64 + kt * 16 + 4 * lq;           // chunk-local index of the first of 4 keys
-      float4 o;
-      o.x = c0 + kl + 0 < nvis ? sacc[0] : -INFINITY;
-      o.y = c0 + kl + 1 < nvis ? sacc[1] : -INFINITY;
-      o.z = c0 + kl + 2 < nvis ? sacc[2] : -INFINITY;
-      o.w = c0 + kl + 3 < nvis ? sacc[3] : -INFINITY;
-      *(float4*)&sc[lr][kl] = o;
-    }
-    {
+      const int kb = k0 + kt * 16 + 4 * lq;
 #pragma unroll
-      for (int x = 0; x < 8; ++x) {
-        const int kl = (tid >> 3) + 32 * x;                   // chunk-local key of this piece
-        const uint4 v = c0 + kl < nkeys ? vraw[x] : make_uint4(0, 0, 0, 0);
-        *(uint2*)&vs[kl][8 * (tid & 7)] = make_uint2(v.x, v.y);
-        *(uint2*)&vs[kl][8 * (tid & 7) + 4] = make_uint2(v.z, v.w);
+      for (int r = 0; r < 4; ++r) {
+        a[r] = kb + r < nvis ? a[r] : -INFINITY;
+        mx = fmaxf(mx, a[r]);
       }
+      sacc[kt] = a;
     }
-    __syncthreads();
-    // running max / sum: 16 lanes per row, 4 rows per wave at once
-    {
-      const int i = wave * 4 + (lane >> 4), j0 = lane & 15;
-      if (i < nrows) {
-        float v[16], mx = -INFINITY;
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = (m_new == -INFINITY) ? 1.f : __expf(m_run - m_new);
+    float sum = 0.f;
 #pragma unroll
-        for (int x = 0; x < 16; ++x) { v[x] = sc[i][j0 + 16 * x]; mx = fmaxf(mx, v[x]); }
+    for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-        for (int o = 8; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-        const float m_old = m_s[i];
-        const float m_new = fmaxf(m_old, mx);
-        float sum = 0.f;
-#pragma unroll
-        for (int x = 0; x < 16; ++x) {
-          const float pv = (m_new == -INFINITY) ? 0.f : __expf(v[x] - m_new);
-          sc[i][j0 + 16 * x] = pv;
-          sum += pv;
-        }
-#pragma unroll
-        for (int o = 8; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
-        if (j0 == 0) {
-          const float a = (m_new == -INFINITY) ? 1.f : __expf(m_old - m_new);
-          alpha_s[i] = a;
-          l_s[i] = l_s[i] * a + sum;
-          m_s[i] = m_new;
-        }
-      } else {
-#pragma unroll
-        for (int x = 0; x < 16; ++x) sc[i][j0 + 16 * x] = 0.f;      // unused rows contribute nothing
+      for (int r = 0; r < 4; ++r) {
+        const float pv = (m_new == -INFINITY) ? 0.f : __expf(sacc[kt][r] - m_new);
+        sacc[kt][r] = pv;
+        sum += pv;
       }
-    }
-    __syncthreads();
-    // weighted values
-    {
-      const float al = alpha_s[lr];
-      acc[0] *= al; acc[1] *= al; acc[2] *= al; acc[3] *= al;
-      const int ksteps = (min(CH, nkeys - c0) + 31) >> 5;
-      for (int ks = 0; ks < ksteps; ++ks) {
-        const int k0 = 32 * ks + 8 * lq;
+    sum += __shfl_xor(sum, 16, 64);
+    sum += __shfl_xor(sum, 32, 64);
+    l_run = l_run * alpha + sum;
+    m_run = m_new;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) { acc[dt][0] *= alpha; acc[dt][1] *= alpha; acc[dt][2] *= alpha; acc[dt][3] *= alpha; }
+    // weighted values: two contractions over 32 keys each.  Position 8*lq + e of the contraction is key
+    // 32*j + 4*lq + e (e < 4) or 32*j + 16 + 4*lq + e - 4 (e >= 4): what the score tiles 2j and 2j+1 hold in this lane
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const float pvv[8] = {sacc[2 * j][0], sacc[2 * j][1], sacc[2 * j][2], sacc[2 * j][3],
+                            sacc[2 * j + 1][0], sacc[2 * j + 1][1], sacc[2 * j + 1][2], sacc[2 * j + 1][3]};
+      bf16x8 phi, plo;
+      split_bf16x8(pvv, phi, plo);
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) {
         unsigned short vv[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) vv[j] = vs[k0 + j][16 * wave + lr];
+        for (int e = 0; e < 8; ++e) vv[e] = vs[wave][32 * j + (e < 4 ? 4 * lq + e : 16 + 4 * lq + e - 4)][16 * dt + lr];
         const bf16x8 va = __builtin_bit_cast(bf16x8, make_uint4((unsigned)vv[0] | ((unsigned)vv[1] << 16), (unsigned)vv[2] | ((unsigned)vv[3] << 16),
                                                                  (unsigned)vv[4] | ((unsigned)vv[5] << 16), (unsigned)vv[6] | ((unsigned)vv[7] << 16)));
-        const float4 p0 = *(const float4*)&sc[lr][k0], p1 = *(const float4*)&sc[lr][k0 + 4];
-        const float pvv[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-        bf16x8 phi, plo;
-        split_bf16x8(pvv, phi, plo);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, phi, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, plo, acc, 0, 0, 0);
+        acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, phi, acc[dt], 0, 0, 0);
+        acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, plo, acc[dt], 0, 0, 0);
       }
     }
-    __syncthreads();
   }
 #undef BPD_LOAD_KV
+  // the four waves meet: wave w finishes head dimensions 16w .. 16w+15
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) o_s[wave][dt][lane] = acc[dt];
+  if (lq == 0) { m_s[wave][lr] = m_run; l_s[wave][lr] = l_run; }
+  __syncthreads();
+  float M = -INFINITY;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) M = fmaxf(M, m_s[w][lr]);
+  float L = 0.f;
+  f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const float mw = m_s[w][lr];
+    const float wgt = (mw == -INFINITY) ? 0.f : __expf(mw - M);
+    L = fmaf(l_s[w][lr], wgt, L);
+    const f32x4 ow = o_s[w][wave][lane];
+    o[0] = fmaf(ow[0], wgt, o[0]); o[1] = fmaf(ow[1], wgt, o[1]); o[2] = fmaf(ow[2], wgt, o[2]); o[3] = fmaf(ow[3], wgt, o[3]);
+  }
   const int dim = 16 * wave + 4 * lq;
   if (p.nsplit == 1) {
     if (lr < nrows) {
-      const float inv = 1.0f / l_s[lr];
-      bf16_t* o = (bf16_t*)p.out + ((long)b * p.R + r0 + lr) * p.d + h * DH + dim;
-      *(uint2*)o = make_uint2((unsigned)f2bf(acc[0] * inv) | ((unsigned)f2bf(acc[1] * inv) << 16),
-                              (unsigned)f2bf(acc[2] * inv) | ((unsigned)f2bf(acc[3] * inv) << 16));
+      const float inv = 1.0f / L;
+      bf16_t* op = (bf16_t*)p.out + ((long)b * p.R + r0 + lr) * p.d + h * DH + dim;
+      *(uint2*)op = make_uint2((unsigned)f2bf(o[0] * inv) | ((unsigned)f2bf(o[1] * inv) << 16),
+                               (unsigned)f2bf(o[2] * inv) | ((unsigned)f2bf(o[3] * inv) << 16));
     }
   } else {
     const int tiles = gridDim.z / p.nsplit;
     float* part = p.part + ((((long)b * gridDim.x + h) * tiles + tile) * p.nsplit + split) * (RT * (DH + 2));
-    *(float4*)(part + lr * DH + dim) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-    if (tid < RT) { part[RT * DH + tid] = m_s[tid]; part[RT * DH + RT + tid] = l_s[tid]; }
+    *(float4*)(part + lr * DH + dim) = make_float4(o[0], o[1], o[2], o[3]);
+    if (tid < RT) { part[RT * DH + tid] = M; part[RT * DH + RT + tid] = L; }
   }
 }
 
