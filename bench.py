@@ -153,7 +153,7 @@ def other_configs(torch, binding):
     return res
 
 
-def cpu_baseline(cfg, weights, src, n, sched_col, tokens_target=40):
+def cpu_baseline(cfg, weights, src, n, sched_col, tokens_target=128):
     """The oracle as it stands, on the host cores: blockwise decoding of the first
     `tokens_target` tokens of the batch-1 sentence under the same imposed schedule."""
     from oracle import CombinedModel, blockwise_decode, scorers
