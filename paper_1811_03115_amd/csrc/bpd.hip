@@ -156,6 +156,7 @@ struct bpd_ctx {
   int64_t steps = 0;
   int distance_eps = 0, min_block = 1, top_n = 1, two_phase = 0;
   int num_cus = 256;                   // compute units of the device the context was created on
+  int x_ready_k = 0;                   // > 0: the last step's accept kernel already embedded the next block of that many rows
   bool weights_exceed_llc = false;     // decoder-side weights read per step > 192 MB (the Infinity Cache holds 256 MB)
   const int* cur_imposed = nullptr; int cur_imposed_stride = 0, cur_imposed_step = 0;   // of the step being run
   int* pinned = nullptr;       // small pinned host scratch
@@ -725,7 +726,10 @@ int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
   bool xs = false;      // L.stats_big describes the current L.x
   {
     PhaseTimer t(ctx, BPD_PHASE_LAYERS);
-    embed(ctx, L.P, c.k_max, L.L, R, M, L.pos_tgt, L.x, zero_input, L.keys, (int)nk);
+    // (the previous step's accept kernel may already have embedded this block and cleared the keys)
+    const bool have_x = sp && !zero_input && R == k && ctx->x_ready_k == k;
+    ctx->x_ready_k = 0;
+    if (!have_x) embed(ctx, L.P, c.k_max, L.L, R, M, L.pos_tgt, L.x, zero_input, L.keys, (int)nk);
     for (int l = 0; l < c.n_dec_layers; ++l) {
       DecL& w = L.dec[l];
       char* Kl = (char*)L.selfK + (size_t)l * c.max_batch * slots * d * as;
@@ -994,7 +998,7 @@ int bpd_encode(bpd_ctx* ctx, const int32_t* src_ids, const int32_t* src_len, con
       if (max_len[b] < 1 || max_len[b] > c.max_out_len) return fail(ctx, BPD_E_ARG, "bpd_encode: max_len out of range");
   }
   Layout& L = ctx->lay;
-  ctx->B = B; ctx->S = S; ctx->encoded = false;
+  ctx->B = B; ctx->S = S; ctx->encoded = false; ctx->x_ready_k = 0;
   HIPCHK(hipMemcpyAsync(L.src_ids, src_ids, (size_t)B * S * 4, hipMemcpyDefault, ctx->stream));
   HIPCHK(hipMemcpyAsync(L.src_len, src_len, (size_t)B * 4, hipMemcpyDefault, ctx->stream));
   if (max_len) HIPCHK(hipMemcpyAsync(L.max_len, max_len, (size_t)B * 4, hipMemcpyDefault, ctx->stream));
@@ -1032,7 +1036,16 @@ static int step_impl(bpd_ctx* ctx, int k, const int* imposed_dev, int imposed_st
     PhaseTimer t(ctx, BPD_PHASE_ACCEPT);
     StateP s = state_params(ctx);
     s.imposed = imposed_dev; s.imposed_stride = imposed_stride;
-    hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(64), 0, ctx->stream, s, L.keys, k, ctx->B, 1, imposed_step, accepted_dev);
+    const bpd_config& c = ctx->cfg;
+    if (stats_path(ctx, ctx->B * k) && c.d_model <= 1024) {
+      // one block of at most 16 rows: the accept kernel also embeds the next block (same k assumed; checked by forward)
+      hipLaunchKernelGGL(accept_embed_kernel, dim3(ctx->B), dim3(1024), 0, ctx->stream, s, L.keys, k, ctx->B, imposed_step, accepted_dev,
+                         c.d_model, (const bf16_t*)L.emb, c.vocab, (const float*)L.pos_tgt, sqrtf((float)c.d_model), L.x, L.stats_ln);
+      ctx->x_ready_k = k;
+    } else {
+      hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(64), 0, ctx->stream, s, L.keys, k, ctx->B, 1, imposed_step, accepted_dev);
+      ctx->x_ready_k = 0;
+    }
   }
   LAUNCHCHK();
   ctx->steps++;
@@ -1153,6 +1166,7 @@ int bpd_set_proposals(bpd_ctx* ctx, const int32_t* P) {
       if (P[i] < 0 || P[i] >= ctx->cfg.vocab) return fail(ctx, BPD_E_ARG, "bpd_set_proposals: token id out of range");
   }
   HIPCHK(hipMemcpyAsync(ctx->lay.P, P, n * 4, hipMemcpyDefault, ctx->stream));
+  ctx->x_ready_k = 0;              // a block embedded ahead of time used the old proposals
   return BPD_OK;
 }
 

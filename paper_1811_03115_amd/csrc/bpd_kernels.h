@@ -1160,6 +1160,84 @@ __global__ __launch_bounds__(64) void accept_kernel(StateP s, const unsigned lon
   }
 }
 
+// accept_kernel followed, in the same launch, by the embedding of the next block (embed_stats_kernel): for blocks of at
+// most 16 rows in all (bf16), where the step is a chain of small dependent kernels and each one saved counts.  One
+// workgroup of 16 waves per sequence: wave 0 verifies / accepts / commits, then every wave embeds four 16-column tiles of
+// the sequence's k next rows (token i = new proposal i, position = new L + i) with their partial LayerNorm statistics,
+// exactly as embed_stats_kernel would at the start of the next step, and the sequence's k*k arg-max keys are cleared
+// for the next vocabulary projection.
+__global__ __launch_bounds__(1024) void accept_embed_kernel(StateP s, unsigned long long* keys, int k, int B, int step,
+                                                            int* accepted_out, int d, const bf16_t* E, int V,
+                                                            const float* pos, float scale, float* x, float* stats) {
+  __shared__ int tok_s[16];
+  __shared__ int L_s;
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (b >= B) return;
+  if (wave == 0) {
+    for (int e = lane; e < k * k; e += 64) {
+      const int ip = e / k, i = e % k;
+      s.A[(b * s.kmax + ip) * s.kmax + i] = key_index(keys[(long)b * k * k + e]);
+    }
+    const int myP = lane < k ? s.P[b * s.kmax + lane] : -1;
+    if (s.finished[b]) {
+      if (lane == 0) { s.accepted[b] = 0; if (accepted_out) accepted_out[b] = 0; L_s = s.L[b]; }
+      if (lane < k) tok_s[lane] = myP;
+    } else {
+      const int a1 = (lane >= 1 && lane < k) ? key_index(keys[(long)b * k * k + (lane - 1) * k + 0]) : 0;
+      int khat = verified_length(s, b, k, lane, myP, a1, step);
+      bool eos = false;
+      const int j = s.j[b];
+      khat = cut_length(s, b, lane, myP, khat, eos);
+      if (lane < khat) s.out_ids[(long)b * s.max_out + j + lane] = myP;
+      const int nextP = lane < k ? key_index(keys[(long)b * k * k + (khat - 1) * k + lane]) : 0;
+      if (lane < k) { s.P[b * s.kmax + lane] = nextP; tok_s[lane] = nextP; }
+      if (lane == 0) {
+        const int fin = eos || (j + khat >= s.max_len[b]);
+        const int Ln = s.L[b] + khat;
+        s.j[b] = j + khat;
+        s.L[b] = Ln;
+        L_s = Ln;
+        s.finished[b] = fin;
+        s.accepted[b] = khat;
+        if (accepted_out) accepted_out[b] = khat;
+        atomicAdd((unsigned long long*)&s.stats[0], 1ull);
+        atomicAdd((unsigned long long*)&s.stats[1], (unsigned long long)khat);
+        if (fin) atomicAdd((unsigned long long*)&s.stats[2], 1ull);
+        atomicAdd((unsigned long long*)&s.stats[3 + khat], 1ull);
+        atomicMax((unsigned long long*)&s.stats[20], (unsigned long long)(step + 1));   // steps with a live sequence
+      }
+    }
+  }
+  __syncthreads();
+  for (int e = tid; e < k * k; e += 1024) keys[(long)b * k * k + e] = 0ull;
+  // rows b*k .. b*k + k - 1 of the next block
+  const int i = lane & 15, ic = i < k ? i : k - 1;
+  int t = tok_s[ic];
+  t = t < 0 ? 0 : (t >= V ? V - 1 : t);
+  const int position = L_s + ic;
+  const int row = b * k + ic;
+  const int ksteps = d >> 5, ntiles = d >> 4;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int tile = wave + 16 * q;
+    if (tile >= ntiles) break;                   // the same for the whole wave
+    const int c0 = tile * 16 + (lane >> 4) * 4;
+    const float4 pv = *(const float4*)(pos + (long)position * d + c0);
+    const long tl = (long)(t >> 4) * ksteps + (c0 >> 5);
+    const int ln = 16 * ((c0 & 31) >> 3) + (t & 15);
+    const uint2 raw = *(const uint2*)(E + (tl * 64 + ln) * 8 + (c0 & 7));
+    float v[4] = {pv.x, pv.y, pv.z, pv.w};
+    v[0] += scale * __uint_as_float(raw.x << 16); v[1] += scale * __uint_as_float(raw.x & 0xFFFF0000u);
+    v[2] += scale * __uint_as_float(raw.y << 16); v[3] += scale * __uint_as_float(raw.y & 0xFFFF0000u);
+    float sv = (v[0] + v[1]) + (v[2] + v[3]);
+    float qv = (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
+    sv += __shfl_xor(sv, 16, 64); sv += __shfl_xor(sv, 32, 64);
+    qv += __shfl_xor(qv, 16, 64); qv += __shfl_xor(qv, 32, 64);
+    if (lane < 16 && i < k) ((float2*)stats)[tile * 16 + row] = make_float2(sv, qv);
+    if (i < k) *(float4*)(x + (long)row * d + c0) = make_float4(v[0], v[1], v[2], v[3]);
+  }
+}
+
 // ---------------------------------------------------------------------------------------
 // Machine peaks, measured the way the step's kernels use the machine (bpd_measure_*).
 // Streaming read: every thread sums 16-byte words of a buffer, grid-stride, nothing written
