@@ -411,3 +411,32 @@ def test_lockstep_random_shapes(seed):
     for s in range(2):
         ls.step(imposed=None)
     print(cfg.name, "max logit err", ls.max_logit_err, "bit-identical argmax fraction", np.mean(ls.match))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("which", ["S-bf16", "odd-dh16", "odd-stream9"])
+def test_accept_kernel_embedding_next_block_changes_nothing(which):
+    """With at most 16 block rows the accept kernel also embeds the next block.  Re-sending the current proposals
+    (bpd_set_proposals) makes the next step embed the block itself instead: both ways give the same state after every
+    step, under an imposed schedule, under exact matching, and when k changes between steps."""
+    cfg = {c.name: c for c in [SMALL_BF16] + ODD_SHAPES}[which]
+    weights = wl.make_weights(cfg)
+    ctx = gpu_context(cfg, weights)
+    src, n = ragged_sources(cfg, 5)
+    sched = wl.make_schedule(cfg, 2, cfg.max_out, seed=3)
+    ks = [cfg.k, cfg.k, max(1, cfg.k - 1), cfg.k, cfg.k, 1, cfg.k, cfg.k]
+
+    def run(resend):
+        ctx.bpd_encode(src, n)
+        states = []
+        for s, k in enumerate(ks):
+            if resend:
+                ctx.bpd_set_proposals(ctx.bpd_get_state()[0])
+            ctx.bpd_step(k, sched[s] if s % 2 == 0 else None)
+            states.append([np.array(v) for v in ctx.bpd_get_state()] + [np.array(v) for v in ctx.bpd_get_output()])
+        return states
+
+    ahead, separate = run(False), run(True)
+    for s, (a, b) in enumerate(zip(ahead, separate)):
+        for u, v in zip(a, b):
+            np.testing.assert_array_equal(u, v, err_msg=f"step {s}")
