@@ -586,7 +586,10 @@ void attention(bpd_ctx* ctx, const float* Q, const void* Kc, const void* Vc, voi
   p.limit = limit; p.causal = causal; p.scale = 1.0f / sqrtf((float)dh);
   // Few (head, sequence) pairs over a long cache: deal the 256-key chunks to several workgroups
   // and merge their partial softmax results in a second kernel.
-  const int tiles = (R + 15) / 16, chunks = (cap + 255) / 256, wgs = c.n_heads * B * tiles;
+  // (the committed length is on the device, but it grows by at most k_max per step: the host knows a bound on the keys)
+  long keys_max = cap;
+  if (causal && (long)ctx->steps * c.k_max + R < keys_max) keys_max = (long)ctx->steps * c.k_max + R;
+  const int tiles = (R + 15) / 16, chunks = (int)((keys_max + 255) / 256), wgs = c.n_heads * B * tiles;
   int nsplit = 1;
   if (chunks >= 3 && wgs * 2 <= ATTN_PART_SLOTS) {
     nsplit = ATTN_PART_SLOTS / wgs;
