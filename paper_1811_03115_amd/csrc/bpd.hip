@@ -363,7 +363,7 @@ constexpr int LDSX_LN_MT_MAX = 3;      // LayerNorm-fused consumers and statisti
 constexpr int LDSX_LN_M_MAX = 128;     // and blocks of at most 128 rows
 constexpr long LDSX_MIN_WGS = 448;
 constexpr long LDSX_MIN_WGS_LONGK = 320;   // K >= 2048: a workgroup lives long enough that 1.25 per CU suffice
-void pick_tile(int M, int N, int K, long zdim, bool argmax, int& mt, int& nt, int mt_max = 8) {
+void pick_tile(int M, int N, int K, long zdim, int& mt, int& nt, int mt_max = 8) {
   const int mts[7] = {8, 7, 5, 4, 3, 2, 1};
   long best_area = 0, best_pad = 0;
   mt = 1; nt = (K % 256 == 0) ? 1 : 4;
@@ -389,7 +389,7 @@ bool dispatch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float
   int mt, nt;
   const int kslice = p.ksplit > 1 ? p.K / p.ksplit : p.K;
   const bool stats = !ARGMAX && e.mode == 0 && e.stats_out != nullptr && groups == 1 && p.ksplit <= 1;
-  pick_tile(p.M, p.N, kslice, groups, ARGMAX, mt, nt, stats ? LDSX_LN_MT_MAX : 8);       // groups = K slices for a split-K launch
+  pick_tile(p.M, p.N, kslice, groups, mt, nt, stats ? LDSX_LN_MT_MAX : 8);       // groups = K slices for a split-K launch
   if constexpr (!ARGMAX) {
     if (stats) {
 #define BPD_CASE(MT_, NT_, KC_) if (mt == MT_ && nt == NT_) { launch_ldsx<MT_, NT_, KC_, false, false, true>(p, e, keys, logits, groups, s); return true; }
@@ -411,7 +411,7 @@ bool dispatch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float
 // (tiles of at most 48 rows: the staging registers).
 void dispatch_ldsx_ln(const GemmP& p, const Epi& e, const LnP& ln, hipStream_t s) {
   int mt, nt;
-  pick_tile(p.M, p.N, p.K, 1, false, mt, nt, LDSX_LN_MT_MAX);
+  pick_tile(p.M, p.N, p.K, 1, mt, nt, LDSX_LN_MT_MAX);
 #define BPD_CASE(MT_, NT_, KC_) if (mt == MT_ && nt == NT_) { launch_ldsx<MT_, NT_, KC_, false, true>(p, e, nullptr, nullptr, 1, s, ln); return; }
   BPD_CASE(3, 1, 256) BPD_CASE(2, 1, 256) BPD_CASE(1, 1, 256)
   BPD_CASE(3, 2, 128) BPD_CASE(2, 2, 128) BPD_CASE(1, 2, 128)
@@ -448,11 +448,11 @@ bool gemm(bpd_ctx* ctx, const GemmP& p, const Epi& e_in, int groups = 1) {
       // fewest slices with which a tile of at least 48 rows still fills the chip; if no slicing gets
       // there, the most slices allowed (each at least 256 deep)
       int mt, nt, ns = 1;
-      pick_tile(p.M, p.N, p.K, 1, false, mt, nt);
+      pick_tile(p.M, p.N, p.K, 1, mt, nt);
       if (nt == 1 && mt < 3) {
         for (int t = 2; t <= KSPLIT_MAX && p.K % (t * 256) == 0 && (size_t)t * p.M * p.N <= ctx->lay.n_kpart; t *= 2) {
           ns = t;
-          pick_tile(p.M, p.N, p.K / t, t, false, mt, nt);
+          pick_tile(p.M, p.N, p.K / t, t, mt, nt);
           if (nt > 1 || mt >= 3) break;
         }
       }

@@ -320,6 +320,7 @@ __global__ void gemm_f32_kernel(GemmP p, Epi e) {
 __global__ __launch_bounds__(256) void vocab_argmax_f32_kernel(const float* O, int ldo, const float* E, int M, int V,
                                                                int d, unsigned long long* keys, float* logits) {
   const int m = blockIdx.x;
+  if (m >= M) return;
   const float* o = O + (long)m * ldo;
   unsigned long long best = 0ull;
   for (int v = threadIdx.x; v < V; v += blockDim.x) {
