@@ -17,6 +17,9 @@
  * never throws or aborts; bpd_last_error() gives a message.  On an argument error the decode
  * state is left unchanged.
  *
+ * Calls on one context must not overlap (one thread at a time, or external locking), and all
+ * contexts of a process must live on one device: kernel attributes are set once per process.
+ *
  * Pointer arguments marked [host|device] may be either (they are copied with
  * hipMemcpyDefault); arguments marked [device] are dereferenced by kernels.
  */
