@@ -15,6 +15,7 @@ namespace {
 
 constexpr size_t ALIGN = 256;
 constexpr int KSPLIT_MAX = 16;          // K slices of a split-K GEMM
+constexpr int ATTN_LIMF_MIN_WGS = 256;  // attention launches of at least this many workgroups clamp their K/V loads to the length
 constexpr int ATTN_PART_SLOTS = 512;   // workgroups of one split attention launch (partial-result slots)
 
 struct Arena {
@@ -602,8 +603,16 @@ void attention(bpd_ctx* ctx, const float* Q, const void* Kc, const void* Vc, voi
     if (dh == 64) {
       // a K/V buffer beyond half the last-level cache is streamed past it
       const size_t kv_bytes = (size_t)2 * c.n_dec_layers * B * cap * c.d_model * 2;
-      if (causal && kv_bytes > ((size_t)128 << 20)) hipLaunchKernelGGL(attention_mfma_kernel<true>, grid, dim3(256), 0, ctx->stream, p);
-      else hipLaunchKernelGGL(attention_mfma_kernel<false>, grid, dim3(256), 0, ctx->stream, p);
+      // many workgroups: fetch only the rows in use (the length is read first); few: one round trip, rows past the end too
+      // (a split launch walks a long cache, where nearly all fetched rows are in use: measured slower with the extra round trip)
+      const bool limf = nsplit == 1 && wgs >= ATTN_LIMF_MIN_WGS;
+      if (causal && kv_bytes > ((size_t)128 << 20)) {
+        if (limf) hipLaunchKernelGGL((attention_mfma_kernel<true, true>), grid, dim3(256), 0, ctx->stream, p);
+        else hipLaunchKernelGGL((attention_mfma_kernel<true, false>), grid, dim3(256), 0, ctx->stream, p);
+      } else {
+        if (limf) hipLaunchKernelGGL((attention_mfma_kernel<false, true>), grid, dim3(256), 0, ctx->stream, p);
+        else hipLaunchKernelGGL((attention_mfma_kernel<false, false>), grid, dim3(256), 0, ctx->stream, p);
+      }
       if (nsplit > 1) hipLaunchKernelGGL((attention_combine_kernel<bf16_t, 64>), cgrid, dim3(256), 0, ctx->stream, p);
     } else {
       hipLaunchKernelGGL((attention_kernel<bf16_t, 16>), grid, dim3(256), 0, ctx->stream, p);

@@ -783,7 +783,9 @@ __device__ __forceinline__ void split_bf16x8(const float (&v)[8], bf16x8& hi, bf
 // KVNT: K and V are fetched with non-temporal loads (a cache too large for the last-level cache is a
 // stream that should not evict the weights).
 typedef unsigned int u32x4_kv __attribute__((ext_vector_type(4)));
-template <bool KVNT>
+// LIMF: the sequence's length is fetched first and the K/V loads are clamped to it instead of to the buffer's rows: one
+// more dependent round trip, but rows past the end are not fetched (many sequences: the traffic is what counts).
+template <bool KVNT, bool LIMF>
 __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p) {
   constexpr int RT = 16, CH = 256, DH = 64, WK = 64, VLD = DH + 4;
   __shared__ __attribute__((aligned(16))) bf16_t vs[4][WK][VLD];     // per wave: its 64 V rows of the chunk
@@ -797,13 +799,20 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p) {
   const int lr = lane & 15, lq = lane >> 4;
   const bf16_t* Kb = (const bf16_t*)p.Kc + b * p.kv_seq_stride + h * DH;
   const bf16_t* Vb = (const bf16_t*)p.Vc + b * p.kv_seq_stride + h * DH;
+  int kmax = p.cap;                              // rows that may be fetched
+  if (LIMF) {
+    int l0 = p.limit[b];
+    l0 = l0 < 0 ? 0 : l0;
+    const int nk0 = p.causal ? l0 + r0 + nrows : l0;
+    kmax = nk0 < p.cap ? (nk0 > 0 ? nk0 : 1) : p.cap;
+  }
   // K fragments (4 key tiles x 2 halves of the head dimension) and this lane's 8 pieces of the wave's V rows
   uint4 kf[4][2], vraw[8];
 #define BPD_LOAD_KV(c0)                                                                         \
   {                                                                                             \
     _Pragma("unroll") for (int kt = 0; kt < 4; ++kt) {                                          \
       int key = (c0) + wave * WK + kt * 16 + lr;                                                \
-      key = key < p.cap ? key : p.cap - 1;                                                      \
+      key = key < kmax ? key : kmax - 1;                                                        \
       const bf16_t* kp = Kb + (long)key * p.d + 8 * lq;                                         \
       if (KVNT) {                                                                               \
         kf[kt][0] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_kv*)kp));     \
@@ -814,7 +823,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p) {
     }                                                                                           \
     _Pragma("unroll") for (int x = 0; x < 8; ++x) {       /* 8 lanes per V row: a wave-load covers 8 whole rows */ \
       int vkey = (c0) + wave * WK + 8 * x + (lane >> 3);                                        \
-      vkey = vkey < p.cap ? vkey : p.cap - 1;                                                   \
+      vkey = vkey < kmax ? vkey : kmax - 1;                                                     \
       const bf16_t* vp_ = Vb + (long)vkey * p.d + 8 * (lane & 7);                               \
       if (KVNT) vraw[x] = __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_kv*)vp_)); \
       else vraw[x] = *(const uint4*)vp_;                                                        \
