@@ -362,7 +362,7 @@ void launch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* 
 // workgroups per CU.  If nothing qualifies the smallest tile spreads the work furthest.
 constexpr int LDSX_LN_MT_MAX = 3;      // LayerNorm-fused consumers and statistics-writing producers: tiles of at most 48 rows
 constexpr int LDSX_LN_M_MAX = 128;     // and blocks of at most 128 rows
-constexpr long LDSX_MIN_WGS = 448;
+constexpr long LDSX_MIN_WGS = 440;
 constexpr long LDSX_MIN_WGS_LONGK = 400;   // K >= 2048: a workgroup lives long enough that about 1.5 per CU suffice
 void pick_tile(int M, int N, int K, long zdim, int& mt, int& nt, int mt_max = 8) {
   const int mts[7] = {8, 7, 5, 4, 3, 2, 1};
