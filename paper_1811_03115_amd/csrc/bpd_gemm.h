@@ -748,7 +748,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
   int bx = blockIdx.x, by = blockIdx.y;
   {
     const int NB = gridDim.x, MB = gridDim.y, L = blockIdx.x + NB * blockIdx.y;
-    if ((NB & 7) == 0) { const int j = L >> 3; by = j % MB; bx = (L & 7) + 8 * (j / MB); }
+    if ((NB & 7) == 0) {
+      // within an XCD: groups of G column blocks, row blocks next, the G column blocks of a group fastest, so that a
+      // row block of activations is fetched once per G column blocks while their G weight blocks stay in L2
+      const int j = L >> 3, per = NB >> 3;
+      const int G = (per & 3) == 0 ? 4 : ((per & 1) == 0 ? 2 : 1);
+      const int grp = j / (MB * G), within = j - grp * (MB * G);
+      by = within / G;
+      bx = (L & 7) + 8 * (grp * G + within % G);
+    }
     else { by = L % MB; bx = L / MB; }
   }
   const int m0 = by * BM;
