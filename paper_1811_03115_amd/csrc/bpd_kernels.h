@@ -522,7 +522,14 @@ __global__ __launch_bounds__(256) void layernorm_kernel(float* x, const float* g
     if (c4 < nv) {
       const float y0 = (v[i].x - mu) * rstd * gg[i].x + bb[i].x, y1 = (v[i].y - mu) * rstd * gg[i].y + bb[i].y;
       const float y2 = (v[i].z - mu) * rstd * gg[i].z + bb[i].z, y3 = (v[i].w - mu) * rstd * gg[i].w + bb[i].w;
-      if (ya) { ACT* o = ya + (long)row * d + 4 * c4; o[0] = from_f<ACT>(y0); o[1] = from_f<ACT>(y1); o[2] = from_f<ACT>(y2); o[3] = from_f<ACT>(y3); }
+      if (ya) {
+        ACT* o = ya + (long)row * d + 4 * c4;
+        if constexpr (sizeof(ACT) == 2) {          // bf16: one 8-byte store
+          *(uint2*)o = make_uint2((unsigned)f2bf(y0) | ((unsigned)f2bf(y1) << 16), (unsigned)f2bf(y2) | ((unsigned)f2bf(y3) << 16));
+        } else {
+          o[0] = from_f<ACT>(y0); o[1] = from_f<ACT>(y1); o[2] = from_f<ACT>(y2); o[3] = from_f<ACT>(y3);
+        }
+      }
       if (yf) ((float4*)(yf + (long)row * d))[c4] = make_float4(y0, y1, y2, y3);
     }
   }
