@@ -577,6 +577,14 @@ void layernorm(bpd_ctx* ctx, float* x, LnW w, int M, void* ya, float* yf) {
 #undef BPD_LN
 }
 
+// merge of the split attention's partial results: as few partials read per thread as the split needs
+template <typename ACT, int DH>
+void launch_combine(const AttnP& p, dim3 grid, hipStream_t s) {
+  if (p.nsplit <= 4) hipLaunchKernelGGL((attention_combine_kernel<ACT, DH, 4>), grid, dim3(256), 0, s, p);
+  else if (p.nsplit <= 8) hipLaunchKernelGGL((attention_combine_kernel<ACT, DH, 8>), grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL((attention_combine_kernel<ACT, DH, 16>), grid, dim3(256), 0, s, p);
+}
+
 void attention(bpd_ctx* ctx, const float* Q, const void* Kc, const void* Vc, void* out, int cap,
                int B, int R, const int* limit, int causal) {
   const long kv_seq_stride = (long)cap * ctx->cfg.d_model;
@@ -613,14 +621,14 @@ void attention(bpd_ctx* ctx, const float* Q, const void* Kc, const void* Vc, voi
         if (limf) hipLaunchKernelGGL((attention_mfma_kernel<false, true>), grid, dim3(256), 0, ctx->stream, p);
         else hipLaunchKernelGGL((attention_mfma_kernel<false, false>), grid, dim3(256), 0, ctx->stream, p);
       }
-      if (nsplit > 1) hipLaunchKernelGGL((attention_combine_kernel<bf16_t, 64>), cgrid, dim3(256), 0, ctx->stream, p);
+      if (nsplit > 1) launch_combine<bf16_t, 64>(p, cgrid, ctx->stream);
     } else {
       hipLaunchKernelGGL((attention_kernel<bf16_t, 16>), grid, dim3(256), 0, ctx->stream, p);
-      if (nsplit > 1) hipLaunchKernelGGL((attention_combine_kernel<bf16_t, 16>), cgrid, dim3(256), 0, ctx->stream, p);
+      if (nsplit > 1) launch_combine<bf16_t, 16>(p, cgrid, ctx->stream);
     }
   } else {
     hipLaunchKernelGGL((attention_kernel<float, 16>), grid, dim3(256), 0, ctx->stream, p);
-    if (nsplit > 1) hipLaunchKernelGGL((attention_combine_kernel<float, 16>), cgrid, dim3(256), 0, ctx->stream, p);
+    if (nsplit > 1) launch_combine<float, 16>(p, cgrid, ctx->stream);
   }
 }
 

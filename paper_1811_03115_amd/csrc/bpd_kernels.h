@@ -971,33 +971,41 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p) {
 
 // Merge of the nsplit partial results of attention_kernel: with M the largest of the partial
 // maxima, output = sum_s acc_s e^(m_s - M) / sum_s l_s e^(m_s - M).  Grid (heads, B, row tiles).
-template <typename ACT, int DH>
+template <typename ACT, int DH, int NS>
 __global__ __launch_bounds__(256) void attention_combine_kernel(AttnP p) {
-  constexpr int RT = 16, PS = RT * (DH + 2), NS = 16;
+  constexpr int RT = 16, PS = RT * (DH + 2), Q4 = DH / 4;       // NS >= p.nsplit: partial results read per thread
   const int h = blockIdx.x, b = blockIdx.y, tile = blockIdx.z, r0 = tile * RT;
   const int nrows = min(RT, p.R - r0);
   const float* part = p.part + (((long)b * gridDim.x + h) * gridDim.z + tile) * p.nsplit * PS;
-  for (int idx = threadIdx.x; idx < nrows * DH; idx += 256) {
-    const int i = idx / DH, cc = idx % DH;
-    float m[NS], l[NS], a[NS];
+  // one thread per (row, four head dimensions)
+  const int i = threadIdx.x / Q4, c4 = threadIdx.x % Q4;
+  if (i >= nrows) return;
+  float m[NS], l[NS];
+  float4 a[NS];
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      const int ss = s < p.nsplit ? s : 0;                 // unconditional loads, unused ones masked below
-      m[s] = part[ss * PS + RT * DH + i];
-      l[s] = part[ss * PS + RT * DH + RT + i];
-      a[s] = part[ss * PS + idx];
-    }
-    float mx = -INFINITY;
+  for (int s = 0; s < NS; ++s) {
+    const int ss = s < p.nsplit ? s : 0;                 // unconditional loads, unused ones masked below
+    m[s] = part[ss * PS + RT * DH + i];
+    l[s] = part[ss * PS + RT * DH + RT + i];
+    a[s] = *(const float4*)(part + ss * PS + i * DH + 4 * c4);
+  }
+  float mx = -INFINITY;
 #pragma unroll
-    for (int s = 0; s < NS; ++s) mx = fmaxf(mx, s < p.nsplit ? m[s] : -INFINITY);
-    float num = 0.f, den = 0.f;
+  for (int s = 0; s < NS; ++s) mx = fmaxf(mx, s < p.nsplit ? m[s] : -INFINITY);
+  float den = 0.f;
+  float4 num = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      const float w = (s < p.nsplit && m[s] != -INFINITY) ? __expf(m[s] - mx) : 0.f;
-      num = fmaf(a[s], w, num);
-      den = fmaf(l[s], w, den);
-    }
-    ((ACT*)p.out)[((long)b * p.R + r0 + i) * p.d + h * DH + cc] = from_f<ACT>(num / den);
+  for (int s = 0; s < NS; ++s) {
+    const float w = (s < p.nsplit && m[s] != -INFINITY) ? __expf(m[s] - mx) : 0.f;
+    num.x = fmaf(a[s].x, w, num.x); num.y = fmaf(a[s].y, w, num.y); num.z = fmaf(a[s].z, w, num.z); num.w = fmaf(a[s].w, w, num.w);
+    den = fmaf(l[s], w, den);
+  }
+  ACT* o = (ACT*)p.out + ((long)b * p.R + r0 + i) * p.d + h * DH + 4 * c4;
+  if constexpr (sizeof(ACT) == 2) {
+    *(uint2*)o = make_uint2((unsigned)f2bf(num.x / den) | ((unsigned)f2bf(num.y / den) << 16),
+                            (unsigned)f2bf(num.z / den) | ((unsigned)f2bf(num.w / den) << 16));
+  } else {
+    o[0] = from_f<ACT>(num.x / den); o[1] = from_f<ACT>(num.y / den); o[2] = from_f<ACT>(num.z / den); o[3] = from_f<ACT>(num.w / den);
   }
 }
 
