@@ -585,8 +585,17 @@ void launch_combine(const AttnP& p, dim3 grid, hipStream_t s) {
   else hipLaunchKernelGGL((attention_combine_kernel<ACT, DH, 16>), grid, dim3(256), 0, s, p);
 }
 
+// Cross-attention whose query projection runs inside the attention kernel: the single-tile statistics path, 64-wide
+// heads, d = 128 / 256 / 512 / 1024 and a source short enough for one workgroup per (head, sequence).
+bool attention_qproj_ok(const bpd_ctx* ctx, int M) {
+  const bpd_config& c = ctx->cfg;
+  const int d = c.d_model;
+  return stats_path(ctx, M) && d == 64 * c.n_heads && (d == 128 || d == 256 || d == 512 || d == 1024) &&
+         (c.max_src_len + 255) / 256 < 3;
+}
+
 void attention(bpd_ctx* ctx, const float* Q, const void* Kc, const void* Vc, void* out, int cap,
-               int B, int R, const int* limit, int causal) {
+               int B, int R, const int* limit, int causal, const QProjP* qproj = nullptr) {
   const long kv_seq_stride = (long)cap * ctx->cfg.d_model;
   const bpd_config& c = ctx->cfg;
   const int dh = c.d_model / c.n_heads;
@@ -614,12 +623,21 @@ void attention(bpd_ctx* ctx, const float* Q, const void* Kc, const void* Vc, voi
       // many workgroups: fetch only the rows in use (the length is read first); few: one round trip, rows past the end too
       // (a split launch walks a long cache, where nearly all fetched rows are in use: measured slower with the extra round trip)
       const bool limf = nsplit == 1 && wgs >= ATTN_LIMF_MIN_WGS;
+      if (qproj) {                               // queries projected in the kernel (attention_qproj_ok() holds)
+        switch (c.d_model / 128) {
+          case 1: hipLaunchKernelGGL((attention_mfma_kernel<false, false, 1>), grid, dim3(256), 0, ctx->stream, p, *qproj); break;
+          case 2: hipLaunchKernelGGL((attention_mfma_kernel<false, false, 2>), grid, dim3(256), 0, ctx->stream, p, *qproj); break;
+          case 4: hipLaunchKernelGGL((attention_mfma_kernel<false, false, 4>), grid, dim3(256), 0, ctx->stream, p, *qproj); break;
+          default: hipLaunchKernelGGL((attention_mfma_kernel<false, false, 8>), grid, dim3(256), 0, ctx->stream, p, *qproj); break;
+        }
+        return;
+      }
       if (causal && kv_bytes > ((size_t)128 << 20)) {
-        if (limf) hipLaunchKernelGGL((attention_mfma_kernel<true, true>), grid, dim3(256), 0, ctx->stream, p);
-        else hipLaunchKernelGGL((attention_mfma_kernel<true, false>), grid, dim3(256), 0, ctx->stream, p);
+        if (limf) hipLaunchKernelGGL((attention_mfma_kernel<true, true, 0>), grid, dim3(256), 0, ctx->stream, p, QProjP{});
+        else hipLaunchKernelGGL((attention_mfma_kernel<true, false, 0>), grid, dim3(256), 0, ctx->stream, p, QProjP{});
       } else {
-        if (limf) hipLaunchKernelGGL((attention_mfma_kernel<false, true>), grid, dim3(256), 0, ctx->stream, p);
-        else hipLaunchKernelGGL((attention_mfma_kernel<false, false>), grid, dim3(256), 0, ctx->stream, p);
+        if (limf) hipLaunchKernelGGL((attention_mfma_kernel<false, true, 0>), grid, dim3(256), 0, ctx->stream, p, QProjP{});
+        else hipLaunchKernelGGL((attention_mfma_kernel<false, false, 0>), grid, dim3(256), 0, ctx->stream, p, QProjP{});
       }
       if (nsplit > 1) launch_combine<bf16_t, 64>(p, cgrid, ctx->stream);
     } else {
@@ -761,8 +779,13 @@ int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
       attention(ctx, L.q, Kl, Vl, L.attn, slots, B, R, L.L, 1);
       xs = gemm(ctx, gp(L.attn, d, w.wo, d, M, d, d), residual(nullptr));
       // cross-attention sublayer over the encoder memory
-      gemm_ln(ctx, L.x, w.ln2, L.xn, nullptr, gp(L.xn, d, w.cq, d, M, d, d), plain(nullptr, 0, nullptr, 0, L.q, d, nullptr, 0), sp, xs);
-      attention(ctx, L.q, cK, cV, L.attn, c.max_src_len, B, R, L.src_len, 0);
+      if (sp && attention_qproj_ok(ctx, M)) {
+        const QProjP qp{L.x, w.ln2.g, w.ln2.b, L.stats_ln, w.cq, c.ln_eps};
+        attention(ctx, nullptr, cK, cV, L.attn, c.max_src_len, B, R, L.src_len, 0, &qp);
+      } else {
+        gemm_ln(ctx, L.x, w.ln2, L.xn, nullptr, gp(L.xn, d, w.cq, d, M, d, d), plain(nullptr, 0, nullptr, 0, L.q, d, nullptr, 0), sp, xs);
+        attention(ctx, L.q, cK, cV, L.attn, c.max_src_len, B, R, L.src_len, 0);
+      }
       xs = gemm(ctx, gp(L.attn, d, w.co, d, M, d, d), residual(nullptr));
       // feed-forward sublayer
       gemm_ln(ctx, L.x, w.ln3, L.xn, nullptr, gp(L.xn, d, w.w1, F, M, F, d), plain(w.b1, 1, nullptr, 0, nullptr, 0, L.ffh, F), sp, xs);

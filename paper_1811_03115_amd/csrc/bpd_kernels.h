@@ -787,17 +787,32 @@ __device__ __forceinline__ void split_bf16x8(const float (&v)[8], bf16x8& hi, bf
   lo = __builtin_bit_cast(bf16x8, make_uint4(l[0], l[1], l[2], l[3]));
 }
 
+__device__ __forceinline__ unsigned pack_bf16_pair(float lo, float hi) { return (unsigned)f2bf(lo) | ((unsigned)f2bf(hi) << 16); }
+
 // KVNT: K and V are fetched with non-temporal loads (a cache too large for the last-level cache is a
 // stream that should not evict the weights).
 typedef unsigned int u32x4_kv __attribute__((ext_vector_type(4)));
 // LIMF: the sequence's length is fetched first and the K/V loads are clamped to it instead of to the buffer's rows: one
 // more dependent round trip, but rows past the end are not fetched (many sequences: the traffic is what counts).
-template <bool KVNT, bool LIMF>
-__global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p) {
+// QU > 0 (one row tile, at most 16 rows in all, d = 128 * QU): the queries are projected inside the kernel,
+//   Q = LayerNorm(x) Wq[:, 64 h .. 64 h + 63]   (x: fp32 residual stream with its partial LayerNorm statistics),
+// instead of being read from p.Q: the four waves split the contraction, their partial sums meet in LDS, and the K/V
+// loads of the first chunk are already in flight meanwhile.  Saves the projection's kernel and its round trip.
+struct QProjP {
+  const float* x;       // [M][d] residual stream
+  const float* g;       // LayerNorm gain, bias
+  const float* b;
+  const float* stats;   // partial statistics of x: [(tile * 16 + row) * 2]
+  const void* W;        // packed [d/16 column tiles][d/32 k-steps][64 lanes][8]
+  float eps;
+};
+template <bool KVNT, bool LIMF, int QU>
+__global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p, QProjP qp) {
   constexpr int RT = 16, CH = 256, DH = 64, WK = 64, VLD = DH + 4;
   __shared__ __attribute__((aligned(16))) bf16_t vs[4][WK][VLD];     // per wave: its 64 V rows of the chunk
   __shared__ f32x4 o_s[4][4][64];                                    // per wave and output tile: un-normalised out^T
   __shared__ float m_s[4][RT], l_s[4][RT];                           // per wave: running maximum and sum per query row
+  __shared__ __attribute__((aligned(16))) float q_s[QU > 0 ? RT * (DH + 4) : 4];   // projected queries
   const int h = blockIdx.x, b = blockIdx.y;
   const int split = blockIdx.z % p.nsplit, tile = blockIdx.z / p.nsplit, r0 = tile * RT;
   const int first = split * CH, hop = p.nsplit * CH;
@@ -836,10 +851,95 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p) {
       else vraw[x] = *(const uint4*)vp_;                                                        \
     }                                                                                           \
   }
-  BPD_LOAD_KV(first)
   // queries: row lr (clamped), head dimensions 32s + 8*lq .. +8, scaled, as bf16 hi + lo
   bf16x8 qhi[2], qlo[2];
-  {
+  if constexpr (QU > 0) {
+    constexpr int K = 128 * QU, KSTEPS = K / 32, NV4 = 64 * QU, J = QU > 4 ? 2 : 1;
+    // LDS that the key loop and the final merge use later: statistics and gain / bias in vs, the waves' partial sums in o_s
+    float* st_s = (float*)&vs[0][0][0];          // [K/16][16][2]   (<= 8 KB)
+    float* gb_s = st_s + 2048;                   // gain at 0, bias at 1024   (8 KB)
+    f32x4* red = &o_s[0][0][0];                  // [wave][column tile][lane]
+    static_assert(sizeof(vs) >= 4 * 4096, "prologue operands fit the V staging area");
+    // every global load of the kernel is issued before the first wait: small operands, x, weights, then K / V
+    // (named registers: indexed arrays of these were placed in LDS by the compiler)
+    const int i0 = tid < NV4 ? tid : 0, i1 = tid + 256 < NV4 ? tid + 256 : 0;
+    const float4 gb0 = ((const float4*)(i0 < NV4 / 2 ? qp.g : qp.b))[i0 < NV4 / 2 ? i0 : i0 - NV4 / 2];
+    const float4 st0 = ((const float4*)qp.stats)[i0];
+    float4 gb1 = gb0, st1 = st0;
+    if constexpr (J > 1) {
+      gb1 = ((const float4*)(i1 < NV4 / 2 ? qp.g : qp.b))[i1 < NV4 / 2 ? i1 : i1 - NV4 / 2];
+      st1 = ((const float4*)qp.stats)[i1];
+    }
+    const int grow = b * p.R + r0 + (lr < nrows ? lr : nrows - 1);
+    float4 xv[QU][2];
+#pragma unroll
+    for (int i = 0; i < QU; ++i) {
+      const float* xp = qp.x + (long)grow * K + (wave + 4 * i) * 32 + 8 * lq;
+      xv[i][0] = *(const float4*)xp; xv[i][1] = *(const float4*)(xp + 4);
+    }
+    uint4 wf[QU][4];
+#pragma unroll
+    for (int i = 0; i < QU; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        wf[i][j] = ((const uint4*)qp.W)[((long)(4 * h + j) * KSTEPS + wave + 4 * i) * 64 + lane];
+    BPD_LOAD_KV(first)
+    __builtin_amdgcn_sched_barrier(0);
+    if (tid < NV4) {
+      *(float4*)&gb_s[tid < NV4 / 2 ? 4 * tid : 1024 + 4 * (tid - NV4 / 2)] = gb0;
+      *(float4*)&st_s[4 * tid] = st0;
+    }
+    if (J > 1 && tid + 256 < NV4) {
+      const int idx = tid + 256;
+      *(float4*)&gb_s[idx < NV4 / 2 ? 4 * idx : 1024 + 4 * (idx - NV4 / 2)] = gb1;
+      *(float4*)&st_s[4 * idx] = st1;
+    }
+    __syncthreads();
+    float sm = 0.f, sq = 0.f;                    // row statistics: this lane adds partials lq, lq + 4, ...
+#pragma unroll
+    for (int i = 0; i < 2 * QU; ++i) {
+      const float2 v = ((const float2*)st_s)[(lq + 4 * i) * 16 + grow];
+      sm += v.x; sq += v.y;
+    }
+    sm += __shfl_xor(sm, 16, 64); sm += __shfl_xor(sm, 32, 64);
+    sq += __shfl_xor(sq, 16, 64); sq += __shfl_xor(sq, 32, 64);
+    const float mu = sm / K;
+    const float rstd = 1.0f / sqrtf(fmaxf(sq / K - mu * mu, 0.f) + qp.eps);
+    f32x4 qa[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) qa[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < QU; ++i) {
+      const int col = (wave + 4 * i) * 32 + 8 * lq;
+      const float4 g0 = *(const float4*)&gb_s[col], g1 = *(const float4*)&gb_s[col + 4];
+      const float4 b0 = *(const float4*)&gb_s[1024 + col], b1 = *(const float4*)&gb_s[1024 + col + 4];
+      const uint4 yb = make_uint4(pack_bf16_pair((xv[i][0].x - mu) * rstd * g0.x + b0.x, (xv[i][0].y - mu) * rstd * g0.y + b0.y),
+                                  pack_bf16_pair((xv[i][0].z - mu) * rstd * g0.z + b0.z, (xv[i][0].w - mu) * rstd * g0.w + b0.w),
+                                  pack_bf16_pair((xv[i][1].x - mu) * rstd * g1.x + b1.x, (xv[i][1].y - mu) * rstd * g1.y + b1.y),
+                                  pack_bf16_pair((xv[i][1].z - mu) * rstd * g1.z + b1.z, (xv[i][1].w - mu) * rstd * g1.w + b1.w));
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        qa[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i][j]), __builtin_bit_cast(bf16x8, yb), qa[j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) red[(wave * 4 + j) * 64 + lane] = qa[j];
+    __syncthreads();
+    {                                            // wave w finishes column tile w: a lane holds row lr, columns 16w + 4lq ..
+      f32x4 sum = red[wave * 64 + lane];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) sum += red[(w * 4 + wave) * 64 + lane];
+      *(float4*)&q_s[lr * (DH + 4) + 16 * wave + 4 * lq] = make_float4(sum[0], sum[1], sum[2], sum[3]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      const float4 q0 = *(const float4*)&q_s[lr * (DH + 4) + 32 * s2 + 8 * lq], q1 = *(const float4*)&q_s[lr * (DH + 4) + 32 * s2 + 8 * lq + 4];
+      const float v[8] = {q0.x * p.scale, q0.y * p.scale, q0.z * p.scale, q0.w * p.scale,
+                          q1.x * p.scale, q1.y * p.scale, q1.z * p.scale, q1.w * p.scale};
+      split_bf16x8(v, qhi[s2], qlo[s2]);
+    }
+  } else {
+    BPD_LOAD_KV(first)
     const int row = r0 + (lr < nrows ? lr : nrows - 1);
     const float* qp = p.Q + ((long)b * p.R + row) * p.d + h * DH + 8 * lq;
     float4 qa[2][2];

@@ -351,6 +351,9 @@ ODD_SHAPES = [
     # row blocks with K = 512; 25 rows with K = 1024; column tiles that do not divide evenly among the workgroups
     wl.Config("odd-vocab81", 28, 1, 1, 512, 8, 1024, 16400, 9, 1, 6, 20, "bf16", 2, src_len_kind="lognormal"),
     wl.Config("odd-vocab25", 29, 1, 1, 1024, 16, 1024, 32784, 5, 1, 5, 12, "bf16", 2),
+    # cross-attention with the query projection inside the attention kernel (one row tile, 64-wide heads): two
+    # sequences share the tile, d = 256 (d = 128, 512 and 1024 are S-bf16, odd-k16 and odd-stream16)
+    wl.Config("odd-q256", 30, 1, 2, 256, 4, 512, 784, 6, 2, 9, 20, "bf16", 2, src_len_kind="lognormal"),
 ]
 
 
