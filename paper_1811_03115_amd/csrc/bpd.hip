@@ -585,13 +585,32 @@ void launch_combine(const AttnP& p, dim3 grid, hipStream_t s) {
   else hipLaunchKernelGGL((attention_combine_kernel<ACT, DH, 16>), grid, dim3(256), 0, s, p);
 }
 
-// Cross-attention whose query projection runs inside the attention kernel: the single-tile statistics path, 64-wide
-// heads, d = 128 / 256 / 512 / 1024 and a source short enough for one workgroup per (head, sequence).
-bool attention_qproj_ok(const bpd_ctx* ctx, int M) {
+// Workgroups per (head, sequence, row tile) of an attention launch: few such pairs over a long cache deal the 256-key
+// chunks to several workgroups whose partial softmax results a second kernel merges.
+// (the committed length is on the device, but it grows by at most k_max per step: the host knows a bound on the keys)
+int attention_nsplit(const bpd_ctx* ctx, int cap, int B, int R, int causal) {
+  const bpd_config& c = ctx->cfg;
+  long keys_max = cap;
+  if (causal && (long)ctx->steps * c.k_max + R < keys_max) keys_max = (long)ctx->steps * c.k_max + R;
+  const int tiles = (R + 15) / 16, chunks = (int)((keys_max + 255) / 256), wgs = c.n_heads * B * tiles;
+  int nsplit = 1;
+  if (chunks >= 3 && wgs * 2 <= ATTN_PART_SLOTS) {
+    nsplit = ATTN_PART_SLOTS / wgs;
+    if (nsplit > chunks) nsplit = chunks;
+    if (nsplit > 16) nsplit = 16;
+  }
+  return nsplit;
+}
+
+// Cross-attention whose query projection runs inside the attention kernel: LayerNorm statistics of x at hand (the
+// caller checks), at most 16 rows per sequence, 64-wide heads, d = 128 / 256 / 512 / 1024, one workgroup per (head,
+// sequence) and few enough of them that each streaming its head's 128 d bytes of weights beats one GEMM doing it once.
+constexpr int ATTN_QPROJ_MAX_WGS = 128;
+bool attention_qproj_ok(const bpd_ctx* ctx, int B, int R) {
   const bpd_config& c = ctx->cfg;
   const int d = c.d_model;
-  return stats_path(ctx, M) && d == 64 * c.n_heads && (d == 128 || d == 256 || d == 512 || d == 1024) &&
-         (c.max_src_len + 255) / 256 < 3;
+  return c.dtype == BPD_BF16 && R <= 16 && d == 64 * c.n_heads && (d == 128 || d == 256 || d == 512 || d == 1024) &&
+         c.n_heads * B <= ATTN_QPROJ_MAX_WGS && attention_nsplit(ctx, c.max_src_len, B, R, 0) == 1;
 }
 
 void attention(bpd_ctx* ctx, const float* Q, const void* Kc, const void* Vc, void* out, int cap,
@@ -602,18 +621,8 @@ void attention(bpd_ctx* ctx, const float* Q, const void* Kc, const void* Vc, voi
   AttnP p{};
   p.Q = Q; p.Kc = Kc; p.Vc = Vc; p.out = out; p.kv_seq_stride = kv_seq_stride; p.cap = cap; p.d = c.d_model; p.R = R;
   p.limit = limit; p.causal = causal; p.scale = 1.0f / sqrtf((float)dh);
-  // Few (head, sequence) pairs over a long cache: deal the 256-key chunks to several workgroups
-  // and merge their partial softmax results in a second kernel.
-  // (the committed length is on the device, but it grows by at most k_max per step: the host knows a bound on the keys)
-  long keys_max = cap;
-  if (causal && (long)ctx->steps * c.k_max + R < keys_max) keys_max = (long)ctx->steps * c.k_max + R;
-  const int tiles = (R + 15) / 16, chunks = (int)((keys_max + 255) / 256), wgs = c.n_heads * B * tiles;
-  int nsplit = 1;
-  if (chunks >= 3 && wgs * 2 <= ATTN_PART_SLOTS) {
-    nsplit = ATTN_PART_SLOTS / wgs;
-    if (nsplit > chunks) nsplit = chunks;
-    if (nsplit > 16) nsplit = 16;
-  }
+  const int tiles = (R + 15) / 16, wgs = c.n_heads * B * tiles;
+  const int nsplit = attention_nsplit(ctx, cap, B, R, causal);
   p.nsplit = nsplit; p.part = ctx->lay.attn_part;
   dim3 grid(c.n_heads, B, tiles * nsplit), cgrid(c.n_heads, B, tiles);
   if (c.dtype == BPD_BF16) {
@@ -779,8 +788,8 @@ int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
       attention(ctx, L.q, Kl, Vl, L.attn, slots, B, R, L.L, 1);
       xs = gemm(ctx, gp(L.attn, d, w.wo, d, M, d, d), residual(nullptr));
       // cross-attention sublayer over the encoder memory
-      if (sp && attention_qproj_ok(ctx, M)) {
-        const QProjP qp{L.x, w.ln2.g, w.ln2.b, L.stats_ln, w.cq, c.ln_eps};
+      if ((sp || xs) && attention_qproj_ok(ctx, B, R)) {
+        const QProjP qp{L.x, w.ln2.g, w.ln2.b, sp ? L.stats_ln : L.stats_big, sp ? 16 : M, w.cq, c.ln_eps};
         attention(ctx, nullptr, cK, cV, L.attn, c.max_src_len, B, R, L.src_len, 0, &qp);
       } else {
         gemm_ln(ctx, L.x, w.ln2, L.xn, nullptr, gp(L.xn, d, w.cq, d, M, d, d), plain(nullptr, 0, nullptr, 0, L.q, d, nullptr, 0), sp, xs);

@@ -794,7 +794,7 @@ __device__ __forceinline__ unsigned pack_bf16_pair(float lo, float hi) { return 
 typedef unsigned int u32x4_kv __attribute__((ext_vector_type(4)));
 // LIMF: the sequence's length is fetched first and the K/V loads are clamped to it instead of to the buffer's rows: one
 // more dependent round trip, but rows past the end are not fetched (many sequences: the traffic is what counts).
-// QU > 0 (one row tile, at most 16 rows in all, d = 128 * QU): the queries are projected inside the kernel,
+// QU > 0 (at most 16 rows per sequence, d = 128 * QU): the queries are projected inside the kernel,
 //   Q = LayerNorm(x) Wq[:, 64 h .. 64 h + 63]   (x: fp32 residual stream with its partial LayerNorm statistics),
 // instead of being read from p.Q: the four waves split the contraction, their partial sums meet in LDS, and the K/V
 // loads of the first chunk are already in flight meanwhile.  Saves the projection's kernel and its round trip.
@@ -802,7 +802,8 @@ struct QProjP {
   const float* x;       // [M][d] residual stream
   const float* g;       // LayerNorm gain, bias
   const float* b;
-  const float* stats;   // partial statistics of x: [(tile * 16 + row) * 2]
+  const float* stats;   // partial statistics of x: [(tile * srows + row) * 2]
+  int srows;            // rows per tile in stats (16 on the single-tile path, M otherwise)
   const void* W;        // packed [d/16 column tiles][d/32 k-steps][64 lanes][8]
   float eps;
 };
@@ -864,13 +865,19 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p, QProjP qp)
     // (named registers: indexed arrays of these were placed in LDS by the compiler)
     const int i0 = tid < NV4 ? tid : 0, i1 = tid + 256 < NV4 ? tid + 256 : 0;
     const float4 gb0 = ((const float4*)(i0 < NV4 / 2 ? qp.g : qp.b))[i0 < NV4 / 2 ? i0 : i0 - NV4 / 2];
-    const float4 st0 = ((const float4*)qp.stats)[i0];
-    float4 gb1 = gb0, st1 = st0;
-    if constexpr (J > 1) {
-      gb1 = ((const float4*)(i1 < NV4 / 2 ? qp.g : qp.b))[i1 < NV4 / 2 ? i1 : i1 - NV4 / 2];
-      st1 = ((const float4*)qp.stats)[i1];
-    }
-    const int grow = b * p.R + r0 + (lr < nrows ? lr : nrows - 1);
+    float4 gb1 = gb0;
+    if constexpr (J > 1) gb1 = ((const float4*)(i1 < NV4 / 2 ? qp.g : qp.b))[i1 < NV4 / 2 ? i1 : i1 - NV4 / 2];
+    // statistics of this sequence's rows: element e = 16 * tile + local row
+    constexpr int NS2 = 128 * QU, JS = QU >= 2 ? QU / 2 : 1;
+    const int row_first = b * p.R + r0;
+#define BPD_ST_SRC(e) ((const float2*)qp.stats)[(e) < NS2 ? ((e) >> 4) * qp.srows + row_first + (((e) & 15) < nrows ? ((e) & 15) : nrows - 1) : 0]
+    const float2 s0 = BPD_ST_SRC(tid);
+    float2 s1 = s0, s2 = s0, s3 = s0;
+    if constexpr (JS > 1) s1 = BPD_ST_SRC(tid + 256);
+    if constexpr (JS > 2) { s2 = BPD_ST_SRC(tid + 512); s3 = BPD_ST_SRC(tid + 768); }
+#undef BPD_ST_SRC
+    const int lrc = lr < nrows ? lr : nrows - 1;
+    const int grow = row_first + lrc;
     float4 xv[QU][2];
 #pragma unroll
     for (int i = 0; i < QU; ++i) {
@@ -885,20 +892,19 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p, QProjP qp)
         wf[i][j] = ((const uint4*)qp.W)[((long)(4 * h + j) * KSTEPS + wave + 4 * i) * 64 + lane];
     BPD_LOAD_KV(first)
     __builtin_amdgcn_sched_barrier(0);
-    if (tid < NV4) {
-      *(float4*)&gb_s[tid < NV4 / 2 ? 4 * tid : 1024 + 4 * (tid - NV4 / 2)] = gb0;
-      *(float4*)&st_s[4 * tid] = st0;
-    }
+    if (tid < NV4) *(float4*)&gb_s[tid < NV4 / 2 ? 4 * tid : 1024 + 4 * (tid - NV4 / 2)] = gb0;
     if (J > 1 && tid + 256 < NV4) {
       const int idx = tid + 256;
       *(float4*)&gb_s[idx < NV4 / 2 ? 4 * idx : 1024 + 4 * (idx - NV4 / 2)] = gb1;
-      *(float4*)&st_s[4 * idx] = st1;
     }
+    if (tid < NS2) ((float2*)st_s)[tid] = s0;
+    if constexpr (JS > 1) ((float2*)st_s)[tid + 256] = s1;
+    if constexpr (JS > 2) { ((float2*)st_s)[tid + 512] = s2; ((float2*)st_s)[tid + 768] = s3; }
     __syncthreads();
     float sm = 0.f, sq = 0.f;                    // row statistics: this lane adds partials lq, lq + 4, ...
 #pragma unroll
     for (int i = 0; i < 2 * QU; ++i) {
-      const float2 v = ((const float2*)st_s)[(lq + 4 * i) * 16 + grow];
+      const float2 v = ((const float2*)st_s)[(lq + 4 * i) * 16 + lrc];
       sm += v.x; sq += v.y;
     }
     sm += __shfl_xor(sm, 16, 64); sm += __shfl_xor(sm, 32, 64);
