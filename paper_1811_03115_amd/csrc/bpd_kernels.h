@@ -1179,34 +1179,40 @@ __global__ __launch_bounds__(256) void topn_rank_kernel(const float* logits, int
 // a1 = arg-max of p_1 at block row i; returns k-hat before the cut at EOS / max_len: the longest
 // prefix whose proposals pass the test (exact match, |P - a1| <= eps, or top-n membership), at
 // least min_block, or the imposed value.
-__device__ __forceinline__ int verified_length(const StateP& s, int b, int k, int lane, int myP, int a1, int step) {
+// (_v: with the values the decision reads from memory already at hand: topn = topn_ok[b][lane - 1], imposed = the
+// step's imposed value; both ignored when the criterion / schedule is off)
+__device__ __forceinline__ int verified_length_v(const StateP& s, int k, int lane, int myP, int a1, int topn, int imposed) {
   bool ok = true;
   if (lane >= 1 && lane < k) {
     const int diff = myP > a1 ? myP - a1 : a1 - myP;
-    ok = diff <= s.distance_eps || (s.topn_ok && s.topn_ok[b * s.kmax + lane - 1]);
+    ok = diff <= s.distance_eps || (s.topn_ok && topn);
   }
   const unsigned long long lanes_k = (k >= 64) ? ~0ull : ((1ull << k) - 1ull);
   const unsigned long long bad = (~__ballot(ok)) & lanes_k;
   int khat = bad ? __ffsll((long long)bad) - 1 : k;
   if (khat < s.min_block) khat = s.min_block < k ? s.min_block : k;
-  if (s.imposed) {
-    int v = s.imposed[(long)step * s.imposed_stride + b];
-    khat = v < 1 ? 1 : (v > k ? k : v);
-  }
+  if (s.imposed) khat = imposed < 1 ? 1 : (imposed > k ? k : imposed);
   return khat;
+}
+__device__ __forceinline__ int verified_length(const StateP& s, int b, int k, int lane, int myP, int a1, int step) {
+  const int topn = (s.topn_ok && lane >= 1 && lane < k) ? s.topn_ok[b * s.kmax + lane - 1] : 0;
+  const int imposed = s.imposed ? s.imposed[(long)step * s.imposed_stride + b] : 0;
+  return verified_length_v(s, k, lane, myP, a1, topn, imposed);
 }
 
 // Accept substep, the cut: a verified block ends at (and includes) its first EOS and never exceeds
-// the room left under max_len; `eos` tells whether the block that remains ends in EOS.
-__device__ __forceinline__ int cut_length(const StateP& s, int b, int lane, int myP, int khat, bool& eos) {
+// the room left under max_len (room = max_len - j); `eos` tells whether the block that remains ends in EOS.
+__device__ __forceinline__ int cut_length_v(const StateP& s, int lane, int myP, int khat, int room, bool& eos) {
   eos = false;
   if (s.eos_id >= 0) {
     const unsigned long long eb = __ballot(lane < khat && myP == s.eos_id);
     if (eb) { khat = __ffsll((long long)eb); eos = true; }
   }
-  const int room = s.max_len[b] - s.j[b];
   if (khat > room) { khat = room; eos = false; }   // the EOS, if any, was beyond the budget
   return khat;
+}
+__device__ __forceinline__ int cut_length(const StateP& s, int b, int lane, int myP, int khat, bool& eos) {
+  return cut_length_v(s, lane, myP, khat, s.max_len[b] - s.j[b], eos);
 }
 
 // Two-phase scoring, between the phases: k-hat (verified, then cut as in the accept kernel) from
@@ -1302,29 +1308,46 @@ __global__ __launch_bounds__(1024) void accept_embed_kernel(StateP s, unsigned l
                                                             const float* pos, float scale, float* x, float* stats) {
   __shared__ int tok_s[16];
   __shared__ int L_s;
+  __shared__ int A_s[256];                       // the sequence's k x k arg-max table
   const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (b >= B) return;
   if (wave == 0) {
-    for (int e = lane; e < k * k; e += 64) {
-      const int ip = e / k, i = e % k;
-      s.A[(b * s.kmax + ip) * s.kmax + i] = key_index(keys[(long)b * k * k + e]);
+    // one round trip for all the state the decision reads (the chain of dependent loads of accept_kernel costs more
+    // than its arithmetic); the table then passes through LDS, so row k-hat needs no second trip
+    const int kk = k * k;
+    unsigned long long kv[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) kv[q] = keys[(long)b * kk + (lane + 64 * q < kk ? lane + 64 * q : 0)];
+    const int myP_raw = s.P[b * s.kmax + (lane < k ? lane : 0)];
+    const int fin0 = s.finished[b], j = s.j[b], max_len = s.max_len[b], L0 = s.L[b];
+    const int imp_raw = s.imposed ? s.imposed[(long)step * s.imposed_stride + b] : 0;
+    const int topn_raw = s.topn_ok ? s.topn_ok[b * s.kmax + ((lane >= 1 && lane < k) ? lane - 1 : 0)] : 0;
+    __builtin_amdgcn_sched_barrier(0);
+    const int myP = lane < k ? myP_raw : -1;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int e = lane + 64 * q;
+      if (e < kk) {
+        const int a = key_index(kv[q]);
+        A_s[e] = a;
+        s.A[(b * s.kmax + e / k) * s.kmax + e % k] = a;
+      }
     }
-    const int myP = lane < k ? s.P[b * s.kmax + lane] : -1;
-    if (s.finished[b]) {
-      if (lane == 0) { s.accepted[b] = 0; if (accepted_out) accepted_out[b] = 0; L_s = s.L[b]; }
+    if (fin0) {
+      if (lane == 0) { s.accepted[b] = 0; if (accepted_out) accepted_out[b] = 0; L_s = L0; }
       if (lane < k) tok_s[lane] = myP;
     } else {
-      const int a1 = (lane >= 1 && lane < k) ? key_index(keys[(long)b * k * k + (lane - 1) * k + 0]) : 0;
-      int khat = verified_length(s, b, k, lane, myP, a1, step);
+      // (a wave's LDS accesses execute in order: the table written above is read back without a barrier)
+      const int a1 = (lane >= 1 && lane < k) ? A_s[(lane - 1) * k] : 0;
+      int khat = verified_length_v(s, k, lane, myP, a1, topn_raw, imp_raw);
       bool eos = false;
-      const int j = s.j[b];
-      khat = cut_length(s, b, lane, myP, khat, eos);
+      khat = cut_length_v(s, lane, myP, khat, max_len - j, eos);
       if (lane < khat) s.out_ids[(long)b * s.max_out + j + lane] = myP;
-      const int nextP = lane < k ? key_index(keys[(long)b * k * k + (khat - 1) * k + lane]) : 0;
+      const int nextP = lane < k ? A_s[(khat > 0 ? khat - 1 : 0) * k + lane] : 0;
       if (lane < k) { s.P[b * s.kmax + lane] = nextP; tok_s[lane] = nextP; }
       if (lane == 0) {
-        const int fin = eos || (j + khat >= s.max_len[b]);
-        const int Ln = s.L[b] + khat;
+        const int fin = eos || (j + khat >= max_len);
+        const int Ln = L0 + khat;
         s.j[b] = j + khat;
         s.L[b] = Ln;
         L_s = Ln;
