@@ -162,7 +162,7 @@ def cpu_baseline(cfg, weights, src, n, sched_col, tokens_target=128):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
     except Exception:
         cores = os.cpu_count() or 1
-    model = CombinedModel(weights, cfg.n_enc, cfg.n_dec, cfg.n_heads, cfg.k, cfg.ln_eps)
+    model = CombinedModel(weights, cfg.n_enc, cfg.n_dec, cfg.n_heads, cfg.k, cfg.ln_eps, cfg.local_q, cfg.local_m)
     score, block = scorers(model, src[0, :n[0]])
     t0 = time.perf_counter()
     dec = blockwise_decode(score, cfg.k, tokens_target, -1, schedule=list(sched_col), block_score=block)

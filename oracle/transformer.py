@@ -25,7 +25,14 @@ What the paper leaves open, and the readings taken here:
     projection (logits = o @ E^T, no bias);
   * the decoder input at position 0 is the zero vector (shifted-right targets,
     no BOS id); attention projections have no bias, FFN layers do;
-  * scaled dot-product attention with 1/sqrt(d_head), softmax over visible keys.
+  * scaled dot-product attention with 1/sqrt(d_head), softmax over visible keys;
+  * the image model of Section 7.2 is named as an Image Transformer with 1D local
+    attention and no more is said.  Reading (the published layer of that name):
+    target positions are cut into consecutive query blocks of ``local_q``
+    positions; position t sees, causally, its own block and the ``local_m``
+    positions before the block:  j visible to t  iff  b(t) - local_m <= j <= t,
+    b(t) = floor(t / local_q) * local_q.  local_q = 0 means full causal attention.
+    Block lengths are not given: they are parameters here.
 
 Parity status: every function here is pinned by tests/test_oracle_model.py
 (library attention/LayerNorm/decoder-layer routines, closed forms, causality,
@@ -70,6 +77,21 @@ def multi_head_attention(xq: np.ndarray, xkv: np.ndarray, wq, wk, wv, wo,
     return out.reshape(tq, d) @ wo
 
 
+def self_attention_visibility(t1: int, local_q: int = 0, local_m: int = 0) -> np.ndarray:
+    """[t1, t1] bool: may decoder position t (row) look at position j (column)?
+
+    Full causal attention: j <= t.  1D local attention (Section 7.2, see the module
+    header): additionally j >= floor(t / local_q) * local_q - local_m."""
+    vis = np.zeros((t1, t1), dtype=bool)
+    for t in range(t1):
+        lo = 0
+        if local_q > 0:
+            lo = max(0, (t // local_q) * local_q - local_m)
+        for j in range(lo, t + 1):
+            vis[t, j] = True
+    return vis
+
+
 def feed_forward(x, w1, b1, w2, b2):
     return np.maximum(x @ w1 + b1, 0.0) @ w2 + b2
 
@@ -78,9 +100,10 @@ class CombinedModel:
     """The network of Section 6: Transformer + k residual FFN heads + shared projection."""
 
     def __init__(self, weights: Dict[str, np.ndarray], n_enc: int, n_dec: int,
-                 n_heads: int, k: int, ln_eps: float = 1e-6):
+                 n_heads: int, k: int, ln_eps: float = 1e-6, local_q: int = 0, local_m: int = 0):
         self.w = {n: np.asarray(a, dtype=np.float64) for n, a in weights.items()}
         self.n_enc, self.n_dec, self.n_heads, self.k, self.eps = n_enc, n_dec, n_heads, k, ln_eps
+        self.local_q, self.local_m = local_q, local_m
         self.d = self.w["emb"].shape[1]
         self.vocab = self.w["emb"].shape[0]
 
@@ -119,7 +142,7 @@ class CombinedModel:
         if t1 > 1:
             u[1:] = math.sqrt(self.d) * self.w["emb"][y]
         x = u + self.w["pos_tgt"][:t1]
-        causal = np.tril(np.ones((t1, t1), dtype=bool))
+        causal = self_attention_visibility(t1, self.local_q, self.local_m)
         mem_visible = np.ones((t1, memory.shape[0]), dtype=bool)
         for l in range(self.n_dec):
             a = self._ln(x, f"dec.{l}.ln1")

@@ -23,7 +23,7 @@ TOL = {"f32": 1e-4, "bf16": 2e-2}
 
 
 def oracle_model(cfg, weights):
-    return CombinedModel(weights, cfg.n_enc, cfg.n_dec, cfg.n_heads, cfg.k, cfg.ln_eps)
+    return CombinedModel(weights, cfg.n_enc, cfg.n_dec, cfg.n_heads, cfg.k, cfg.ln_eps, cfg.local_q, cfg.local_m)
 
 
 def gpu_context(cfg, weights, max_batch=None):

@@ -14,6 +14,7 @@ import torch
 import workloads
 from oracle import (CombinedModel, blockwise_decode, blockwise_decode_two_calls, feed_forward,
                     greedy_decode, layer_norm, multi_head_attention, scorers, softmax_rows)
+from oracle.transformer import self_attention_visibility
 
 torch.set_grad_enabled(False)
 
@@ -142,6 +143,77 @@ def test_encoder_and_decoder_stacks_against_torch_layers():
         y = layer(y, mem_ref, tgt_mask=causal)
     h_ref = torch.nn.functional.layer_norm(y, (d,), t64(model.w["dec.lnf.g"]), t64(model.w["dec.lnf.b"]), cfg.ln_eps)
     np.testing.assert_allclose(model.decoder_states(memory, prefix), h_ref[0].numpy(), atol=1e-10)
+
+
+# ----------------------------------------------------------------------------- 1D local attention (Section 7.2)
+
+def test_local_attention_visibility_worked_example():
+    """Query blocks of 4 positions, 2 positions of memory before the block, 7 positions: typed out by hand."""
+    want = np.array([
+        # j: 0  1  2  3  4  5  6
+        [1, 0, 0, 0, 0, 0, 0],    # t = 0: block 0..3, nothing before it
+        [1, 1, 0, 0, 0, 0, 0],
+        [1, 1, 1, 0, 0, 0, 0],
+        [1, 1, 1, 1, 0, 0, 0],
+        [0, 0, 1, 1, 1, 0, 0],    # t = 4: block 4..7 and positions 2, 3
+        [0, 0, 1, 1, 1, 1, 0],
+        [0, 0, 1, 1, 1, 1, 1],
+    ], dtype=bool)
+    np.testing.assert_array_equal(self_attention_visibility(7, 4, 2), want)
+    # no local window, or one query block that holds everything: plain causal attention
+    tril = np.tril(np.ones((7, 7), dtype=bool))
+    np.testing.assert_array_equal(self_attention_visibility(7), tril)
+    np.testing.assert_array_equal(self_attention_visibility(7, 7, 0), tril)
+    np.testing.assert_array_equal(self_attention_visibility(7, 64, 3), tril)
+    # every row sees between 1 and local_q + local_m keys, itself included, none in the future
+    for lq, lm in ((1, 0), (1, 3), (3, 5), (5, 1)):
+        vis = self_attention_visibility(23, lq, lm)
+        assert vis.diagonal().all() and not np.triu(vis, 1).any()
+        assert vis.sum(axis=1).max() == lq + lm
+        for t in range(23):
+            first = int(np.argmax(vis[t]))
+            assert vis[t, first:t + 1].all()                       # one contiguous run ending at t
+            assert first == max(0, t - t % lq - lm)
+
+
+def test_local_attention_decoder_against_torch_layers_and_receptive_field():
+    """Decoder stack with the hand-typed band mask of the example above vs torch's decoder layers;
+    then, with one layer, h_t must ignore tokens outside its window and react to those inside."""
+    cfg = tiny_cfg()
+    _, w = build(cfg, seed=21)
+    model = CombinedModel(w, cfg.n_enc, cfg.n_dec, cfg.n_heads, cfg.k, cfg.ln_eps, local_q=4, local_m=2)
+    d, h, f = cfg.d_model, cfg.n_heads, cfg.d_ff
+    src = [3, 9, 4]
+    prefix = [6, 3, 8, 7, 5, 10]
+    memory = model.encode(src)
+    t1 = len(prefix) + 1
+    blocked = torch.tensor([[0, 1, 1, 1, 1, 1, 1], [0, 0, 1, 1, 1, 1, 1], [0, 0, 0, 1, 1, 1, 1], [0, 0, 0, 0, 1, 1, 1],
+                            [1, 1, 0, 0, 0, 1, 1], [1, 1, 0, 0, 0, 0, 1], [1, 1, 0, 0, 0, 0, 0]], dtype=torch.bool)
+    u = np.zeros((t1, d)); u[1:] = math.sqrt(d) * model.w["emb"][prefix]
+    y = t64(u + model.w["pos_tgt"][:t1])[None]
+    for l in range(cfg.n_dec):
+        layer = torch.nn.TransformerDecoderLayer(d, h, f, dropout=0.0, activation="relu", layer_norm_eps=cfg.ln_eps,
+                                                 batch_first=True, norm_first=True).double()
+        _load_attn(layer.self_attn, model.w, f"dec.{l}.self")
+        _load_attn(layer.multihead_attn, model.w, f"dec.{l}.cross")
+        _load_common(layer, model.w, None, f"dec.{l}.ffn",
+                     [(layer.norm1, f"dec.{l}.ln1"), (layer.norm2, f"dec.{l}.ln2"), (layer.norm3, f"dec.{l}.ln3")])
+        y = layer(y, t64(memory)[None], tgt_mask=blocked)
+    h_ref = torch.nn.functional.layer_norm(y, (d,), t64(model.w["dec.lnf.g"]), t64(model.w["dec.lnf.b"]), cfg.ln_eps)
+    np.testing.assert_allclose(model.decoder_states(memory, prefix), h_ref[0].numpy(), atol=1e-10)
+    full = CombinedModel(w, cfg.n_enc, cfg.n_dec, cfg.n_heads, cfg.k, cfg.ln_eps)
+    assert np.abs(full.decoder_states(memory, prefix) - h_ref[0].numpy()).max() > 1e-3      # the window matters
+
+    one = CombinedModel(w, cfg.n_enc, 1, cfg.n_heads, cfg.k, cfg.ln_eps, local_q=4, local_m=2)
+    base = one.decoder_states(memory, prefix)
+    changed = list(prefix); changed[0] = 4                      # token y_1 sits at position 1
+    other = one.decoder_states(memory, changed)
+    np.testing.assert_array_equal(other[0], base[0])            # position 0 precedes it
+    assert np.abs(other[1:4] - base[1:4]).max() > 1e-6          # positions 1..3 see position 1
+    np.testing.assert_array_equal(other[4:], base[4:])          # positions 4..6 see 2..6 only
+    changed = list(prefix); changed[1] = 4                      # position 2: inside the memory of block 4..7
+    other = one.decoder_states(memory, changed)
+    assert all(np.abs(other[t] - base[t]).max() > 1e-6 for t in range(2, 7))
 
 
 def test_embedding_scale_positions_and_tied_projection_closed_form():

@@ -44,6 +44,8 @@ class Config:
     ln_eps: float = 1e-6
     src_kind: str = "zipf"      # "uniform3" (ids in [3,V)), "zipf", "uniform0" (ids in [0,V))
     src_len_kind: str = "fixed"  # "fixed" or "lognormal"
+    local_q: int = 0            # 1D local self-attention in the decoder (Section 7.2): query block length, 0 = full causal
+    local_m: int = 0            # ... and the number of positions before the query block that stay visible
 
     @property
     def d_head(self) -> int:
@@ -64,7 +66,10 @@ C3 = Config("C3-big-bf16-b32", 3, 6, 6, 1024, 16, 4096, 32768, 10, 32, 128, 128,
             src_len_kind="lognormal")
 C4 = Config("C4-superres-bf16-b8", 4, 6, 6, 512, 8, 2048, 256, 10, 8, 192, 3072, "bf16", -1,
             src_kind="uniform0")
-CONFIGS = {c.name.split("-")[0]: c for c in (C0, C1, C2, C3, C4)}
+# C4 with the decoder's self-attention as 1D local attention, the layer the paper names for its image model (Section
+# 7.2).  The paper gives no block lengths: 256 query positions + 256 of memory are this build's example.
+C4L = dataclasses.replace(C4, name="C4L-superres-local-bf16-b8", index=5, local_q=256, local_m=256)
+CONFIGS = {c.name.split("-")[0]: c for c in (C0, C1, C2, C3, C4, C4L)}
 
 
 def scaled(cfg: Config, **kw) -> Config:
