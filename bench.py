@@ -116,15 +116,18 @@ def k_sweep(ctx, cfg, src, n, max_len, torch, steps=100):
 def other_configs(torch, binding):
     """bpd_step latency of the remaining workloads (parity-test configurations, reported for context):
     C0 and C1 over a decode session, C4 at three cache lengths (accepting one token per step so
-    that the cache length stays put while timing)."""
+    that the cache length stays put while timing), and C4L (C4 with 1D local self-attention in the decoder,
+    Section 7.2) at the same lengths."""
     res = {}
-    for name in ("C0", "C1", "C4"):
+    for name in ("C0", "C1", "C4", "C4L"):
         cfg = wl.CONFIGS[name]
         ctx = binding.Context(binding.config_from_workload(cfg))
         ctx.bpd_load_weights(wl.make_weights(cfg))
+        if cfg.local_q:
+            ctx.bpd_set_local_attention(cfg.local_q, cfg.local_m)
         src, n = wl.make_sources(cfg)
         ml = wl.make_max_len(cfg, n)
-        if name != "C4":
+        if name not in ("C4", "C4L"):
             mean = {"C0": 2, "C1": 4}[name]
             sched = wl.make_schedule(cfg, mean, cfg.max_out)
             run_sessions(ctx, cfg, src, n, ml, sched, cfg.k, 10, torch)
@@ -147,7 +150,7 @@ def other_configs(torch, binding):
                     ctx.bpd_step(cfg.k, one)
                 torch.cuda.synchronize()
                 L += 23
-                res[f"C4@L{target}"] = {"ms_per_step": 1e3 * (time.perf_counter() - t0) / 20, "batch": cfg.batch, "k": cfg.k,
+                res[f"{name}@L{target}"] = {"ms_per_step": 1e3 * (time.perf_counter() - t0) / 20, "batch": cfg.batch, "k": cfg.k,
                                         "scored_positions_per_s": cfg.batch * cfg.k * 20 / (time.perf_counter() - t0)}
         ctx.close()
     return res

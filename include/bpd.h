@@ -156,6 +156,17 @@ int bpd_set_top_n(bpd_ctx* ctx, int n);
  * (other entries -1).  Default off.  Errors: BPD_E_ARG (null ctx). */
 int bpd_set_two_phase(bpd_ctx* ctx, int on);
 
+/* 1D local self-attention in the decoder (the attention layer of the image model of Section 7.2;
+ * the paper names it without giving lengths).  Target positions are cut into consecutive query
+ * blocks of query_block positions; the row at position t attends to
+ *     floor(t / query_block) * query_block - memory_len  ..  t
+ * (clipped at 0): its own block, causally, and the memory_len positions before the block.
+ * query_block = 0 (then memory_len must be 0) restores full causal attention, the default.
+ * The cache keeps every row either way, so the setting may change between steps; it applies to
+ * later bpd_encode / bpd_step / bpd_decode / bpd_debug_step_logits calls.  Encoder and
+ * cross-attention are not affected.  Errors: BPD_E_ARG (null ctx, negative lengths). */
+int bpd_set_local_attention(bpd_ctx* ctx, int query_block, int memory_len);
+
 /* Repeat bpd_step until every sequence has ended (EOS accepted or max_len reached) or
  * max_steps steps were made; synchronises.
  *   schedule [host|device] int32 [max_steps, B] imposed accepted lengths, or NULL

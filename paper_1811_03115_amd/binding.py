@@ -42,7 +42,7 @@ class bpd_stats(C.Structure):
 
 
 EXPORTS = ["bpd_workspace_bytes", "bpd_create", "bpd_destroy", "bpd_load_weights", "bpd_encode", "bpd_step",
-           "bpd_set_acceptance", "bpd_set_top_n", "bpd_set_two_phase", "bpd_decode", "bpd_get_state", "bpd_get_output", "bpd_get_stats",
+           "bpd_set_acceptance", "bpd_set_top_n", "bpd_set_two_phase", "bpd_set_local_attention", "bpd_decode", "bpd_get_state", "bpd_get_output", "bpd_get_stats",
            "bpd_set_proposals", "bpd_debug_step_logits", "bpd_profile_enable", "bpd_profile_read",
            "bpd_profile_samples", "bpd_measure_hbm_read", "bpd_measure_mfma_bf16", "bpd_last_error"]
 
@@ -68,6 +68,7 @@ def lib() -> C.CDLL:
         L.bpd_set_acceptance.argtypes = [vp, C.c_int, C.c_int]
         L.bpd_set_top_n.argtypes = [vp, C.c_int]
         L.bpd_set_two_phase.argtypes = [vp, C.c_int]
+        L.bpd_set_local_attention.argtypes = [vp, C.c_int, C.c_int]
         L.bpd_decode.argtypes = [vp, C.c_int, i32p, C.c_int, i32p, i32p, C.POINTER(bpd_stats)]
         L.bpd_get_state.argtypes = [vp, i32p, i32p, i32p, i32p]
         L.bpd_get_output.argtypes = [vp, i32p, i32p]
@@ -209,6 +210,9 @@ class Context:
 
     def bpd_set_two_phase(self, on: bool = True):
         self._check(self.L.bpd_set_two_phase(self.h, int(on)))
+
+    def bpd_set_local_attention(self, query_block: int, memory_len: int):
+        self._check(self.L.bpd_set_local_attention(self.h, int(query_block), int(memory_len)))
 
     def bpd_decode(self, k: int, schedule=None, max_steps: Optional[int] = None):
         """Returns (out_ids [B,max_out] int32 numpy, out_len [B], stats)."""

@@ -156,6 +156,7 @@ struct bpd_ctx {
   bool encoded = false;
   int64_t steps = 0;
   int distance_eps = 0, min_block = 1, top_n = 1, two_phase = 0;
+  int local_q = 0, local_m = 0;   // 1D local self-attention in the decoder (0: full causal), bpd_set_local_attention
   int num_cus = 256;                   // compute units of the device the context was created on
   int x_ready_k = 0;                   // > 0: the last step's accept kernel already embedded the next block of that many rows
   bool weights_exceed_llc = false;     // decoder-side weights read per step > 192 MB (the Infinity Cache holds 256 MB)
@@ -592,6 +593,8 @@ int attention_nsplit(const bpd_ctx* ctx, int cap, int B, int R, int causal) {
   const bpd_config& c = ctx->cfg;
   long keys_max = cap;
   if (causal && (long)ctx->steps * c.k_max + R < keys_max) keys_max = (long)ctx->steps * c.k_max + R;
+  // (local attention: the chunks start at the first row's window and end at the last row)
+  if (causal && ctx->local_q > 0 && (long)ctx->local_q + ctx->local_m + R < keys_max) keys_max = (long)ctx->local_q + ctx->local_m + R;
   const int tiles = (R + 15) / 16, chunks = (int)((keys_max + 255) / 256), wgs = c.n_heads * B * tiles;
   int nsplit = 1;
   if (chunks >= 3 && wgs * 2 <= ATTN_PART_SLOTS) {
@@ -621,6 +624,8 @@ void attention(bpd_ctx* ctx, const float* Q, const void* Kc, const void* Vc, voi
   AttnP p{};
   p.Q = Q; p.Kc = Kc; p.Vc = Vc; p.out = out; p.kv_seq_stride = kv_seq_stride; p.cap = cap; p.d = c.d_model; p.R = R;
   p.limit = limit; p.causal = causal; p.scale = 1.0f / sqrtf((float)dh);
+  const bool local = causal && ctx->local_q > 0;
+  p.local_q = local ? ctx->local_q : 0; p.local_m = local ? ctx->local_m : 0;
   const int tiles = (R + 15) / 16, wgs = c.n_heads * B * tiles;
   const int nsplit = attention_nsplit(ctx, cap, B, R, causal);
   p.nsplit = nsplit; p.part = ctx->lay.attn_part;
@@ -631,7 +636,8 @@ void attention(bpd_ctx* ctx, const float* Q, const void* Kc, const void* Vc, voi
       const size_t kv_bytes = (size_t)2 * c.n_dec_layers * B * cap * c.d_model * 2;
       // many workgroups: fetch only the rows in use (the length is read first); few: one round trip, rows past the end too
       // (a split launch walks a long cache, where nearly all fetched rows are in use: measured slower with the extra round trip)
-      const bool limf = nsplit == 1 && wgs >= ATTN_LIMF_MIN_WGS;
+      // (local attention: where the keys start depends on the length, so it is always read first)
+      const bool limf = (nsplit == 1 && wgs >= ATTN_LIMF_MIN_WGS) || local;
       if (qproj) {                               // queries projected in the kernel (attention_qproj_ok() holds)
         switch (c.d_model / 128) {
           case 1: hipLaunchKernelGGL((attention_mfma_kernel<false, false, 1>), grid, dim3(256), 0, ctx->stream, p, *qproj); break;
@@ -1143,6 +1149,14 @@ int bpd_set_top_n(bpd_ctx* ctx, int n) {
 int bpd_set_two_phase(bpd_ctx* ctx, int on) {
   if (!ctx) return BPD_E_ARG;
   ctx->two_phase = on != 0;
+  return BPD_OK;
+}
+
+int bpd_set_local_attention(bpd_ctx* ctx, int query_block, int memory_len) {
+  if (!ctx) return BPD_E_ARG;
+  if (query_block < 0 || memory_len < 0 || (query_block == 0 && memory_len != 0))
+    return fail(ctx, BPD_E_ARG, "local attention: query_block >= 0, memory_len >= 0 (and 0 when query_block is 0)");
+  ctx->local_q = query_block; ctx->local_m = memory_len;
   return BPD_OK;
 }
 

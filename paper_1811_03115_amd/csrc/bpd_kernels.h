@@ -596,9 +596,18 @@ struct AttnP {
   const int* limit;       // [B]: base (causal) or len (non-causal)
   int causal;
   float scale;
+  int local_q, local_m;   // causal only, local_q > 0: 1D local attention (Section 7.2): the row at position t sees keys
+                          // floor(t / local_q) * local_q - local_m .. t; the chunks then start at the first row's bound
   int nsplit;             // key chunks are dealt round-robin to nsplit workgroups per (head, sequence, row tile)
   float* part;            // nsplit > 1: partial results [b][h][tile][split][16*DH acc | 16 max | 16 sum]
 };
+
+// first key that the row at position t may see
+__device__ __forceinline__ int attn_first_key(const AttnP& p, int t) {
+  if (!(p.causal && p.local_q > 0)) return 0;
+  const int lo = t / p.local_q * p.local_q - p.local_m;
+  return lo > 0 ? lo : 0;
+}
 
 // With nsplit == 1 the kernel writes the attention output.  With nsplit > 1 (long caches, few
 // sequences) every workgroup leaves its running maximum, sum and un-normalised weighted values
@@ -612,7 +621,9 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnP p) {
   __shared__ float m_s[RT], l_s[RT], alpha_s[RT];
   const int h = blockIdx.x, b = blockIdx.y;
   const int split = blockIdx.z % p.nsplit, tile = blockIdx.z / p.nsplit, r0 = tile * RT;
-  const int first = split * CH, hop = p.nsplit * CH;
+  int kbeg = 0;                                  // local attention: the length decides where the keys start (read first)
+  if (p.causal && p.local_q > 0) { const int l0 = p.limit[b]; kbeg = attn_first_key(p, (l0 < 0 ? 0 : l0) + r0); }
+  const int first = kbeg + split * CH, hop = p.nsplit * CH;
   const int nrows = min(RT, p.R - r0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const ACT* Kb = (const ACT*)p.Kc + b * p.kv_seq_stride + h * DH;
@@ -678,7 +689,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttnP p) {
           s = fmaf(qv.z, kr[x + 2], s); s = fmaf(qv.w, kr[x + 3], s);
         }
         const int nvis = p.causal ? lim + r0 + i + 1 : lim;
-        sc[i][tid] = key < nvis ? s : -INFINITY;
+        sc[i][tid] = (key < nvis && key >= attn_first_key(p, lim + r0 + i)) ? s : -INFINITY;
       }
       const bool live = key < nkeys;
 #pragma unroll
@@ -816,19 +827,21 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p, QProjP qp)
   __shared__ __attribute__((aligned(16))) float q_s[QU > 0 ? RT * (DH + 4) : 4];   // projected queries
   const int h = blockIdx.x, b = blockIdx.y;
   const int split = blockIdx.z % p.nsplit, tile = blockIdx.z / p.nsplit, r0 = tile * RT;
-  const int first = split * CH, hop = p.nsplit * CH;
   const int nrows = min(RT, p.R - r0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 15, lq = lane >> 4;
   const bf16_t* Kb = (const bf16_t*)p.Kc + b * p.kv_seq_stride + h * DH;
   const bf16_t* Vb = (const bf16_t*)p.Vc + b * p.kv_seq_stride + h * DH;
   int kmax = p.cap;                              // rows that may be fetched
+  int kbeg = 0;                                  // first key of the first chunk (local attention: LIMF only)
   if (LIMF) {
     int l0 = p.limit[b];
     l0 = l0 < 0 ? 0 : l0;
     const int nk0 = p.causal ? l0 + r0 + nrows : l0;
     kmax = nk0 < p.cap ? (nk0 > 0 ? nk0 : 1) : p.cap;
+    kbeg = attn_first_key(p, l0 + r0);
   }
+  const int first = kbeg + split * CH, hop = p.nsplit * CH;
   // K fragments (4 key tiles x 2 halves of the head dimension) and this lane's 8 pieces of the wave's V rows
   uint4 kf[4][2], vraw[8];
 #define BPD_LOAD_KV(c0)                                                                         \
@@ -965,7 +978,8 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p, QProjP qp)
   lim = lim < 0 ? 0 : lim;
   int nkeys = p.causal ? lim + r0 + nrows : lim;
   nkeys = nkeys < p.cap ? nkeys : p.cap;
-  const int nvis = lr < nrows ? (p.causal ? lim + r0 + lr + 1 : lim) : 0;     // keys row lr may see
+  const int nvis = lr < nrows ? (p.causal ? lim + r0 + lr + 1 : lim) : 0;     // keys row lr may see: nlo .. nvis - 1
+  const int nlo = LIMF ? attn_first_key(p, lim + r0 + lr) : 0;
   float m_run = -INFINITY, l_run = 0.f;          // of query row lr over this wave's keys (the 4 lanes of a row agree)
   f32x4 acc[4];                                  // out^T tile dt: head dimensions 16*dt + 4*lq + r, row lr
 #pragma unroll
@@ -996,7 +1010,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p, QProjP qp)
       const int kb = k0 + kt * 16 + 4 * lq;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        a[r] = kb + r < nvis ? a[r] : -INFINITY;
+        a[r] = (kb + r < nvis && kb + r >= nlo) ? a[r] : -INFINITY;
         mx = fmaxf(mx, a[r]);
       }
       sacc[kt] = a;

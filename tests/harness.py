@@ -30,6 +30,8 @@ def gpu_context(cfg, weights, max_batch=None):
     from paper_1811_03115_amd import binding
     ctx = binding.Context(binding.config_from_workload(cfg, max_batch=max_batch))
     ctx.bpd_load_weights(weights)
+    if cfg.local_q:
+        ctx.bpd_set_local_attention(cfg.local_q, cfg.local_m)
     return ctx
 
 

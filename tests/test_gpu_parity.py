@@ -354,6 +354,12 @@ ODD_SHAPES = [
     # cross-attention with the query projection inside the attention kernel (one row tile, 64-wide heads): two
     # sequences share the tile, d = 256 (d = 128, 512 and 1024 are S-bf16, odd-k16 and odd-stream16)
     wl.Config("odd-q256", 30, 1, 2, 256, 4, 512, 784, 6, 2, 9, 20, "bf16", 2, src_len_kind="lognormal"),
+    # 1D local self-attention (query blocks + memory, Section 7.2) on the three attention kernels: matrix cores,
+    # scalar fp32, scalar bf16; the blocks of a step straddle query-block boundaries, windows start past key 0
+    wl.Config("loc-bf16", 32, 1, 2, 128, 2, 256, 528, 5, 3, 7, 40, "bf16", 2, src_len_kind="lognormal", local_q=8, local_m=5),
+    wl.Config("loc-f32", 33, 1, 2, 64, 4, 128, 272, 4, 2, 6, 36, "f32", 2, local_q=6, local_m=3),
+    wl.Config("loc-dh16", 34, 1, 1, 128, 8, 256, 528, 3, 2, 7, 30, "bf16", 2, local_q=4, local_m=9),
+    wl.Config("loc-b20", 35, 1, 1, 128, 2, 256, 528, 4, 20, 7, 30, "bf16", 2, src_len_kind="lognormal", local_q=5, local_m=0),
 ]
 
 

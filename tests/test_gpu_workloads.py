@@ -273,3 +273,49 @@ def test_long_cache_with_16_wide_heads(dtype):
         print(cfg.name, "j =", int(ctx.bpd_get_state()[2][1]), "logit err", err)
     out_ids, out_len, st = ctx.bpd_decode(cfg.k)
     assert (out_len == 900).all() and st.finished == cfg.batch
+
+
+@pytest.mark.parametrize("heads", [2, 8])
+def test_local_attention_long_cache(heads):
+    """1D local attention (Section 7.2) with a window of several 256-key chunks: the chunks start at the window of
+    the block's first row, are dealt to several workgroups per head and merged; 64-wide heads (matrix cores) and
+    16-wide heads (scalar kernel).  Checked before the window leaves key 0, after, and near the end."""
+    cfg = wl.Config(f"long-local-h{heads}", 36, 1, 2, 128, heads, 256, 272, 4, 2, 6, 900, "bf16", -1, src_kind="uniform0",
+                    local_q=300, local_m=290)
+    weights = wl.make_weights(cfg, std=0.02)
+    ctx = gpu_context(cfg, weights)
+    model = oracle_model(cfg, weights)
+    src, n = wl.make_sources(cfg)
+    ctx.bpd_encode(src, n)
+    full = np.full(cfg.batch, cfg.k, np.int32)
+    for target in (200, 302, 700, 880):
+        while int(ctx.bpd_get_state()[2][0]) + cfg.k <= target:
+            ctx.bpd_step(cfg.k, full)
+        err = check_state_against_oracle(ctx, cfg, model, src, n, 1, cfg.k)
+        print(cfg.name, "j =", int(ctx.bpd_get_state()[2][1]), "logit err", err)
+    # the window matters: the same state scored with full causal attention differs
+    lg_local = ctx.bpd_debug_step_logits(cfg.k).cpu().numpy()
+    ctx.bpd_set_local_attention(0, 0)
+    lg_full = ctx.bpd_debug_step_logits(cfg.k).cpu().numpy()
+    assert np.abs(lg_local - lg_full).max() > 1e-3
+    ctx.bpd_set_local_attention(cfg.local_q, cfg.local_m)
+    np.testing.assert_array_equal(ctx.bpd_debug_step_logits(cfg.k).cpu().numpy(), lg_local)
+    out_ids, out_len, st = ctx.bpd_decode(cfg.k)
+    assert (out_len == 900).all() and st.finished == cfg.batch
+
+
+def test_c4_local_attention_full_size():
+    """The super-resolution workload with the decoder's self-attention local (256 + 256 positions)."""
+    cfg = wl.C4L
+    weights = wl.make_weights(cfg)
+    ctx = gpu_context(cfg, weights)
+    model = oracle_model(cfg, weights)
+    src, n = wl.make_sources(cfg)
+    ctx.bpd_encode(src, n)
+    full = np.full(cfg.batch, cfg.k, np.int32)
+    for s in range(60):
+        ctx.bpd_step(cfg.k, full)
+    e1 = check_state_against_oracle(ctx, cfg, model, src, n, 3, cfg.k)        # j = 600: window 256 .. 600
+    out_ids, out_len, st = ctx.bpd_decode(cfg.k)
+    assert (out_len == 3072).all() and st.finished == cfg.batch
+    print("C4L logit err at j=600:", e1, "steps", st.steps)
