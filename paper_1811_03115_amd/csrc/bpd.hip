@@ -507,14 +507,20 @@ size_t stream_vocab_lds_bytes(const GemmP& p) {
   const int rows = p.M < 64 ? p.M : 64;
   return (size_t)8 * 64 * 8 + (size_t)rows * (p.K + 8) * 2;
 }
+// workgroups per row block: one per CU of the row block's share, fewer when that leaves a wave less than two units of
+// 16 weight loads to take turns with (K = 512: a unit is a whole column tile; 32000 columns at 64 rows: 14.5 us with
+// 100 .. 167 workgroups, 15.5 us with 250, whose 250 atomics per row also cost more)
 int stream_vocab_gx(const bpd_ctx* ctx, const GemmP& p) {
-  const int rb = (p.M + 63) / 64;
-  const int gx = ctx->num_cus / rb;
+  const int rb = (p.M + 63) / 64, per = p.K == 512 ? 12 : 8;      // column tiles per workgroup, at least
+  int gx = ctx->num_cus / rb;
+  if (gx > p.N / 16 / per) gx = p.N / 16 / per;
   return gx < 1 ? 1 : gx;
 }
 bool stream_vocab_ok(const bpd_ctx* ctx, const GemmP& p) {
+  const int rb = (p.M + 63) / 64;
   return ctx->cfg.dtype == BPD_BF16 && p.M > 16 && p.M <= 128 && (p.K == 512 || p.K == 1024) && p.N % 16 == 0 &&
-         p.ldx % 8 == 0 && p.N / 16 >= 8 * stream_vocab_gx(ctx, p) && stream_vocab_lds_bytes(p) <= (size_t)160 * 1024;
+         p.ldx % 8 == 0 && 2 * rb * stream_vocab_gx(ctx, p) >= ctx->num_cus &&       // at least half the chip streams
+         stream_vocab_lds_bytes(p) <= (size_t)160 * 1024;
 }
 template <int NT, int UPT>
 void launch_stream_vocab_cfg(const bpd_ctx* ctx, const GemmP& p, unsigned long long* keys, float* logits) {
