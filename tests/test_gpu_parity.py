@@ -399,9 +399,13 @@ def random_config(seed):
     V = 16 * int(rng.integers(2, 160))
     k = int(rng.integers(1, 17))
     B = int(rng.integers(1, 21))
-    return wl.Config(f"rnd{seed}-{dtype}-d{d}-h{heads}-F{F}-V{V}-k{k}-B{B}", 40 + seed, int(rng.integers(1, 3)), int(rng.integers(1, 3)),
-                     d, heads, F, V, k, B, int(rng.integers(1, 21)), int(rng.integers(5, 41)), dtype, 2,
-                     src_kind="uniform3", src_len_kind="lognormal")
+    cfg = wl.Config(f"rnd{seed}-{dtype}-d{d}-h{heads}-F{F}-V{V}-k{k}-B{B}", 40 + seed, int(rng.integers(1, 3)), int(rng.integers(1, 3)),
+                    d, heads, F, V, k, B, int(rng.integers(1, 21)), int(rng.integers(5, 41)), dtype, 2,
+                    src_kind="uniform3", src_len_kind="lognormal")
+    if seed % 3 == 1:     # every third shape decodes with 1D local self-attention (windows of a few positions)
+        lq, lm = int(rng.integers(1, 9)), int(rng.integers(0, 9))
+        cfg = wl.scaled(cfg, name=cfg.name + f"-loc{lq}+{lm}", local_q=lq, local_m=lm)
+    return cfg
 
 
 @pytest.mark.parametrize("seed", range(12))
