@@ -32,7 +32,9 @@ struct Arena {
 
 struct LnW { float *g, *b; };
 struct EncL { LnW ln1, ln2; void *wqkv, *wo, *w1, *w2; float *b1, *b2; };
-struct DecL { LnW ln1, ln2, ln3; void *wqkv, *wo, *cq, *co, *ckv, *w1, *w2; float *b1, *b2; };
+// (FoldW: a matrix with the LayerNorm in front of it folded in, see fold_layernorm_kernel; W == nullptr: not kept)
+struct FoldW { void* W = nullptr; float* c = nullptr; float* d = nullptr; };
+struct DecL { LnW ln1, ln2, ln3; void *wqkv, *wo, *cq, *co, *ckv, *w1, *w2; float *b1, *b2; FoldW f_qkv, f_cq, f_w1; };
 
 struct Layout {
   // weights
@@ -72,6 +74,12 @@ bool config_ok(const bpd_config& c) {
   return true;
 }
 
+// Decoder blocks of more than 128 rows run their LayerNorm-then-GEMM pairs as one GEMM on weights with the LayerNorm
+// folded in (ROWAFF in bpd_gemm.h); contexts that can see such blocks keep a folded copy of those matrices.
+bool fold_kept(const bpd_config& c) {
+  return c.dtype == BPD_BF16 && (long)c.max_batch * c.k_max > 128 && c.d_model % 64 == 0 && c.d_model <= 1024;
+}
+
 size_t build_layout(const bpd_config& c, char* base, Layout& L) {
   Arena a(base);
   const size_t d = c.d_model, F = c.d_ff, V = c.vocab, k = c.k_max, ws = act_size(c), as = act_size(c);
@@ -95,6 +103,10 @@ size_t build_layout(const bpd_config& c, char* base, Layout& L) {
     e.ln3 = ln(); e.w1 = mat(d, F); e.b1 = vec(F); e.w2 = mat(F, d); e.b2 = vec(d);
   }
   L.dec_lnf = ln();
+  if (fold_kept(c)) {
+    auto fold = [&](size_t nn) { FoldW f; f.W = mat(d, nn); f.c = vec(nn); f.d = vec(nn); return f; };
+    for (auto& e : L.dec) { e.f_qkv = fold(3 * d); e.f_cq = fold(d); e.f_w1 = fold(F); }
+  }
   L.hw1 = mat(d, k * F); L.hb1 = vec(k * F); L.hw2 = mat(k * F, d); L.hb2 = vec(k * d);
   const size_t B = c.max_batch, nd = c.n_dec_layers, S = c.max_src_len;
   L.selfK = a.take(nd * B * slots * d * as); L.selfV = a.take(nd * B * slots * d * as);
@@ -154,6 +166,7 @@ struct bpd_ctx {
   std::string err;
   int B = 0, S = 0;
   bool encoded = false;
+  bool fold_ready = false;        // the folded copies match the loaded weights
   int64_t steps = 0;
   int distance_eps = 0, min_block = 1, top_n = 1, two_phase = 0;
   int local_q = 0, local_m = 0;   // 1D local self-attention in the decoder (0: full causal), bpd_set_local_attention
@@ -341,7 +354,7 @@ bool stats_path(const bpd_ctx* ctx, int M) {
 }
 
 // ---- ldsx path: many rows ---------------------------------------------------------------
-template <int MT, int NT, int KC, bool ARGMAX, bool XLN = false, bool STATS = false>
+template <int MT, int NT, int KC, bool ARGMAX, bool XLN = false, bool STATS = false, bool ROWAFF = false>
 void launch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* logits, int groups, hipStream_t s,
                  const LnP& ln = LnP{}) {
   const int ntiles = p.N / 16;
@@ -349,10 +362,10 @@ void launch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* 
   const size_t lds = ldsx_lds_bytes<MT, NT, KC>();
   static bool attr_set = false;                 // per instantiation: allow more than 64 KiB of LDS
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)gemm_ldsx_kernel<MT, NT, KC, ARGMAX, XLN, STATS>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute((const void*)gemm_ldsx_kernel<MT, NT, KC, ARGMAX, XLN, STATS, ROWAFF>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_ldsx_kernel<MT, NT, KC, ARGMAX, XLN, STATS>), grid, dim3(256), lds, s, p, e, keys, logits, ln);
+  hipLaunchKernelGGL((gemm_ldsx_kernel<MT, NT, KC, ARGMAX, XLN, STATS, ROWAFF>), grid, dim3(256), lds, s, p, e, keys, logits, ln);
 }
 
 // Tile of the LDS-staged GEMM: 16*mt rows x 64*nt columns per workgroup, K walked in chunks of
@@ -420,8 +433,35 @@ void dispatch_ldsx_ln(const GemmP& p, const Epi& e, const LnP& ln, hipStream_t s
   BPD_CASE(3, 4, 64) BPD_CASE(2, 4, 64) BPD_CASE(1, 4, 64)
 #undef BPD_CASE
 }
+// Y = epilogue(LayerNorm(x) W) with the LayerNorm folded into the weights (e.ra_*): X is the raw bf16 copy of x.
+void dispatch_ldsx_fold(const GemmP& p, const Epi& e, hipStream_t s) {
+  int mt, nt;
+  pick_tile(p.M, p.N, p.K, 1, mt, nt, LDSX_LN_MT_MAX);
+#define BPD_CASE(MT_, NT_, KC_) if (mt == MT_ && nt == NT_) { launch_ldsx<MT_, NT_, KC_, false, false, false, true>(p, e, nullptr, nullptr, 1, s); return; }
+  BPD_CASE(3, 1, 256) BPD_CASE(2, 1, 256) BPD_CASE(1, 1, 256)
+  BPD_CASE(3, 2, 128) BPD_CASE(2, 2, 128) BPD_CASE(1, 2, 128)
+  BPD_CASE(3, 4, 64) BPD_CASE(2, 4, 64) BPD_CASE(1, 4, 64)
+#undef BPD_CASE
+}
 bool ldsx_ln_ok(const bpd_ctx* ctx, const GemmP& p) {
   return ctx->cfg.dtype == BPD_BF16 && p.M > 16 && p.K == ctx->cfg.d_model && p.K % 64 == 0 && p.K <= 1024 && p.N % 16 == 0;
+}
+
+// In-place residual update with a long K and few output tiles on the LDS-staged kernel: the number of K slices it is
+// split into (1: not split): the fewest with which a tile of at least 48 rows still fills the chip; if no slicing gets
+// there, the most slices allowed (each at least 256 deep).
+int residual_k_slices(const bpd_ctx* ctx, const GemmP& p) {
+  if (p.N != ctx->cfg.d_model || p.K < 2048 || p.K % 64 != 0) return 1;
+  int mt, nt, ns = 1;
+  pick_tile(p.M, p.N, p.K, 1, mt, nt);
+  if (nt == 1 && mt < 3) {
+    for (int t = 2; t <= KSPLIT_MAX && p.K % (t * 256) == 0 && (size_t)t * p.M * p.N <= ctx->lay.n_kpart; t *= 2) {
+      ns = t;
+      pick_tile(p.M, p.N, p.K / t, t, mt, nt);
+      if (nt > 1 || mt >= 3) break;
+    }
+  }
+  return ns;
 }
 
 // Y = epilogue(X W).  bf16 mode: M <= 16 -> skinny kernel; otherwise the LDS-staged kernel
@@ -447,17 +487,7 @@ bool gemm(bpd_ctx* ctx, const GemmP& p, const Epi& e_in, int groups = 1) {
     // slices are added, in a fixed order, by the LayerNorm kernel that reads the residual next.
     if (groups == 1 && e.mode == 0 && e.R && e.R == e.Yf && !e.Ya && !e.relu && !e.lnR_stats &&
         e.ldr == p.N && e.ldyf == p.N && p.N == ctx->cfg.d_model && p.K >= 2048) {
-      // fewest slices with which a tile of at least 48 rows still fills the chip; if no slicing gets
-      // there, the most slices allowed (each at least 256 deep)
-      int mt, nt, ns = 1;
-      pick_tile(p.M, p.N, p.K, 1, mt, nt);
-      if (nt == 1 && mt < 3) {
-        for (int t = 2; t <= KSPLIT_MAX && p.K % (t * 256) == 0 && (size_t)t * p.M * p.N <= ctx->lay.n_kpart; t *= 2) {
-          ns = t;
-          pick_tile(p.M, p.N, p.K / t, t, mt, nt);
-          if (nt > 1 || mt >= 3) break;
-        }
-      }
+      const int ns = residual_k_slices(ctx, p);
       if (ns > 1) {
         GemmP q = p;
         q.ksplit = ns; q.part = ctx->lay.kpart;
@@ -481,7 +511,17 @@ void layernorm(bpd_ctx* ctx, float* x, LnW w, int M, void* ya, float* yf);
 // Y = epilogue(LayerNorm(x) W).  Block of <= 16 rows: LayerNorm is applied inside the skinny
 // kernel from the partial statistics the producer of x left in L.stats_ln.  Otherwise a
 // LayerNorm kernel (into `xn`, and `yf` in fp32 if given) followed by the GEMM.
-void gemm_ln(bpd_ctx* ctx, float* x, LnW w, void* xn, float* yf, GemmP p, const Epi& e, bool with_stats, bool big_stats = false) {
+void gemm_ln(bpd_ctx* ctx, float* x, LnW w, void* xn, float* yf, GemmP p, const Epi& e, bool with_stats, bool big_stats = false,
+             const FoldW* fold = nullptr) {
+  // fold: the producer of x left its bf16 copy in xn and per-tile statistics in L.stats_big (more than 128 rows): one
+  // GEMM on the weights with this LayerNorm folded in
+  if (fold && fold->W && big_stats && !yf && ldsx_ln_ok(ctx, p)) {
+    p.X = xn; p.W = fold->W;
+    Epi ef = e;
+    ef.ra_stats = ctx->lay.stats_big; ef.ra_c = fold->c; ef.ra_d = fold->d; ef.ra_eps = ctx->cfg.ln_eps;
+    dispatch_ldsx_fold(p, ef, ctx->stream);
+    return;
+  }
   // with_stats: the producer of x left its partial LayerNorm statistics in L.stats_ln (decoder block of one
   // row tile only; the encoder's kernels do not write them)
   if (with_stats && stats_path(ctx, p.M) && p.K == ctx->cfg.d_model) {
@@ -491,7 +531,7 @@ void gemm_ln(bpd_ctx* ctx, float* x, LnW w, void* xn, float* yf, GemmP p, const 
     return;
   }
   // big_stats: more than 16 rows and the GEMM that produced x left per-tile statistics in L.stats_big
-  if (big_stats && !yf && ldsx_ln_ok(ctx, p)) {
+  if (big_stats && !yf && p.M <= LDSX_LN_M_MAX && ldsx_ln_ok(ctx, p)) {
     LnP ln{x, w.g, w.b, ctx->lay.stats_big, ctx->cfg.ln_eps};
     dispatch_ldsx_ln(p, e, ln, ctx->stream);
     return;
@@ -776,10 +816,14 @@ int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
   // with more rows the LDS-staged kernel leaves them per tile in L.stats_big for the LayerNorm-fused GEMM that follows
   // (up to 128 rows: with more, every column block repeating the normalisation of its rows costs more than the kernel saved)
   const bool bigs = !sp && c.dtype == BPD_BF16 && M > 16 && M <= LDSX_LN_M_MAX && d % 64 == 0 && d <= 1024;
-  auto residual = [&](const float* bias) {
+  // more than 128 rows: the GEMMs that update x also leave its bf16 copy in L.xn, and the LayerNorm + GEMM that follows
+  // runs as one GEMM on folded weights (unless that update is split over K: its slices are summed by a LayerNorm kernel)
+  const bool folds = !sp && !bigs && c.dtype == BPD_BF16 && M > LDSX_LN_M_MAX && L.dec[0].f_qkv.W != nullptr;
+  auto residual = [&](const float* bias, int K) {
     Epi e = plain(bias, 0, L.x, d, L.x, d, nullptr, 0);
     if (sp) e.stats_out = L.stats_ln;
     else if (bigs) e.stats_out = L.stats_big;
+    else if (folds && residual_k_slices(ctx, gp(nullptr, K, nullptr, d, M, d, K)) == 1) { e.stats_out = L.stats_big; e.Ya = L.xn; e.ldya = d; }
     return e;
   };
   bool xs = false;      // L.stats_big describes the current L.x
@@ -796,21 +840,21 @@ int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
       char* cK = (char*)L.crossK + (size_t)l * c.max_batch * c.max_src_len * d * as;
       char* cV = (char*)L.crossV + (size_t)l * c.max_batch * c.max_src_len * d * as;
       // self-attention sublayer: K/V of the block rows go straight into the cache at L_b + i'
-      gemm_ln(ctx, L.x, w.ln1, L.xn, nullptr, gp(L.xn, d, w.wqkv, 3 * d, M, 3 * d, d), split(L.q, Kl, Vl, d, 0, R, slots, L.L), sp, xs);
+      gemm_ln(ctx, L.x, w.ln1, L.xn, nullptr, gp(L.xn, d, w.wqkv, 3 * d, M, 3 * d, d), split(L.q, Kl, Vl, d, 0, R, slots, L.L), sp, xs, folds ? &w.f_qkv : nullptr);
       attention(ctx, L.q, Kl, Vl, L.attn, slots, B, R, L.L, 1);
-      xs = gemm(ctx, gp(L.attn, d, w.wo, d, M, d, d), residual(nullptr));
+      xs = gemm(ctx, gp(L.attn, d, w.wo, d, M, d, d), residual(nullptr, d));
       // cross-attention sublayer over the encoder memory
       if ((sp || xs) && attention_qproj_ok(ctx, B, R)) {
         const QProjP qp{L.x, w.ln2.g, w.ln2.b, sp ? L.stats_ln : L.stats_big, sp ? 16 : M, w.cq, c.ln_eps};
         attention(ctx, nullptr, cK, cV, L.attn, c.max_src_len, B, R, L.src_len, 0, &qp);
       } else {
-        gemm_ln(ctx, L.x, w.ln2, L.xn, nullptr, gp(L.xn, d, w.cq, d, M, d, d), plain(nullptr, 0, nullptr, 0, L.q, d, nullptr, 0), sp, xs);
+        gemm_ln(ctx, L.x, w.ln2, L.xn, nullptr, gp(L.xn, d, w.cq, d, M, d, d), plain(nullptr, 0, nullptr, 0, L.q, d, nullptr, 0), sp, xs, folds ? &w.f_cq : nullptr);
         attention(ctx, L.q, cK, cV, L.attn, c.max_src_len, B, R, L.src_len, 0);
       }
-      xs = gemm(ctx, gp(L.attn, d, w.co, d, M, d, d), residual(nullptr));
+      xs = gemm(ctx, gp(L.attn, d, w.co, d, M, d, d), residual(nullptr, d));
       // feed-forward sublayer
-      gemm_ln(ctx, L.x, w.ln3, L.xn, nullptr, gp(L.xn, d, w.w1, F, M, F, d), plain(w.b1, 1, nullptr, 0, nullptr, 0, L.ffh, F), sp, xs);
-      xs = gemm(ctx, gp(L.ffh, F, w.w2, d, M, d, F), residual(w.b2));
+      gemm_ln(ctx, L.x, w.ln3, L.xn, nullptr, gp(L.xn, d, w.w1, F, M, F, d), plain(w.b1, 1, nullptr, 0, nullptr, 0, L.ffh, F), sp, xs, folds ? &w.f_w1 : nullptr);
+      xs = gemm(ctx, gp(L.ffh, F, w.w2, d, M, d, F), residual(w.b2, F));
     }
   }
   { PhaseTimer t(ctx, BPD_PHASE_EMPTY); }       // calibration of the event bracketing itself
@@ -1036,6 +1080,7 @@ int bpd_load_weights(bpd_ctx* ctx, const bpd_tensor* tensors, int n) {
     LAUNCHCHK();
     HIPCHK(hipStreamSynchronize(ctx->stream));   // the staging area and the caller's buffer are free again
     e.loaded = true;
+    ctx->fold_ready = false;
   }
   ctx->encoded = false;
   return BPD_OK;
@@ -1063,6 +1108,15 @@ int bpd_encode(bpd_ctx* ctx, const int32_t* src_ids, const int32_t* src_len, con
   }
   Layout& L = ctx->lay;
   ctx->B = B; ctx->S = S; ctx->encoded = false; ctx->x_ready_k = 0;
+  if (!ctx->fold_ready && L.dec[0].f_qkv.W) {     // (every tensor is loaded: checked above)
+    const int d = c.d_model;
+    auto fold = [&](const void* W, const FoldW& f, const LnW& w, int N) {
+      hipLaunchKernelGGL(fold_layernorm_kernel, dim3(N / 16), dim3(64), 0, ctx->stream, (const bf16_t*)W, (bf16_t*)f.W, w.g, w.b, f.c, f.d, d / 32);
+    };
+    for (auto& e : L.dec) { fold(e.wqkv, e.f_qkv, e.ln1, 3 * d); fold(e.cq, e.f_cq, e.ln2, d); fold(e.w1, e.f_w1, e.ln3, c.d_ff); }
+    LAUNCHCHK();
+    ctx->fold_ready = true;
+  }
   HIPCHK(hipMemcpyAsync(L.src_ids, src_ids, (size_t)B * S * 4, hipMemcpyDefault, ctx->stream));
   HIPCHK(hipMemcpyAsync(L.src_len, src_len, (size_t)B * 4, hipMemcpyDefault, ctx->stream));
   if (max_len) HIPCHK(hipMemcpyAsync(L.max_len, max_len, (size_t)B * 4, hipMemcpyDefault, ctx->stream));

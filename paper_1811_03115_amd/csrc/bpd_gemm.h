@@ -15,18 +15,28 @@
 
 // With e.stats_out (mode 0): per 16-column tile and row the sum and the sum of squares of the stored values go to
 // stats_out[(tile * M + row) * 2 + {0, 1}], for the LayerNorm that the next GEMM applies while it stages its activations.
-template <int MT, int NT, bool STATS>
+// ROWAFF: the products are finished as rstd * (acc - mu * c[n]) + d[n] first (LayerNorm folded into the weights, see
+// Epi); ms: (mu, rstd) of the workgroup's rows, in LDS.
+template <int MT, int NT, bool STATS, bool ROWAFF = false>
 __device__ __forceinline__ void store_tiles(const Epi& e, int g, const f32x4 (&acc)[MT][NT], int m0, int nt0,
-                                            int ntiles, int M, int lane) {
+                                            int ntiles, int M, int lane, const float2* ms = nullptr,
+                                            const float4* rc = nullptr, const float4* rd = nullptr) {
   const bool stats = STATS && e.mode == 0 && e.stats_out != nullptr;
 #pragma unroll
   for (int t = 0; t < MT; ++t) {
     const int m = m0 + t * 16 + (lane & 15);
+    float2 mr = make_float2(0.f, 1.f);
+    if constexpr (ROWAFF) mr = ms[t * 16 + (lane & 15)];
 #pragma unroll
     for (int u = 0; u < NT; ++u) {
       if (nt0 + u >= ntiles) continue;            // the same for the whole wave
       const int n = (nt0 + u) * 16 + (lane >> 4) * 4;
-      const float v[4] = {acc[t][u][0], acc[t][u][1], acc[t][u][2], acc[t][u][3]};
+      float v[4] = {acc[t][u][0], acc[t][u][1], acc[t][u][2], acc[t][u][3]};
+      if constexpr (ROWAFF) {
+        const float4 cc = rc[u], dd = rd[u];     // fetched at kernel entry: no round trip here
+        v[0] = mr.y * (v[0] - mr.x * cc.x) + dd.x; v[1] = mr.y * (v[1] - mr.x * cc.y) + dd.y;
+        v[2] = mr.y * (v[2] - mr.x * cc.z) + dd.z; v[3] = mr.y * (v[3] - mr.x * cc.w) + dd.w;
+      }
       float fin[4] = {0.f, 0.f, 0.f, 0.f};
       if (m < M) epi_store4f(e, g, m, n, v, fin);
       if (stats) {
@@ -729,9 +739,15 @@ constexpr size_t ldsx_lds_bytes() { return (size_t)2 * ((16 * MT * (KC / 8) + 25
 // workgroup adds them for its rows, and every activation chunk goes global (fp32) -> registers -> normalised -> bf16 ->
 // LDS, in the layout the direct loads would have produced.  Saves the LayerNorm kernel and its round trip through memory.
 // STATS: store_tiles also writes the LayerNorm statistics of the output (e.stats_out).
-template <int MT, int NT, int KC, bool ARGMAX, bool XLN, bool STATS>
+// ROWAFF (one group, no split-K, K <= 1024, BM <= 64): LayerNorm folded into the weights; mu / rstd of the rows from the
+// producer's partial statistics (requested before everything else, reduced while the first chunk arrives), applied in
+// the epilogue.  X comes through the direct loads like any bf16 operand: no LayerNorm kernel and no normalisation here.
+template <int MT, int NT, int KC, bool ARGMAX, bool XLN, bool STATS, bool ROWAFF = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_min<MT, NT, KC>(), ldsx_waves_max<MT, NT, KC>()))) void gemm_ldsx_kernel(GemmP p, Epi e, unsigned long long* keys, float* logits, LnP ln) {
   constexpr int BM = 16 * MT, KS = KC / 32, SEG = KC / 8;
+  static_assert(!ROWAFF || (BM <= 64 && !XLN && !ARGMAX), "row statistics: one pass over at most 64 rows");
+  __shared__ float2 ra_part[ROWAFF ? 4 * 64 : 1];
+  __shared__ float2 ra_ms[ROWAFF ? 64 : 1];
   constexpr int XI = (BM * SEG + 255) / 256;       // direct-to-LDS loads per thread per chunk
   constexpr int BUF = XI * 256 * 8;                // bf16 elements per buffer (whole wave-loads)
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -919,8 +935,47 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
   static_assert(YOUNGER <= 63, "vmcnt range");
   BPD_X_TO_LDS(xs0, cbase)
   BPD_LOAD_W(a0, cbase)
-  BPD_WAIT_VM(YOUNGER);
+  float2 rpv[ROWAFF ? 16 : 1];
+  float4 ra_c4[NT], ra_d4[NT];
+  if constexpr (ROWAFF) {                        // behind the first chunk's loads, in the shadow of their round trip
+    int row = m0 + lane; row = row < p.M ? row : p.M - 1;
+    const int tiles = p.K >> 4;                  // <= 64
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int t = wave + 4 * i;
+      rpv[i] = ((const float2*)e.ra_stats)[(long)(t < tiles ? t : 0) * p.M + row];
+    }
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {               // column operands of the epilogue, for this lane's four columns per tile
+      const int tile = nt0 + u < ntiles ? nt0 + u : ntiles - 1;
+      ra_c4[u] = *(const float4*)(e.ra_c + tile * 16 + lq * 4);
+      ra_d4[u] = *(const float4*)(e.ra_d + tile * 16 + lq * 4);
+    }
+    BPD_WAIT_VM(0);
+  } else {
+    BPD_WAIT_VM(YOUNGER);
+  }
+  if constexpr (ROWAFF) {
+    const int tiles = p.K >> 4;
+    float sq = 0.f, qq = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float w = (wave + 4 * i) < tiles ? 1.f : 0.f;
+      sq = fmaf(w, rpv[i].x, sq); qq = fmaf(w, rpv[i].y, qq);
+    }
+    ra_part[wave * 64 + lane] = make_float2(sq, qq);
+  }
   __syncthreads();
+  if constexpr (ROWAFF) {                        // read back in the epilogue, many barriers later
+    if (tid < BM) {
+      float S = ra_part[tid].x, Q = ra_part[tid].y;
+#pragma unroll
+      for (int w = 1; w < 4; ++w) { S += ra_part[w * 64 + tid].x; Q += ra_part[w * 64 + tid].y; }
+      const float mean = S / p.K;
+      const float var = fmaxf(Q / p.K - mean * mean, 0.f);
+      ra_ms[tid] = make_float2(mean, 1.0f / sqrtf(var + e.ra_eps));
+    }
+  }
   // One chunk c (weights in AC, activations in xc): chunk c + 1 starts moving into AL / xl, chunk c is multiplied, then the
   // workgroup meets once activation chunk c + 1 has landed.  The weights requested after that chunk stay in flight across
   // the barrier, so the memory pipe never drains.  The last chunk re-requests itself (branch-free).
@@ -1011,5 +1066,5 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
     }
     return;
   }
-  store_tiles<MT, NT, STATS>(e, g, acc, m0, nt0, ntiles, p.M, lane);
+  store_tiles<MT, NT, STATS, ROWAFF>(e, g, acc, m0, nt0, ntiles, p.M, lane, ra_ms, ra_c4, ra_d4);
 }

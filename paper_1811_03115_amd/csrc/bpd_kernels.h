@@ -61,6 +61,11 @@ struct Epi {
   // too, with the row count as the stride between column tiles)
   const float* lnR_stats; const float* lnR_g; const float* lnR_b; int lnR_K; float lnR_eps;
   float* stats_out;
+  // LDS-staged kernel, LayerNorm folded into the GEMM (ROWAFF): X is the raw bf16 copy of the residual stream, W the
+  // weights with the LayerNorm gain multiplied in, and every product is finished per row and column as
+  //   rstd[m] * (acc - mu[m] * ra_c[n]) + ra_d[n],   ra_c = column sums of those weights, ra_d = LayerNorm bias . W,
+  // with mu / rstd from the partial statistics ra_stats[(tile * M + row) * 2] that the producer of X left
+  const float* ra_stats; const float* ra_c; const float* ra_d; float ra_eps;
   // mode 1
   float* Qf; void* Ka; void* Va;
   int dsplit, chunk0, rows_per_seq, cap;
@@ -374,6 +379,35 @@ template <typename SRC>
 __global__ void convert_vector_kernel(const SRC* src, float* dst, long n) {
   const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx < n) dst[idx] = to_f<SRC>(src[idx]);
+}
+
+// LayerNorm folded into the weights that follow it: LN(x) W = rstd * (x W' - mu * c) + dvec with
+//   W'[k][n] = g[k] W[k][n] (rounded to bf16),  c[n] = sum_k W'[k][n] (of the rounded values: what the matrix cores
+//   multiply),  dvec[n] = sum_k b[k] W[k][n].
+// Wp / Wf: packed tiles [N/16][K/32][64 lanes][8]; one wavefront per column tile.  Grid N/16, 64 threads.
+__global__ __launch_bounds__(64) void fold_layernorm_kernel(const bf16_t* Wp, bf16_t* Wf, const float* g, const float* b,
+                                                            float* c, float* dvec, int ksteps) {
+  const int tile = blockIdx.x, lane = threadIdx.x;
+  float cs = 0.f, ds = 0.f;
+  for (int ks = 0; ks < ksteps; ++ks) {
+    const long at = (((long)tile * ksteps + ks) * 64 + lane) * 8;
+    const uint4 raw = *(const uint4*)(Wp + at);
+    const unsigned in[4] = {raw.x, raw.y, raw.z, raw.w};
+    unsigned out[4];
+    const int k0 = ks * 32 + (lane >> 4) * 8;
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) {
+      const float w0 = __uint_as_float(in[e2] << 16), w1 = __uint_as_float(in[e2] & 0xFFFF0000u);
+      const bf16_t f0 = f2bf(w0 * g[k0 + 2 * e2]), f1 = f2bf(w1 * g[k0 + 2 * e2 + 1]);
+      cs += bf2f(f0) + bf2f(f1);
+      ds = fmaf(b[k0 + 2 * e2], w0, ds); ds = fmaf(b[k0 + 2 * e2 + 1], w1, ds);
+      out[e2] = (unsigned)f0 | ((unsigned)f1 << 16);
+    }
+    *(uint4*)(Wf + at) = make_uint4(out[0], out[1], out[2], out[3]);
+  }
+  cs += __shfl_xor(cs, 16, 64); cs += __shfl_xor(cs, 32, 64);
+  ds += __shfl_xor(ds, 16, 64); ds += __shfl_xor(ds, 32, 64);
+  if (lane < 16) { c[tile * 16 + lane] = cs; dvec[tile * 16 + lane] = ds; }
 }
 
 // ---------------------------------------------------------------------------------------

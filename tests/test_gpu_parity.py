@@ -359,6 +359,9 @@ ODD_SHAPES = [
     wl.Config("loc-bf16", 32, 1, 2, 128, 2, 256, 528, 5, 3, 7, 40, "bf16", 2, src_len_kind="lognormal", local_q=8, local_m=5),
     wl.Config("loc-f32", 33, 1, 2, 64, 4, 128, 272, 4, 2, 6, 36, "f32", 2, local_q=6, local_m=3),
     wl.Config("loc-dh16", 34, 1, 1, 128, 8, 256, 528, 3, 2, 7, 30, "bf16", 2, local_q=4, local_m=9),
+    # more than 128 block rows: LayerNorm folded into the weights of the GEMM that follows it (row-affine epilogue on
+    # the raw bf16 copy of the residual stream); 153 rows = nine 16-row tiles and a ragged one
+    wl.Config("odd-fold153", 37, 1, 3, 256, 4, 512, 528, 9, 17, 6, 24, "bf16", 2, src_len_kind="lognormal"),
     wl.Config("loc-b20", 35, 1, 1, 128, 2, 256, 528, 4, 20, 7, 30, "bf16", 2, src_len_kind="lognormal", local_q=5, local_m=0),
 ]
 
