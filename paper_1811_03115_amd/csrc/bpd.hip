@@ -348,6 +348,10 @@ void launch_stream(const bpd_ctx* ctx, const GemmP& p, const Epi& e, int groups)
   if (p.K == 4096) { if (nt) launch_stream_cfg<16, true>(ctx, p, e, groups); else launch_stream_cfg<16, false>(ctx, p, e, groups); }
   else { if (nt) launch_stream_cfg<8, true>(ctx, p, e, groups); else launch_stream_cfg<8, false>(ctx, p, e, groups); }
 }
+// The accept kernel of a step embeds the next step's block (accept_embed_kernel: bf16, at most 64 column tiles)
+bool embed_in_accept(const bpd_ctx* ctx) {
+  return ctx->cfg.dtype == BPD_BF16 && ctx->cfg.d_model <= 1024;
+}
 // LayerNorm statistics ride along with the residual stream when the whole block is one MFMA row tile
 bool stats_path(const bpd_ctx* ctx, int M) {
   return ctx->cfg.dtype == BPD_BF16 && M <= 16 && ctx->cfg.d_model <= 1024;
@@ -829,9 +833,11 @@ int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
   bool xs = false;      // L.stats_big describes the current L.x
   {
     PhaseTimer t(ctx, BPD_PHASE_LAYERS);
-    // (the previous step's accept kernel may already have embedded this block and cleared the keys)
-    const bool have_x = sp && !zero_input && R == k && ctx->x_ready_k == k;
+    // (the previous step's accept kernel may already have embedded this block, with its statistics (and, beyond 16 rows,
+    // its bf16 copy in L.xn), and cleared the keys)
+    const bool have_x = embed_in_accept(ctx) && !zero_input && R == k && ctx->x_ready_k == k;
     ctx->x_ready_k = 0;
+    xs = have_x && !sp;
     if (!have_x) embed(ctx, L.P, c.k_max, L.L, R, M, L.pos_tgt, L.x, zero_input, L.keys, (int)nk);
     for (int l = 0; l < c.n_dec_layers; ++l) {
       DecL& w = L.dec[l];
@@ -1155,10 +1161,13 @@ static int step_impl(bpd_ctx* ctx, int k, const int* imposed_dev, int imposed_st
     StateP s = state_params(ctx);
     s.imposed = imposed_dev; s.imposed_stride = imposed_stride;
     const bpd_config& c = ctx->cfg;
-    if (stats_path(ctx, ctx->B * k) && c.d_model <= 1024) {
-      // one block of at most 16 rows: the accept kernel also embeds the next block (same k assumed; checked by forward)
+    if (embed_in_accept(ctx)) {
+      // the accept kernel also embeds the next block (same k assumed; checked by forward); its LayerNorm statistics go
+      // where the first layer will look for them: the single-tile layout for at most 16 rows, per-tile rows otherwise
+      const bool sp = stats_path(ctx, ctx->B * k);
       hipLaunchKernelGGL(accept_embed_kernel, dim3(ctx->B), dim3(1024), 0, ctx->stream, s, L.keys, k, ctx->B, imposed_step, accepted_dev,
-                         c.d_model, (const bf16_t*)L.emb, c.vocab, (const float*)L.pos_tgt, sqrtf((float)c.d_model), L.x, L.stats_ln);
+                         c.d_model, (const bf16_t*)L.emb, c.vocab, (const float*)L.pos_tgt, sqrtf((float)c.d_model), L.x,
+                         sp ? L.stats_ln : L.stats_big, sp ? 16 : ctx->B * k, sp ? (bf16_t*)nullptr : (bf16_t*)L.xn);
       ctx->x_ready_k = k;
     } else {
       hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(64), 0, ctx->stream, s, L.keys, k, ctx->B, 1, imposed_step, accepted_dev);

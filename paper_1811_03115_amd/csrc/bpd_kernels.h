@@ -1345,15 +1345,18 @@ __global__ __launch_bounds__(64) void accept_kernel(StateP s, const unsigned lon
   }
 }
 
-// accept_kernel followed, in the same launch, by the embedding of the next block (embed_stats_kernel): for blocks of at
-// most 16 rows in all (bf16), where the step is a chain of small dependent kernels and each one saved counts.  One
+// accept_kernel followed, in the same launch, by the embedding of the next block (embed_stats_kernel; bf16, d <= 1024):
+// the step is a chain of dependent kernels and each one saved counts.  One
 // workgroup of 16 waves per sequence: wave 0 verifies / accepts / commits, then every wave embeds four 16-column tiles of
 // the sequence's k next rows (token i = new proposal i, position = new L + i) with their partial LayerNorm statistics,
 // exactly as embed_stats_kernel would at the start of the next step, and the sequence's k*k arg-max keys are cleared
 // for the next vocabulary projection.
+// stats: [(tile * srows + row) * 2] with srows = 16 (single-tile layout) or the number of rows B * k; xb (may be null):
+// bf16 copy of the rows as well.
 __global__ __launch_bounds__(1024) void accept_embed_kernel(StateP s, unsigned long long* keys, int k, int B, int step,
                                                             int* accepted_out, int d, const bf16_t* E, int V,
-                                                            const float* pos, float scale, float* x, float* stats) {
+                                                            const float* pos, float scale, float* x, float* stats,
+                                                            int srows, bf16_t* xb) {
   __shared__ int tok_s[16];
   __shared__ int L_s;
   __shared__ int A_s[256];                       // the sequence's k x k arg-max table
@@ -1435,8 +1438,11 @@ __global__ __launch_bounds__(1024) void accept_embed_kernel(StateP s, unsigned l
     float qv = (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
     sv += __shfl_xor(sv, 16, 64); sv += __shfl_xor(sv, 32, 64);
     qv += __shfl_xor(qv, 16, 64); qv += __shfl_xor(qv, 32, 64);
-    if (lane < 16 && i < k) ((float2*)stats)[tile * 16 + row] = make_float2(sv, qv);
-    if (i < k) *(float4*)(x + (long)row * d + c0) = make_float4(v[0], v[1], v[2], v[3]);
+    if (lane < 16 && i < k) ((float2*)stats)[(long)tile * srows + row] = make_float2(sv, qv);
+    if (i < k) {
+      *(float4*)(x + (long)row * d + c0) = make_float4(v[0], v[1], v[2], v[3]);
+      if (xb) *(uint2*)(xb + (long)row * d + c0) = make_uint2((unsigned)f2bf(v[0]) | ((unsigned)f2bf(v[1]) << 16), (unsigned)f2bf(v[2]) | ((unsigned)f2bf(v[3]) << 16));
+    }
   }
 }
 
