@@ -319,3 +319,24 @@ def test_c4_local_attention_full_size():
     out_ids, out_len, st = ctx.bpd_decode(cfg.k)
     assert (out_len == 3072).all() and st.finished == cfg.batch
     print("C4L logit err at j=600:", e1, "steps", st.steps)
+
+
+@pytest.mark.parametrize("batch", [5, 17])
+def test_block_embedded_by_the_accept_kernel_beyond_16_rows(batch):
+    """Free-running steps (no proposals re-sent, so every block after the first is the one the previous step's accept
+    kernel embedded, with its LayerNorm statistics and bf16 copy): 45 rows (LayerNorm applied while staging) and 153 rows
+    (LayerNorm folded into the weights).  The state reached is checked against the oracle's recomputation."""
+    cfg = wl.Config(f"ahead-b{batch}", 38, 1, 3, 256, 4, 512, 528, 9, batch, 6, 40, "bf16", -1, src_len_kind="lognormal")
+    weights = wl.make_weights(cfg, std=0.02)
+    ctx = gpu_context(cfg, weights)
+    model = oracle_model(cfg, weights)
+    src, n = wl.make_sources(cfg)
+    ctx.bpd_encode(src, n)
+    sched = wl.make_schedule(cfg, 3, 8, seed=5)
+    for s in range(3):
+        ctx.bpd_step(cfg.k, sched[s])
+    for b in (0, batch - 1):
+        err = check_state_against_oracle(ctx, cfg, model, src, n, b, cfg.k)
+        print(cfg.name, "sequence", b, "logit err", err)
+    out_ids, out_len, st = ctx.bpd_decode(cfg.k)
+    assert (out_len == 40).all() and st.finished == cfg.batch
