@@ -806,6 +806,20 @@ int heads_two_phase(bpd_ctx* ctx, int k) {
   return BPD_OK;
 }
 
+// The folded copies of the decoder's LayerNorm + GEMM pairs follow the loaded weights: bpd_load_weights marks them stale
+// (and asks for a new bpd_encode, which calls this).
+void refresh_folded_weights(bpd_ctx* ctx) {
+  Layout& L = ctx->lay;
+  if (ctx->fold_ready || !L.dec[0].f_qkv.W) return;
+  const bpd_config& c = ctx->cfg;
+  const int d = c.d_model;
+  auto fold = [&](const void* W, const FoldW& f, const LnW& w, int N) {
+    hipLaunchKernelGGL(fold_layernorm_kernel, dim3(N / 16), dim3(64), 0, ctx->stream, (const bf16_t*)W, (bf16_t*)f.W, w.g, w.b, f.c, f.d, d / 32);
+  };
+  for (auto& e : L.dec) { fold(e.wqkv, e.f_qkv, e.ln1, 3 * d); fold(e.cq, e.f_cq, e.ln2, d); fold(e.w1, e.f_w1, e.ln3, c.d_ff); }
+  ctx->fold_ready = true;
+}
+
 // One invocation of the combined model on R new rows per sequence (R = 1 for the first call
 // on the empty prefix, R = k afterwards) with the first k heads; fills keys[B*R*k].
 int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
@@ -1114,15 +1128,7 @@ int bpd_encode(bpd_ctx* ctx, const int32_t* src_ids, const int32_t* src_len, con
   }
   Layout& L = ctx->lay;
   ctx->B = B; ctx->S = S; ctx->encoded = false; ctx->x_ready_k = 0;
-  if (!ctx->fold_ready && L.dec[0].f_qkv.W) {     // (every tensor is loaded: checked above)
-    const int d = c.d_model;
-    auto fold = [&](const void* W, const FoldW& f, const LnW& w, int N) {
-      hipLaunchKernelGGL(fold_layernorm_kernel, dim3(N / 16), dim3(64), 0, ctx->stream, (const bf16_t*)W, (bf16_t*)f.W, w.g, w.b, f.c, f.d, d / 32);
-    };
-    for (auto& e : L.dec) { fold(e.wqkv, e.f_qkv, e.ln1, 3 * d); fold(e.cq, e.f_cq, e.ln2, d); fold(e.w1, e.f_w1, e.ln3, c.d_ff); }
-    LAUNCHCHK();
-    ctx->fold_ready = true;
-  }
+  refresh_folded_weights(ctx);                    // (every tensor is loaded: checked above)
   HIPCHK(hipMemcpyAsync(L.src_ids, src_ids, (size_t)B * S * 4, hipMemcpyDefault, ctx->stream));
   HIPCHK(hipMemcpyAsync(L.src_len, src_len, (size_t)B * 4, hipMemcpyDefault, ctx->stream));
   if (max_len) HIPCHK(hipMemcpyAsync(L.max_len, max_len, (size_t)B * 4, hipMemcpyDefault, ctx->stream));

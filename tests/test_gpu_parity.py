@@ -456,3 +456,34 @@ def test_accept_kernel_embedding_next_block_changes_nothing(which):
     for s, (a, b) in enumerate(zip(ahead, separate)):
         for u, v in zip(a, b):
             np.testing.assert_array_equal(u, v, err_msg=f"step {s}")
+
+
+@pytest.mark.gpu
+def test_reloaded_layernorm_weights_reach_the_folded_copies():
+    """Blocks of more than 128 rows multiply by copies of the decoder matrices with the LayerNorm in front of them
+    folded in.  LayerNorm gains and biases loaded later (a new bpd_encode is then required) must reach those
+    copies: the state after the same steps equals that of a fresh context given the new weights from the start."""
+    cfg = {c.name: c for c in ODD_SHAPES}["odd-fold153"]
+    w1 = wl.make_weights(cfg, std=0.02)
+    rng = np.random.default_rng(3)
+    new_ln = {n: (a + rng.normal(0, 0.05, a.shape)).astype(np.float32) for n, a in w1.items()
+              if n.startswith("dec.") and (".ln1." in n or ".ln2." in n or ".ln3." in n)}
+    assert len(new_ln) == 6 * cfg.n_dec
+    w2 = dict(w1); w2.update(new_ln)
+    src, n = ragged_sources(cfg, 5)
+    full = np.full(cfg.batch, cfg.k, np.int32)
+
+    def run(ctx):
+        ctx.bpd_encode(src, n)
+        ctx.bpd_step(cfg.k, full)
+        ctx.bpd_step(cfg.k, full)
+        return [np.array(v) for v in ctx.bpd_get_state()] + [np.array(v) for v in ctx.bpd_get_output()]
+
+    fresh = gpu_context(cfg, w2)
+    want = run(fresh)
+    ctx = gpu_context(cfg, w1)
+    first = run(ctx)
+    assert any((a != b).any() for a, b in zip(first, want))           # the new gains matter
+    ctx.bpd_load_weights(new_ln)
+    for a, b in zip(run(ctx), want):
+        np.testing.assert_array_equal(a, b)
