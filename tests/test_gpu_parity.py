@@ -304,6 +304,11 @@ def test_error_codes_on_gpu():
         with pytest.raises(binding.BpdError) as e:
             ctx.bpd_step(k)
         assert e.value.code == -1
+    for args in ((-1, 0), (4, -1), (0, 3)):             # local attention: negative lengths, memory without a block
+        with pytest.raises(binding.BpdError) as e:
+            ctx.bpd_set_local_attention(*args)
+        assert e.value.code == -1
+    ctx.bpd_set_local_attention(4, 2); ctx.bpd_set_local_attention(0, 0)
     P, A, j, fin = ctx.bpd_get_state()
     ctx.bpd_step(cfg.k)                                 # state was left usable by the failed calls
     assert (ctx.bpd_get_state()[2] >= 1).all()
