@@ -97,6 +97,32 @@ def test_c0_exact_decode_equals_greedy():
             assert [i for i in range(17) for _ in range(st.hist[i])] == sorted(ref.block_sizes)
 
 
+def test_local_attention_exact_decode_equals_greedy():
+    """fp32, 1D local self-attention (query blocks of 6, memory 3; Section 7.2): free-running exact-match decoding over
+    several query blocks reproduces the oracle's greedy output under the same windows, token for token, for every
+    sequence, at k = k_max and k = 1."""
+    cfg = {c.name: c for c in ODD_SHAPES}["loc-f32"]
+    cfg = wl.scaled(cfg, eos_id=-1)               # fixed length: every sequence crosses five block boundaries
+    weights = wl.make_weights(cfg, std=0.08)
+    model = oracle_model(cfg, weights)
+    assert model.local_q == 6 and model.local_m == 3
+    src, n = wl.make_sources(cfg)
+    ctx = gpu_context(cfg, weights)
+    for b in range(cfg.batch):
+        score, block = scorers(model, src[b, :n[b]])
+        gr = greedy_decode(score, cfg.max_out, cfg.eos_id)
+        margins = []
+        for t in range(len(gr.tokens)):
+            z = np.sort(score(gr.tokens[:t])[0])
+            margins.append(z[-1] - z[-2])
+        first = len(gr.tokens) if min(margins) >= 2 * TOL["f32"] else int(np.argmax(np.array(margins) < 2 * TOL["f32"]))
+        assert first > 12                         # (the comparison reaches past the first window that leaves key 0)
+        for k in (cfg.k, 1):
+            ctx.bpd_encode(src, n)
+            out_ids, out_len, st = ctx.bpd_decode(k)
+            assert out_ids[b, :out_len[b]].tolist()[:first] == gr.tokens[:first]
+
+
 def test_free_running_bf16_is_a_valid_greedy_path():
     """bf16, no teacher forcing: every token the GPU emits must be within tolerance of the
     oracle's best token given the GPU's own prefix, and every block boundary consistent."""
