@@ -325,6 +325,28 @@ def test_blockwise_equals_greedy_tiny_transformers(seed, k):
         assert seq.block_sizes == [1] * len(gr.tokens)
 
 
+def test_blockwise_equals_greedy_with_local_attention():
+    """The parallel scoring of a block (Section 3) stays consistent under 1D local attention: scoring all block rows in
+    one pass gives the rows that scoring them one prefix at a time gives, so blockwise decoding still equals greedy."""
+    cfg = tiny_cfg(k=4, vocab=5, eos_id=-1, max_out=9)
+    _, w = build(cfg, seed=6, std=0.6)
+    model = CombinedModel(w, cfg.n_enc, cfg.n_dec, cfg.n_heads, cfg.k, cfg.ln_eps, local_q=3, local_m=2)
+    full = CombinedModel(w, cfg.n_enc, cfg.n_dec, cfg.n_heads, cfg.k, cfg.ln_eps)
+    score, block = scorers(model, [3, 4, 3])
+    gr = greedy_decode(score, cfg.max_out, cfg.eos_id)
+    par = blockwise_decode(score, cfg.k, cfg.max_out, cfg.eos_id, block_score=block)
+    seq = blockwise_decode(score, cfg.k, cfg.max_out, cfg.eos_id)
+    assert par.tokens == gr.tokens == seq.tokens and par.block_sizes == seq.block_sizes
+    mem = model.encode([3, 4, 3])
+    prefix = gr.tokens[:7]
+    z_all = model.all_position_logits(mem, prefix)
+    for t in range(len(prefix) + 1):
+        np.testing.assert_allclose(z_all[t], model.next_logits(mem, prefix[:t]), atol=1e-10)
+    # and the windows matter for this model: the full-attention scores differ once a window leaves position 0
+    assert np.abs(z_all[5] - full.all_position_logits(mem, prefix)[5]).max() > 1e-6
+    np.testing.assert_allclose(z_all[:3], full.all_position_logits(mem, prefix)[:3], atol=1e-10)
+
+
 def test_khat_brute_force_tiny_vocab():
     """V = 4: k-hat from its definition (k sequential greedy calls) and by enumerating
     all V^k candidate blocks: exactly one block of each length is greedy-consistent."""
