@@ -453,13 +453,14 @@ bool ldsx_ln_ok(const bpd_ctx* ctx, const GemmP& p) {
 
 // In-place residual update with a long K and few output tiles on the LDS-staged kernel: the number of K slices it is
 // split into (1: not split): the fewest with which a tile of at least 48 rows still fills the chip; if no slicing gets
-// there, the most slices allowed (each at least 256 deep).
+// there, the most slices allowed (each at least 512 deep: two chunks; 80 x 2048 x 512 took 4 us more per step as eight
+// slices of 256 than as four of 512).
 int residual_k_slices(const bpd_ctx* ctx, const GemmP& p) {
   if (p.N != ctx->cfg.d_model || p.K < 2048 || p.K % 64 != 0) return 1;
   int mt, nt, ns = 1;
   pick_tile(p.M, p.N, p.K, 1, mt, nt);
   if (nt == 1 && mt < 3) {
-    for (int t = 2; t <= KSPLIT_MAX && p.K % (t * 256) == 0 && (size_t)t * p.M * p.N <= ctx->lay.n_kpart; t *= 2) {
+    for (int t = 2; t <= KSPLIT_MAX && p.K % (t * 512) == 0 && (size_t)t * p.M * p.N <= ctx->lay.n_kpart; t *= 2) {
       ns = t;
       pick_tile(p.M, p.N, p.K / t, t, mt, nt);
       if (nt > 1 || mt >= 3) break;
