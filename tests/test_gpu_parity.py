@@ -442,7 +442,7 @@ def random_config(seed):
     return cfg
 
 
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed", range(24))
 def test_lockstep_random_shapes(seed):
     cfg = random_config(seed)
     weights = wl.make_weights(cfg, std=0.08 if cfg.dtype == "f32" else 0.02)
