@@ -935,14 +935,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
   static_assert(YOUNGER <= 63, "vmcnt range");
   BPD_X_TO_LDS(xs0, cbase)
   BPD_LOAD_W(a0, cbase)
-  float2 rpv[ROWAFF ? 16 : 1];
+  // row statistics: RL loads per thread.  16 rows: thread = (tile class tid / 16, row tid % 16), tiles class + 16 i;
+  // more rows: lane = row, tiles wave + 4 i
+  constexpr int RL = MT == 1 ? 4 : 16;
+  float2 rpv[ROWAFF ? RL : 1];
   float4 ra_c4[NT], ra_d4[NT];
   if constexpr (ROWAFF) {                        // behind the first chunk's loads, in the shadow of their round trip
-    int row = m0 + lane; row = row < p.M ? row : p.M - 1;
+    int row = m0 + (MT == 1 ? (tid & 15) : lane); row = row < p.M ? row : p.M - 1;
     const int tiles = p.K >> 4;                  // <= 64
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int t = wave + 4 * i;
+    for (int i = 0; i < RL; ++i) {
+      const int t = MT == 1 ? (tid >> 4) + 16 * i : wave + 4 * i;
       rpv[i] = ((const float2*)e.ra_stats)[(long)(t < tiles ? t : 0) * p.M + row];
     }
 #pragma unroll
@@ -959,18 +962,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
     const int tiles = p.K >> 4;
     float sq = 0.f, qq = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float w = (wave + 4 * i) < tiles ? 1.f : 0.f;
+    for (int i = 0; i < RL; ++i) {
+      const float w = (MT == 1 ? (tid >> 4) + 16 * i : wave + 4 * i) < tiles ? 1.f : 0.f;
       sq = fmaf(w, rpv[i].x, sq); qq = fmaf(w, rpv[i].y, qq);
     }
-    ra_part[wave * 64 + lane] = make_float2(sq, qq);
+    ra_part[MT == 1 ? tid : wave * 64 + lane] = make_float2(sq, qq);      // [class][16 rows] or [wave][64 rows]
   }
   __syncthreads();
   if constexpr (ROWAFF) {                        // read back in the epilogue, many barriers later
     if (tid < BM) {
+      constexpr int NP = MT == 1 ? 16 : 4, PS = MT == 1 ? 16 : 64;
       float S = ra_part[tid].x, Q = ra_part[tid].y;
 #pragma unroll
-      for (int w = 1; w < 4; ++w) { S += ra_part[w * 64 + tid].x; Q += ra_part[w * 64 + tid].y; }
+      for (int w = 1; w < NP; ++w) { S += ra_part[w * PS + tid].x; Q += ra_part[w * PS + tid].y; }
       const float mean = S / p.K;
       const float var = fmaxf(Q / p.K - mean * mean, 0.f);
       ra_ms[tid] = make_float2(mean, 1.0f / sqrtf(var + e.ra_eps));
