@@ -869,12 +869,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
     // one round trip for everything the first chunk needs: the statistics, the first activations and weights
     float mu[XI], rs[XI];
     {
+      // (16 rows: thread = (tile class tid / 16, row tid % 16), tiles class + 16 i: four loads per thread instead of sixteen)
+      constexpr int RL = MT == 1 ? 4 : 16;
       const int tiles = p.K >> 4;                // <= 64
-      int row = m0 + lane; row = row < p.M ? row : p.M - 1;
-      float2 pv[16];
+      int row = m0 + (MT == 1 ? (tid & 15) : lane); row = row < p.M ? row : p.M - 1;
+      float2 pv[RL];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {             // branch-free: all loads in flight together
-        const int t = wave + 4 * i;
+      for (int i = 0; i < RL; ++i) {             // branch-free: all loads in flight together
+        const int t = MT == 1 ? (tid >> 4) + 16 * i : wave + 4 * i;
         pv[i] = ((const float2*)ln.stats)[(long)(t < tiles ? t : 0) * p.M + row];
       }
       BPD_LOAD_X(0)
@@ -882,16 +884,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
       __builtin_amdgcn_sched_barrier(0);
       float sq = 0.f, qq = 0.f;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float w = (wave + 4 * i) < tiles ? 1.f : 0.f;
+      for (int i = 0; i < RL; ++i) {
+        const float w = (MT == 1 ? (tid >> 4) + 16 * i : wave + 4 * i) < tiles ? 1.f : 0.f;
         sq = fmaf(w, pv[i].x, sq); qq = fmaf(w, pv[i].y, qq);
       }
-      part_s[wave][lane] = make_float2(sq, qq);
+      (&part_s[0][0])[MT == 1 ? tid : wave * 64 + lane] = make_float2(sq, qq);      // [class][16 rows] or [wave][64 rows]
       __syncthreads();
       if (tid < BM) {
+        constexpr int NP = MT == 1 ? 16 : 4, PS = MT == 1 ? 16 : 64;
         float S = part_s[0][tid].x, Q = part_s[0][tid].y;
 #pragma unroll
-        for (int w = 1; w < 4; ++w) { S += part_s[w][tid].x; Q += part_s[w][tid].y; }
+        for (int w = 1; w < NP; ++w) { S += (&part_s[0][0])[w * PS + tid].x; Q += (&part_s[0][0])[w * PS + tid].y; }
         const float mean = S / p.K;
         const float var = fmaxf(Q / p.K - mean * mean, 0.f);
         ms_s[tid] = make_float2(mean, 1.0f / sqrtf(var + ln.eps));
