@@ -403,12 +403,23 @@ void pick_tile(int M, int N, int K, long zdim, int& mt, int& nt, int mt_max = 8)
 
 // e.stats_out (mode 0, one group, no split over K): the kernel also writes the LayerNorm statistics of its output, which
 // only the tiles of at most 48 rows are built for.  Returns whether it did.
+// Small tiles fetch bias and residual at kernel entry (Epi::pre_epi): absent operands are replaced by a zero-filled vector.
+void prefetch_epilogue(Epi& e, const GemmP& p, int mt, int nt, const float* zeros) {
+  if (!zeros || mt * nt > 3 || e.mode != 0 || p.ksplit > 1) return;
+  if (!e.bias) { e.bias = zeros; e.bias_g = 0; }
+  if (!e.R) { e.R = zeros; e.ldr = 0; e.r_g = 0; }
+  e.pre_epi = 1;
+}
+
 template <bool ARGMAX>
-bool dispatch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* logits, int groups, hipStream_t s) {
+bool dispatch_ldsx(const GemmP& p, const Epi& e_in, unsigned long long* keys, float* logits, int groups, hipStream_t s,
+                   const float* zeros = nullptr) {
+  Epi e = e_in;
   int mt, nt;
   const int kslice = p.ksplit > 1 ? p.K / p.ksplit : p.K;
   const bool stats = !ARGMAX && e.mode == 0 && e.stats_out != nullptr && groups == 1 && p.ksplit <= 1;
   pick_tile(p.M, p.N, kslice, groups, mt, nt, stats ? LDSX_LN_MT_MAX : 8);       // groups = K slices for a split-K launch
+  if constexpr (!ARGMAX) prefetch_epilogue(e, p, mt, nt, zeros);
   if constexpr (!ARGMAX) {
     if (stats) {
 #define BPD_CASE(MT_, NT_, KC_) if (mt == MT_ && nt == NT_) { launch_ldsx<MT_, NT_, KC_, false, false, true>(p, e, keys, logits, groups, s); return true; }
@@ -438,9 +449,11 @@ void dispatch_ldsx_ln(const GemmP& p, const Epi& e, const LnP& ln, hipStream_t s
 #undef BPD_CASE
 }
 // Y = epilogue(LayerNorm(x) W) with the LayerNorm folded into the weights (e.ra_*): X is the raw bf16 copy of x.
-void dispatch_ldsx_fold(const GemmP& p, const Epi& e, hipStream_t s) {
+void dispatch_ldsx_fold(const GemmP& p, const Epi& e_in, hipStream_t s, const float* zeros) {
+  Epi e = e_in;
   int mt, nt;
   pick_tile(p.M, p.N, p.K, 1, mt, nt, LDSX_LN_MT_MAX);
+  prefetch_epilogue(e, p, mt, nt, zeros);
 #define BPD_CASE(MT_, NT_, KC_) if (mt == MT_ && nt == NT_) { launch_ldsx<MT_, NT_, KC_, false, false, false, true>(p, e, nullptr, nullptr, 1, s); return; }
   BPD_CASE(3, 1, 256) BPD_CASE(2, 1, 256) BPD_CASE(1, 1, 256)
   BPD_CASE(3, 2, 128) BPD_CASE(2, 2, 128) BPD_CASE(1, 2, 128)
@@ -497,12 +510,12 @@ bool gemm(bpd_ctx* ctx, const GemmP& p, const Epi& e_in, int groups = 1) {
         GemmP q = p;
         q.ksplit = ns; q.part = ctx->lay.kpart;
         e.stats_out = nullptr;                     // the slices are raw products: no statistics of the sum yet
-        dispatch_ldsx<false>(q, e, nullptr, nullptr, ns, s);
+        dispatch_ldsx<false>(q, e, nullptr, nullptr, ns, s, ctx->lay.zeros);
         ctx->pend_slices = ns; ctx->pend_bias = e.bias ? e.bias : ctx->lay.zeros; ctx->pend_x = e.Yf;
         return false;
       }
     }
-    return dispatch_ldsx<false>(p, e, nullptr, nullptr, groups, s);
+    return dispatch_ldsx<false>(p, e, nullptr, nullptr, groups, s, ctx->lay.zeros);
   } else {
     e.stats_out = nullptr;
     if (p.M > 64) launch_gemm_bf16<8, 1, 4>(p, e, groups, s);
@@ -524,7 +537,7 @@ void gemm_ln(bpd_ctx* ctx, float* x, LnW w, void* xn, float* yf, GemmP p, const 
     p.X = xn; p.W = fold->W;
     Epi ef = e;
     ef.ra_stats = ctx->lay.stats_big; ef.ra_c = fold->c; ef.ra_d = fold->d; ef.ra_eps = ctx->cfg.ln_eps;
-    dispatch_ldsx_fold(p, ef, ctx->stream);
+    dispatch_ldsx_fold(p, ef, ctx->stream, ctx->lay.zeros);
     return;
   }
   // with_stats: the producer of x left its partial LayerNorm statistics in L.stats_ln (decoder block of one

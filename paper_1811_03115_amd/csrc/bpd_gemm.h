@@ -17,10 +17,12 @@
 // stats_out[(tile * M + row) * 2 + {0, 1}], for the LayerNorm that the next GEMM applies while it stages its activations.
 // ROWAFF: the products are finished as rstd * (acc - mu * c[n]) + d[n] first (LayerNorm folded into the weights, see
 // Epi); ms: (mu, rstd) of the workgroup's rows, in LDS.
+// pre_b / pre_r (with e.pre_epi): bias of the NT column tiles and residual of the MT x NT tiles, fetched at kernel entry.
 template <int MT, int NT, bool STATS, bool ROWAFF = false>
 __device__ __forceinline__ void store_tiles(const Epi& e, int g, const f32x4 (&acc)[MT][NT], int m0, int nt0,
                                             int ntiles, int M, int lane, const float2* ms = nullptr,
-                                            const float4* rc = nullptr, const float4* rd = nullptr) {
+                                            const float4* rc = nullptr, const float4* rd = nullptr,
+                                            const float4* pre_b = nullptr, const float4* pre_r = nullptr) {
   const bool stats = STATS && e.mode == 0 && e.stats_out != nullptr;
 #pragma unroll
   for (int t = 0; t < MT; ++t) {
@@ -38,7 +40,18 @@ __device__ __forceinline__ void store_tiles(const Epi& e, int g, const f32x4 (&a
         v[2] = mr.y * (v[2] - mr.x * cc.z) + dd.z; v[3] = mr.y * (v[3] - mr.x * cc.w) + dd.w;
       }
       float fin[4] = {0.f, 0.f, 0.f, 0.f};
-      if (m < M) epi_store4f(e, g, m, n, v, fin);
+      if (pre_b != nullptr && e.pre_epi) {       // mode 0 with its operands at hand (pre_b is a compile-time null elsewhere)
+        const float4 bs = pre_b[u], rv = pre_r[t * NT + u];
+        v[0] += bs.x; v[1] += bs.y; v[2] += bs.z; v[3] += bs.w;
+        if (e.relu) { v[0] = fmaxf(v[0], 0.f); v[1] = fmaxf(v[1], 0.f); v[2] = fmaxf(v[2], 0.f); v[3] = fmaxf(v[3], 0.f); }
+        v[0] += rv.x; v[1] += rv.y; v[2] += rv.z; v[3] += rv.w;
+        if (m < M) {
+          if (e.Yf) *(float4*)(e.Yf + g * e.yf_g + (long)m * e.ldyf + n) = make_float4(v[0], v[1], v[2], v[3]);
+          if (e.Ya) *(uint2*)((bf16_t*)e.Ya + g * e.ya_g + (long)m * e.ldya + n) =
+                        make_uint2((unsigned)f2bf(v[0]) | ((unsigned)f2bf(v[1]) << 16), (unsigned)f2bf(v[2]) | ((unsigned)f2bf(v[3]) << 16));
+          fin[0] = v[0]; fin[1] = v[1]; fin[2] = v[2]; fin[3] = v[3];
+        }
+      } else if (m < M) epi_store4f(e, g, m, n, v, fin);
       if (stats) {
         float sv = (fin[0] + fin[1]) + (fin[2] + fin[3]);
         float qv = (fin[0] * fin[0] + fin[1] * fin[1]) + (fin[2] * fin[2] + fin[3] * fin[3]);
@@ -938,6 +951,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
   static_assert(YOUNGER <= 63, "vmcnt range");
   BPD_X_TO_LDS(xs0, cbase)
   BPD_LOAD_W(a0, cbase)
+  // small tiles: bias and residual of the epilogue, requested now (younger than the first chunk: the waits below count them)
+  constexpr bool PREF = !ARGMAX && MT * NT <= 3;
+  constexpr int NPRE = PREF ? NT + MT * NT : 0;
+  float4 pre_b[PREF ? NT : 1], pre_r[PREF ? MT * NT : 1];
+  const bool pre = PREF && e.pre_epi != 0;       // (uniform)
+  if constexpr (PREF) {
+    if (pre) {
+#pragma unroll
+      for (int u = 0; u < NT; ++u) {
+        const int n = (nt0 + u < ntiles ? nt0 + u : ntiles - 1) * 16 + lq * 4;
+        pre_b[u] = *(const float4*)(e.bias + g * e.bias_g + n);
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+          int m = m0 + t * 16 + lr; m = m < p.M ? m : p.M - 1;
+          pre_r[t * NT + u] = *(const float4*)(e.R + g * e.r_g + (long)m * e.ldr + n);
+        }
+      }
+    }
+  }
   // row statistics: RL loads per thread.  16 rows: thread = (tile class tid / 16, row tid % 16), tiles class + 16 i;
   // more rows: lane = row, tiles wave + 4 i
   constexpr int RL = MT == 1 ? 4 : 16;
@@ -959,7 +991,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
     }
     BPD_WAIT_VM(0);
   } else {
-    BPD_WAIT_VM(YOUNGER);
+    static_assert(YOUNGER + NPRE <= 63, "vmcnt range");
+    if (pre) { BPD_WAIT_VM(YOUNGER + NPRE); } else { BPD_WAIT_VM(YOUNGER); }
   }
   if constexpr (ROWAFF) {
     const int tiles = p.K >> 4;
@@ -1073,5 +1106,5 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
     }
     return;
   }
-  store_tiles<MT, NT, STATS, ROWAFF>(e, g, acc, m0, nt0, ntiles, p.M, lane, ra_ms, ra_c4, ra_d4);
+  store_tiles<MT, NT, STATS, ROWAFF>(e, g, acc, m0, nt0, ntiles, p.M, lane, ra_ms, ra_c4, ra_d4, PREF ? pre_b : nullptr, PREF ? pre_r : nullptr);
 }

@@ -66,6 +66,10 @@ struct Epi {
   //   rstd[m] * (acc - mu[m] * ra_c[n]) + ra_d[n],   ra_c = column sums of those weights, ra_d = LayerNorm bias . W,
   // with mu / rstd from the partial statistics ra_stats[(tile * M + row) * 2] that the producer of X left
   const float* ra_stats; const float* ra_c; const float* ra_d; float ra_eps;
+  // LDS-staged kernel, small tiles (MT * NT <= 3), mode 0, no split over K: bias and residual are fetched at kernel entry
+  // instead of in the epilogue (one exposed round trip less).  The host then passes a zero-filled vector for an absent
+  // bias (bias_g = 0) or residual (ldr = 0, r_g = 0) so that the loads are unconditional, and sets pre_epi.
+  int pre_epi;
   // mode 1
   float* Qf; void* Ka; void* Va;
   int dsplit, chunk0, rows_per_seq, cap;
