@@ -439,9 +439,11 @@ bool dispatch_ldsx(const GemmP& p, const Epi& e_in, unsigned long long* keys, fl
 
 // Y = epilogue(LayerNorm(ln.x) W) on more than 16 rows with the LayerNorm applied while the activations are staged
 // (tiles of at most 48 rows: the staging registers).
-void dispatch_ldsx_ln(const GemmP& p, const Epi& e, const LnP& ln, hipStream_t s) {
+void dispatch_ldsx_ln(const GemmP& p, const Epi& e_in, const LnP& ln, hipStream_t s, const float* zeros) {
+  Epi e = e_in;
   int mt, nt;
   pick_tile(p.M, p.N, p.K, 1, mt, nt, LDSX_LN_MT_MAX);
+  prefetch_epilogue(e, p, mt, nt, zeros);
 #define BPD_CASE(MT_, NT_, KC_) if (mt == MT_ && nt == NT_) { launch_ldsx<MT_, NT_, KC_, false, true>(p, e, nullptr, nullptr, 1, s, ln); return; }
   BPD_CASE(3, 1, 256) BPD_CASE(2, 1, 256) BPD_CASE(1, 1, 256)
   BPD_CASE(3, 2, 128) BPD_CASE(2, 2, 128) BPD_CASE(1, 2, 128)
@@ -551,7 +553,7 @@ void gemm_ln(bpd_ctx* ctx, float* x, LnW w, void* xn, float* yf, GemmP p, const 
   // big_stats: more than 16 rows and the GEMM that produced x left per-tile statistics in L.stats_big
   if (big_stats && !yf && p.M <= LDSX_LN_M_MAX && ldsx_ln_ok(ctx, p)) {
     LnP ln{x, w.g, w.b, ctx->lay.stats_big, ctx->cfg.ln_eps};
-    dispatch_ldsx_ln(p, e, ln, ctx->stream);
+    dispatch_ldsx_ln(p, e, ln, ctx->stream, ctx->lay.zeros);
     return;
   }
   layernorm(ctx, x, w, p.M, xn, yf);

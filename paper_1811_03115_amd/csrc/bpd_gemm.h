@@ -881,6 +881,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
     }
     // one round trip for everything the first chunk needs: the statistics, the first activations and weights
     float mu[XI], rs[XI];
+    constexpr bool XPREF = MT * NT <= 3;
+    float4 xpre_b[XPREF ? NT : 1], xpre_r[XPREF ? MT * NT : 1];
+    const bool xpre = XPREF && e.pre_epi != 0;
     {
       // (16 rows: thread = (tile class tid / 16, row tid % 16), tiles class + 16 i: four loads per thread instead of sixteen)
       constexpr int RL = MT == 1 ? 4 : 16;
@@ -894,6 +897,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
       }
       BPD_LOAD_X(0)
       BPD_LOAD_WX(a0, 0)
+      if (xpre) {                                // bias and residual of the epilogue ride along (Epi::pre_epi)
+#pragma unroll
+        for (int u = 0; u < NT; ++u) {
+          const int n = (nt0 + u < ntiles ? nt0 + u : ntiles - 1) * 16 + lq * 4;
+          xpre_b[u] = *(const float4*)(e.bias + n);
+#pragma unroll
+          for (int t = 0; t < MT; ++t) {
+            int m = m0 + t * 16 + lr; m = m < p.M ? m : p.M - 1;
+            xpre_r[t * NT + u] = *(const float4*)(e.R + (long)m * e.ldr + n);
+          }
+        }
+      }
       __builtin_amdgcn_sched_barrier(0);
       float sq = 0.f, qq = 0.f;
 #pragma unroll
@@ -929,7 +944,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
 #undef BPD_NORM1
 #undef BPD_LOAD_X
     if (nt0 >= ntiles) return;
-    store_tiles<MT, NT, STATS>(e, g, acc, m0, nt0, ntiles, p.M, lane);
+    store_tiles<MT, NT, STATS>(e, g, acc, m0, nt0, ntiles, p.M, lane, nullptr, nullptr, nullptr, XPREF ? xpre_b : nullptr, XPREF ? xpre_r : nullptr);
     return;
   }
   // The chunk being multiplied and the next one are in use / in flight: weights in two register buffers, activations in
