@@ -508,30 +508,37 @@ __global__ __launch_bounds__(256) void layernorm_kernel(float* x, const float* g
       const int c4 = lane + 64 * i;
       pb[i] = ((const float4*)pbias)[c4 < nv ? c4 : 0];
     }
+    // four slices per batch of loads; the first batch is requested together with the row, gain / bias and the slices'
+    // bias (one round trip), the additions keep their order: x + bias + part[0] + part[1] + ...
+    float4 q[4][V];
+#define BPD_LN_LOAD_SLICES(s0)                                                                  \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                             \
+      const int sl = (s0) + j < nsl ? (s0) + j : nsl - 1;                                       \
+      const float4* pr = (const float4*)(part + ((long)sl * M + row) * d);                      \
+      _Pragma("unroll") for (int i = 0; i < V; ++i) {                                           \
+        const int c4 = lane + 64 * i;                                                           \
+        q[j][i] = pr[c4 < nv ? c4 : 0];                                                         \
+      }                                                                                         \
+    }
+#define BPD_LN_ADD_SLICES(s0)                                                                   \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                             \
+      const float w = (s0) + j < nsl ? 1.f : 0.f;                                               \
+      _Pragma("unroll") for (int i = 0; i < V; ++i) {                                           \
+        v[i].x = fmaf(w, q[j][i].x, v[i].x); v[i].y = fmaf(w, q[j][i].y, v[i].y);               \
+        v[i].z = fmaf(w, q[j][i].z, v[i].z); v[i].w = fmaf(w, q[j][i].w, v[i].w);               \
+      }                                                                                         \
+    }
+    BPD_LN_LOAD_SLICES(0)
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < V; ++i) { v[i].x += pb[i].x; v[i].y += pb[i].y; v[i].z += pb[i].z; v[i].w += pb[i].w; }
-    for (int s0 = 0; s0 < nsl; s0 += 4) {       // four slices per batch of loads
-      float4 q[4][V];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int sl = s0 + j < nsl ? s0 + j : nsl - 1;
-        const float4* pr = (const float4*)(part + ((long)sl * M + row) * d);
-#pragma unroll
-        for (int i = 0; i < V; ++i) {
-          const int c4 = lane + 64 * i;
-          q[j][i] = pr[c4 < nv ? c4 : 0];
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float w = s0 + j < nsl ? 1.f : 0.f;
-#pragma unroll
-        for (int i = 0; i < V; ++i) {
-          v[i].x = fmaf(w, q[j][i].x, v[i].x); v[i].y = fmaf(w, q[j][i].y, v[i].y);
-          v[i].z = fmaf(w, q[j][i].z, v[i].z); v[i].w = fmaf(w, q[j][i].w, v[i].w);
-        }
-      }
+    BPD_LN_ADD_SLICES(0)
+    for (int s0 = 4; s0 < nsl; s0 += 4) {
+      BPD_LN_LOAD_SLICES(s0)
+      BPD_LN_ADD_SLICES(s0)
     }
+#undef BPD_LN_ADD_SLICES
+#undef BPD_LN_LOAD_SLICES
 #pragma unroll
     for (int i = 0; i < V; ++i) {
       const int c4 = lane + 64 * i;
