@@ -1030,7 +1030,6 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p, QProjP qp)
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
   for (int c0 = first; c0 < nkeys; c0 += hop) {
-    if (c0 != first) BPD_LOAD_KV(c0)
     const int k0 = c0 + wave * WK;               // first key of this wave in this chunk
     // V rows of the wave -> LDS (rows past the last key as zeros: their probabilities are zero, their bits unknown)
 #pragma unroll
@@ -1060,6 +1059,9 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p, QProjP qp)
       }
       sacc[kt] = a;
     }
+    // K fragments and V rows of this chunk have been used: the next chunk's are requested now and arrive during the
+    // softmax and the weighted-value products
+    if (c0 + hop < nkeys) BPD_LOAD_KV(c0 + hop)
     mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx);
