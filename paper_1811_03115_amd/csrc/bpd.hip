@@ -529,8 +529,9 @@ bool gemm(bpd_ctx* ctx, const GemmP& p, const Epi& e_in, int groups = 1) {
 void layernorm(bpd_ctx* ctx, float* x, LnW w, int M, void* ya, float* yf);
 
 // Y = epilogue(LayerNorm(x) W).  Block of <= 16 rows: LayerNorm is applied inside the skinny
-// kernel from the partial statistics the producer of x left in L.stats_ln.  Otherwise a
-// LayerNorm kernel (into `xn`, and `yf` in fp32 if given) followed by the GEMM.
+// kernel from the partial statistics the producer of x left in L.stats_ln.  More rows, with per-tile statistics of
+// x in L.stats_big: applied while the LDS-staged kernel stages its activations (up to 128 rows) or folded into the
+// weights (beyond).  Otherwise a LayerNorm kernel (into `xn`, and `yf` in fp32 if given) followed by the GEMM.
 void gemm_ln(bpd_ctx* ctx, float* x, LnW w, void* xn, float* yf, GemmP p, const Epi& e, bool with_stats, bool big_stats = false,
              const FoldW* fold = nullptr) {
   // fold: the producer of x left its bf16 copy in xn and per-tile statistics in L.stats_big (more than 128 rows): one
