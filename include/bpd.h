@@ -89,7 +89,9 @@ typedef struct {
 } bpd_stats;
 
 /* Bytes of device workspace bpd_create needs for this configuration (weights in kernel
- * layout, K/V caches, activations, decode state, a staging area for host weights).
+ * layout -- with max_batch * k_max > 128 in bf16 mode also copies of three decoder matrices
+ * per layer with their LayerNorm folded in --, K/V caches, activations, decode state, a
+ * staging area for host weights).
  * Returns 0 if the configuration is invalid. */
 size_t bpd_workspace_bytes(const bpd_config* cfg);
 
@@ -104,7 +106,9 @@ int bpd_destroy(bpd_ctx* ctx);
 /* Copy n named tensors into the workspace, converting to the kernel layout (bf16 MFMA tiles
  * in BPD_BF16 mode).  The caller's buffers are not referenced after the call returns
  * (the call synchronises the stream).  May be called several times; every tensor must have
- * been loaded before bpd_encode.  Errors: BPD_E_WEIGHTS (unknown name / shape), BPD_E_ARG. */
+ * been loaded before bpd_encode, and a call made after bpd_encode ends the decode in progress
+ * (bpd_step then returns BPD_E_STATE until the next bpd_encode).
+ * Errors: BPD_E_WEIGHTS (unknown name / shape), BPD_E_ARG. */
 int bpd_load_weights(bpd_ctx* ctx, const bpd_tensor* tensors, int n);
 
 /* Condition on a batch of sources (Section 2: the input x) and start decoding:
