@@ -126,7 +126,7 @@ size_t build_layout(const bpd_config& c, char* base, Layout& L) {
   L.hn2 = a.take(B * d * as); L.h2 = vec(B * d);
   L.logits_h1 = vec(M * V);
   const size_t Me = B * S;
-  L.stats_big = vec((size_t)(d / 16 + 1) * (M > Me ? M : Me) * 2);   // per 16-column tile and row: sum, sum of squares
+  L.stats_big = vec((size_t)(d / 64 + 1) * (M > Me ? M : Me) * 2);   // per 64-column block and row: sum, sum of squares
   L.xe = vec(Me * d); L.qe = vec(Me * d);
   L.xen = a.take(Me * d * as); L.ke = a.take(Me * d * as); L.ve = a.take(Me * d * as);
   L.attne = a.take(Me * d * as); L.ffhe = a.take(Me * F * as); L.mem = a.take(Me * d * as);
@@ -417,8 +417,10 @@ bool dispatch_ldsx(const GemmP& p, const Epi& e_in, unsigned long long* keys, fl
   Epi e = e_in;
   int mt, nt;
   const int kslice = p.ksplit > 1 ? p.K / p.ksplit : p.K;
-  const bool stats = !ARGMAX && e.mode == 0 && e.stats_out != nullptr && groups == 1 && p.ksplit <= 1;
-  pick_tile(p.M, p.N, kslice, groups, mt, nt, stats ? LDSX_LN_MT_MAX : 8);       // groups = K slices for a split-K launch
+  const bool stats_req = !ARGMAX && e.mode == 0 && e.stats_out != nullptr && groups == 1 && p.ksplit <= 1;
+  pick_tile(p.M, p.N, kslice, groups, mt, nt, stats_req ? LDSX_LN_MT_MAX : 8);   // groups = K slices for a split-K launch
+  // (the statistics are per 64-column block: every wave of a workgroup must own whole tiles of it)
+  const bool stats = stats_req && p.N % (64 * nt) == 0;
   if constexpr (!ARGMAX) prefetch_epilogue(e, p, mt, nt, zeros);
   if constexpr (!ARGMAX) {
     if (stats) {

@@ -24,6 +24,9 @@ __device__ __forceinline__ void store_tiles(const Epi& e, int g, const f32x4 (&a
                                             const float4* rc = nullptr, const float4* rd = nullptr,
                                             const float4* pre_b = nullptr, const float4* pre_r = nullptr) {
   const bool stats = STATS && e.mode == 0 && e.stats_out != nullptr;
+  float2 wsum[MT];
+#pragma unroll
+  for (int t = 0; t < MT; ++t) wsum[t] = make_float2(0.f, 0.f);
 #pragma unroll
   for (int t = 0; t < MT; ++t) {
     const int m = m0 + t * 16 + (lane & 15);
@@ -57,7 +60,29 @@ __device__ __forceinline__ void store_tiles(const Epi& e, int g, const f32x4 (&a
         float qv = (fin[0] * fin[0] + fin[1] * fin[1]) + (fin[2] * fin[2] + fin[3] * fin[3]);
         sv += __shfl_xor(sv, 16, 64); sv += __shfl_xor(sv, 32, 64);
         qv += __shfl_xor(qv, 16, 64); qv += __shfl_xor(qv, 32, 64);
-        if (lane < 16 && m < M) ((float2*)e.stats_out)[(long)(nt0 + u) * M + m] = make_float2(sv, qv);
+        wsum[t].x += sv; wsum[t].y += qv;        // this wave's NT tiles lie in one 64-column block
+      }
+    }
+  }
+  if constexpr (STATS) {
+    // statistics per 64-column block and row: the waves that share a block (4 / NT of them) meet in LDS; the host
+    // launches this variant only when N is a multiple of 64 * NT, so every wave of the workgroup gets here
+    if (stats) {
+      static_assert(NT == 1 || NT == 2 || NT == 4, "a wave's tiles stay inside one 64-column block");
+      __shared__ float2 st_x[4][16 * MT];
+      const int wave = threadIdx.x >> 6;
+#pragma unroll
+      for (int t = 0; t < MT; ++t)
+        if (lane < 16) st_x[wave][t * 16 + lane] = wsum[t];
+      __syncthreads();
+      constexpr int G = 4 / NT, BMs = 16 * MT;
+      const int blk0 = (nt0 - wave * NT) >> 2;   // first 64-column block of the workgroup
+      for (int idx = threadIdx.x; idx < NT * BMs; idx += 256) {
+        const int j = idx / BMs, r = idx - j * BMs;
+        float2 a = st_x[j * G][r];
+#pragma unroll
+        for (int w = 1; w < G; ++w) { a.x += st_x[j * G + w][r].x; a.y += st_x[j * G + w][r].y; }
+        if (m0 + r < M) ((float2*)e.stats_out)[(long)(blk0 + j) * M + m0 + r] = a;
       }
     }
   }
@@ -748,7 +773,7 @@ template <int MT, int NT, int KC>
 constexpr size_t ldsx_lds_bytes() { return (size_t)2 * ((16 * MT * (KC / 8) + 255) / 256) * 4096; }
 
 // XLN (one group, no split-K, K <= 1024): X = LayerNorm(ln.x) of the fp32 residual stream.  The producer of ln.x left per
-// 16-column tile and row the sum and sum of squares of its values in ln.stats[(tile * M + row) * 2] (store_tiles); the
+// 64-column block and row the sum and sum of squares of its values in ln.stats[(block * M + row) * 2] (store_tiles); the
 // workgroup adds them for its rows, and every activation chunk goes global (fp32) -> registers -> normalised -> bf16 ->
 // LDS, in the layout the direct loads would have produced.  Saves the LayerNorm kernel and its round trip through memory.
 // STATS: store_tiles also writes the LayerNorm statistics of the output (e.stats_out).
@@ -885,9 +910,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
     float4 xpre_b[XPREF ? NT : 1], xpre_r[XPREF ? MT * NT : 1];
     const bool xpre = XPREF && e.pre_epi != 0;
     {
-      // (16 rows: thread = (tile class tid / 16, row tid % 16), tiles class + 16 i: four loads per thread instead of sixteen)
-      constexpr int RL = MT == 1 ? 4 : 16;
-      const int tiles = p.K >> 4;                // <= 64
+      // (one partial per 64-column block; 16 rows: thread = (block tid / 16, row tid % 16): one load per thread)
+      constexpr int RL = MT == 1 ? 1 : 4;
+      const int tiles = p.K >> 6;                // 64-column blocks of the producer, <= 16
       int row = m0 + (MT == 1 ? (tid & 15) : lane); row = row < p.M ? row : p.M - 1;
       float2 pv[RL];
 #pragma unroll
@@ -985,14 +1010,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
       }
     }
   }
-  // row statistics: RL loads per thread.  16 rows: thread = (tile class tid / 16, row tid % 16), tiles class + 16 i;
-  // more rows: lane = row, tiles wave + 4 i
-  constexpr int RL = MT == 1 ? 4 : 16;
+  // row statistics (one partial per 64-column block): RL loads per thread.  16 rows: thread = (block tid / 16, row
+  // tid % 16); more rows: lane = row, blocks wave + 4 i
+  constexpr int RL = MT == 1 ? 1 : 4;
   float2 rpv[ROWAFF ? RL : 1];
   float4 ra_c4[NT], ra_d4[NT];
   if constexpr (ROWAFF) {                        // behind the first chunk's loads, in the shadow of their round trip
     int row = m0 + (MT == 1 ? (tid & 15) : lane); row = row < p.M ? row : p.M - 1;
-    const int tiles = p.K >> 4;                  // <= 64
+    const int tiles = p.K >> 6;                  // 64-column blocks of the producer, <= 16
 #pragma unroll
     for (int i = 0; i < RL; ++i) {
       const int t = MT == 1 ? (tid >> 4) + 16 * i : wave + 4 * i;
@@ -1010,7 +1035,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
     if (pre) { BPD_WAIT_VM(YOUNGER + NPRE); } else { BPD_WAIT_VM(YOUNGER); }
   }
   if constexpr (ROWAFF) {
-    const int tiles = p.K >> 4;
+    const int tiles = p.K >> 6;
     float sq = 0.f, qq = 0.f;
 #pragma unroll
     for (int i = 0; i < RL; ++i) {

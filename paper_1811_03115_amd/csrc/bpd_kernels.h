@@ -858,8 +858,8 @@ struct QProjP {
   const float* x;       // [M][d] residual stream
   const float* g;       // LayerNorm gain, bias
   const float* b;
-  const float* stats;   // partial statistics of x: [(tile * srows + row) * 2]
-  int srows;            // rows per tile in stats (16 on the single-tile path, M otherwise)
+  const float* stats;   // partial statistics of x: [(part * srows + row) * 2]
+  int srows;            // 16: single-tile path, one part per 16 columns; otherwise M rows, one part per 64 columns
   const void* W;        // packed [d/16 column tiles][d/32 k-steps][64 lanes][8]
   float eps;
 };
@@ -926,7 +926,9 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p, QProjP qp)
     float4 gb1 = gb0;
     if constexpr (J > 1) gb1 = ((const float4*)(i1 < NV4 / 2 ? qp.g : qp.b))[i1 < NV4 / 2 ? i1 : i1 - NV4 / 2];
     // statistics of this sequence's rows: element e = 16 * tile + local row
-    constexpr int NS2 = 128 * QU, JS = QU >= 2 ? QU / 2 : 1;
+    // (srows == 16: one partial per 16-column tile, 8 QU of them; otherwise per 64-column block, 2 QU)
+    constexpr int JS = QU >= 2 ? QU / 2 : 1;
+    const int nparts = qp.srows == 16 ? 8 * QU : 2 * QU, NS2 = 16 * nparts;
     const int row_first = b * p.R + r0;
 #define BPD_ST_SRC(e) ((const float2*)qp.stats)[(e) < NS2 ? ((e) >> 4) * qp.srows + row_first + (((e) & 15) < nrows ? ((e) & 15) : nrows - 1) : 0]
     const float2 s0 = BPD_ST_SRC(tid);
@@ -962,8 +964,9 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p, QProjP qp)
     float sm = 0.f, sq = 0.f;                    // row statistics: this lane adds partials lq, lq + 4, ...
 #pragma unroll
     for (int i = 0; i < 2 * QU; ++i) {
-      const float2 v = ((const float2*)st_s)[(lq + 4 * i) * 16 + lrc];
-      sm += v.x; sq += v.y;
+      const int part = lq + 4 * i;
+      const float2 v = ((const float2*)st_s)[(part < nparts ? part : 0) * 16 + lrc];
+      sm += part < nparts ? v.x : 0.f; sq += part < nparts ? v.y : 0.f;
     }
     sm += __shfl_xor(sm, 16, 64); sm += __shfl_xor(sm, 32, 64);
     sq += __shfl_xor(sq, 16, 64); sq += __shfl_xor(sq, 32, 64);
@@ -1364,7 +1367,8 @@ __global__ __launch_bounds__(64) void accept_kernel(StateP s, const unsigned lon
 // the sequence's k next rows (token i = new proposal i, position = new L + i) with their partial LayerNorm statistics,
 // exactly as embed_stats_kernel would at the start of the next step, and the sequence's k*k arg-max keys are cleared
 // for the next vocabulary projection.
-// stats: [(tile * srows + row) * 2] with srows = 16 (single-tile layout) or the number of rows B * k; xb (may be null):
+// stats: srows = 16: [(tile * 16 + row) * 2] per 16-column tile; otherwise srows = B * k rows and one entry per
+// 64-column block, [(block * srows + row) * 2]; xb (may be null):
 // bf16 copy of the rows as well.
 __global__ __launch_bounds__(1024) void accept_embed_kernel(StateP s, unsigned long long* keys, int k, int B, int step,
                                                             int* accepted_out, int d, const bf16_t* E, int V,
@@ -1435,9 +1439,13 @@ __global__ __launch_bounds__(1024) void accept_embed_kernel(StateP s, unsigned l
   const int position = L_s + ic;
   const int row = b * k + ic;
   const int ksteps = d >> 5, ntiles = d >> 4;
+  // srows == 16: statistics per 16-column tile (tiles wave, wave + 16, ..); otherwise per 64-column block: the wave's
+  // four tiles are block `wave` and their sums are added up here
+  const bool per_block = srows != 16;
+  float bs = 0.f, bq = 0.f;
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    const int tile = wave + 16 * q;
+    const int tile = per_block ? 4 * wave + q : wave + 16 * q;
     if (tile >= ntiles) break;                   // the same for the whole wave
     const int c0 = tile * 16 + (lane >> 4) * 4;
     const float4 pv = *(const float4*)(pos + (long)position * d + c0);
@@ -1451,12 +1459,14 @@ __global__ __launch_bounds__(1024) void accept_embed_kernel(StateP s, unsigned l
     float qv = (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
     sv += __shfl_xor(sv, 16, 64); sv += __shfl_xor(sv, 32, 64);
     qv += __shfl_xor(qv, 16, 64); qv += __shfl_xor(qv, 32, 64);
-    if (lane < 16 && i < k) ((float2*)stats)[(long)tile * srows + row] = make_float2(sv, qv);
+    bs += sv; bq += qv;
+    if (!per_block && lane < 16 && i < k) ((float2*)stats)[(long)tile * srows + row] = make_float2(sv, qv);
     if (i < k) {
       *(float4*)(x + (long)row * d + c0) = make_float4(v[0], v[1], v[2], v[3]);
       if (xb) *(uint2*)(xb + (long)row * d + c0) = make_uint2((unsigned)f2bf(v[0]) | ((unsigned)f2bf(v[1]) << 16), (unsigned)f2bf(v[2]) | ((unsigned)f2bf(v[3]) << 16));
     }
   }
+  if (per_block && 4 * wave < ntiles && lane < 16 && i < k) ((float2*)stats)[(long)wave * srows + row] = make_float2(bs, bq);
 }
 
 // ---------------------------------------------------------------------------------------
