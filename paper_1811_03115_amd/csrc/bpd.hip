@@ -381,7 +381,8 @@ void launch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* 
 constexpr int LDSX_LN_MT_MAX = 3;      // LayerNorm-fused consumers and statistics-writing producers: tiles of at most 48 rows
 constexpr int LDSX_LN_M_MAX = 128;     // and blocks of at most 128 rows
 constexpr long LDSX_MIN_WGS = 440;
-constexpr long LDSX_MIN_WGS_LONGK = 400;   // K >= 2048: a workgroup lives long enough that about 1.5 per CU suffice
+constexpr long LDSX_MIN_WGS_LONGK = 400;   // K >= 2048, fewer than 1024 rows: a workgroup lives long enough that about 1.5 per CU suffice
+                                           // (the encoder's 4096-row FFN output: 64-row tiles, 512 workgroups, beat 80-row tiles, 416: encode -2%)
 void pick_tile(int M, int N, int K, long zdim, int& mt, int& nt, int mt_max = 8) {
   const int mts[7] = {8, 7, 5, 4, 3, 2, 1};
   long best_area = 0, best_pad = 0;
@@ -392,7 +393,7 @@ void pick_tile(int M, int N, int K, long zdim, int& mt, int& nt, int mt_max = 8)
     for (int m : mts) {
       if ((n == 1 && m > 3) || m > mt_max) continue;
       const long bm = 16 * m, mblocks = (M + bm - 1) / bm, pad = mblocks * bm;
-      if (mblocks * cols * zdim < (K >= 2048 ? LDSX_MIN_WGS_LONGK : LDSX_MIN_WGS)) continue;
+      if (mblocks * cols * zdim < (K >= 2048 && M < 1024 ? LDSX_MIN_WGS_LONGK : LDSX_MIN_WGS)) continue;
       const long area = (long)m * n;                  // compared as area * M / pad: padded rows are wasted work
       if (best_area == 0 || area * best_pad > best_area * pad || (area * best_pad == best_area * pad && pad < best_pad)) {
         best_area = area; best_pad = pad; mt = m; nt = n;
