@@ -46,7 +46,15 @@ extern "C" {
 typedef struct bpd_ctx bpd_ctx;   /* opaque; owns small host structs only */
 
 /* Model and capacity description.  k_max counts all heads p_1..p_k (Section 3: p_1 is the
- * base model, p_2..p_k the proposal models; Section 6: p_1 passes through a head as well). */
+ * base model, p_2..p_k the proposal models; Section 6: p_1 passes through a head as well).
+ *
+ * Accepted shapes (anything else makes bpd_workspace_bytes return 0 and bpd_create BPD_E_ARG):
+ *   n_enc_layers, n_dec_layers, n_heads, max_batch, max_src_len, max_out_len >= 1;
+ *   1 <= k_max <= 16;
+ *   d_model a multiple of 32 and of n_heads, 32 <= d_model <= 2048;
+ *   head width d_model / n_heads = 16 or 64 (BPD_BF16), 16 only (BPD_F32: meant for small models);
+ *   d_ff a multiple of 32;  vocab a multiple of 16, >= 16;
+ *   dtype BPD_F32 or BPD_BF16;  eos_id < vocab;  ln_eps > 0. */
 typedef struct {
   int32_t n_enc_layers, n_dec_layers;
   int32_t d_model, n_heads, d_ff, vocab;
@@ -77,7 +85,8 @@ typedef struct {
   int32_t on_device;       /* 0: host memory, 1: device memory                              */
 } bpd_tensor;
 
-/* Counters since the last bpd_encode.  mean accepted block size (Section 7.1) =
+/* Counters since the last bpd_encode (they run on over several bpd_step / bpd_decode calls).
+ * mean accepted block size (Section 7.1) =
  * accepted_total / (steps summed over live sequences) = accepted_total / seq_steps.        */
 typedef struct {
   int64_t steps;           /* steps in which at least one sequence was still decoding       */
@@ -103,12 +112,18 @@ int bpd_create(const bpd_config* cfg, void* workspace, size_t workspace_bytes,
                void* hip_stream, bpd_ctx** out);
 int bpd_destroy(bpd_ctx* ctx);
 
-/* Copy n named tensors into the workspace, converting to the kernel layout (bf16 MFMA tiles
+/* The parameters of the combined model of Section 6 (Figure 3): the encoder-decoder Transformer
+ * that is p_1's body, and on top of its decoder output one inserted feed-forward layer per head
+ * with a residual connection, all heads sharing the vocabulary projection (the tensor names are
+ * listed at bpd_tensor).
+ * Copy n named tensors into the workspace, converting to the kernel layout (bf16 MFMA tiles
  * in BPD_BF16 mode).  The caller's buffers are not referenced after the call returns
  * (the call synchronises the stream).  May be called several times; every tensor must have
  * been loaded before bpd_encode, and a call made after bpd_encode ends the decode in progress
- * (bpd_step then returns BPD_E_STATE until the next bpd_encode).
- * Errors: BPD_E_WEIGHTS (unknown name / shape), BPD_E_ARG. */
+ * (bpd_step then returns BPD_E_STATE until the next bpd_encode).  All n tensors are validated
+ * (name, shape, dtype, staging capacity) before the first is copied: a call that fails leaves
+ * the loaded set as it was.
+ * Errors: BPD_E_WEIGHTS (unknown name / shape / dtype), BPD_E_CAPACITY, BPD_E_ARG. */
 int bpd_load_weights(bpd_ctx* ctx, const bpd_tensor* tensors, int n);
 
 /* Condition on a batch of sources (Section 2: the input x) and start decoding:
@@ -171,8 +186,11 @@ int bpd_set_two_phase(bpd_ctx* ctx, int on);
  * cross-attention are not affected.  Errors: BPD_E_ARG (null ctx, negative lengths). */
 int bpd_set_local_attention(bpd_ctx* ctx, int query_block, int memory_len);
 
-/* Repeat bpd_step until every sequence has ended (EOS accepted or max_len reached) or
- * max_steps steps were made; synchronises.
+/* The decoding loop of Section 3 with the merged verify / predict invocation of Section 4:
+ * repeat bpd_step until every sequence has ended or max_steps steps were made; synchronises.
+ * A sequence ends as greedy decoding does (Section 2): when the end-of-sequence token has been
+ * accepted, or at its length budget max_len (the only rule when eos_id < 0: a fixed number of
+ * tokens, as for the images of Section 7.2).
  *   schedule [host|device] int32 [max_steps, B] imposed accepted lengths, or NULL
  *   out_ids  [host|device] int32 [B, max_out_len], pad_id beyond out_len[b]
  *   out_len  [host|device] int32 [B]

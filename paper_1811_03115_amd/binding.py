@@ -82,9 +82,6 @@ def lib() -> C.CDLL:
         L.bpd_measure_mfma_bf16.argtypes = [vp, vp, C.c_int, C.POINTER(C.c_double)]
         L.bpd_last_error.restype = C.c_char_p
         L.bpd_last_error.argtypes = [vp]
-        for name in EXPORTS:
-            if getattr(L, name).restype is C.c_int:
-                pass
         _lib = L
     return _lib
 

@@ -46,7 +46,7 @@ struct Layout {
   void *selfK, *selfV, *crossK, *crossV;        // [n_dec][B][slots|max_src][d]
   // decoder activations (M = max_batch * k_max rows)
   float *x, *q, *h, *stats_ln, *stats_big, *zeros, *attn_part, *kpart; size_t n_zeros, n_kpart; void *xn, *attn, *ffh, *hn, *H, *O;
-  unsigned long long* keys; unsigned long long* keys_h1; unsigned long long* keys2; float* logits_h1; int* topn_ok;
+  unsigned long long* keys; unsigned long long* keys_h1; float* logits_h1; int* topn_ok;
   void* hn2; float* h2; int* sel;
   // encoder activations (max_batch * max_src rows)
   float *xe, *qe; void *xen, *ke, *ve, *attne, *ffhe, *mem;
@@ -121,8 +121,7 @@ size_t build_layout(const bpd_config& c, char* base, Layout& L) {
   L.xn = a.take(M * d * as); L.attn = a.take(M * d * as); L.ffh = a.take(M * F * as);
   L.hn = a.take(M * d * as); L.H = a.take(M * k * F * as); L.O = a.take(M * k * d * as);
   L.keys = (unsigned long long*)a.take(M * k * 8);
-  L.keys_h1 = (unsigned long long*)a.take(2 * M * 8);     // [M] keys of head 1, then [M] keys of the second phase
-  L.keys2 = L.keys_h1 + M;
+  L.keys_h1 = (unsigned long long*)a.take(2 * M * 8);     // keys of head 1 at the step's B*k rows, then the second phase's B*(k-1)
   L.hn2 = a.take(B * d * as); L.h2 = vec(B * d);
   L.logits_h1 = vec(M * V);
   const size_t Me = B * S;
@@ -179,6 +178,9 @@ struct bpd_ctx {
   std::vector<hipEvent_t> prof_ev;
   size_t prof_used = 0;
   int64_t prof_launches = 0;
+  // host / device classification of the pointers bpd_step was last given (a virtual address keeps its kind in the
+  // unified address space, so the runtime is asked once per distinct pointer, not once per step)
+  const void* kind_ptr[4] = {nullptr, nullptr, nullptr, nullptr}; bool kind_host[4] = {false, false, false, false}; int kind_next = 0;
   // a split-K residual update whose slices the next LayerNorm of `pend_x` still has to add
   int pend_slices = 0; const float* pend_bias = nullptr; const float* pend_x = nullptr;
 };
@@ -796,7 +798,8 @@ int heads_two_phase(bpd_ctx* ctx, int k) {
   layernorm(ctx, L.x, L.dec_lnf, M, L.hn, L.h);
   gemm(ctx, gp(L.hn, d, L.hw1, c.k_max * F, M, F, d), plain(L.hb1, 1, nullptr, 0, nullptr, 0, L.H, F));
   gemm(ctx, gp(L.H, F, L.hw2, d, M, d, F), plain(L.hb2, 0, L.h, d, nullptr, 0, L.O, d));
-  fill_i32(ctx, (int*)L.keys_h1, 4L * M, 0);          // keys_h1 and keys2 are neighbours in the workspace
+  unsigned long long* keys2 = L.keys_h1 + M;           // this step's second-phase keys follow its M head-1 keys: one fill clears both
+  fill_i32(ctx, (int*)L.keys_h1, 4L * M, 0);
   const bool topn = ctx->top_n > 1;
   vocab_argmax(ctx, gp(L.O, d, L.emb, c.vocab, M, c.vocab, d), L.keys_h1, topn ? L.logits_h1 : nullptr);
   if (topn)
@@ -818,9 +821,9 @@ int heads_two_phase(bpd_ctx* ctx, int k) {
     e.bias_g = d; e.r_g = 0; e.ya_g = d;
     gemm(ctx, p, e, kh);
   }
-  vocab_argmax(ctx, gp(L.O, d, L.emb, c.vocab, B * kh, c.vocab, d), L.keys2, nullptr);
+  vocab_argmax(ctx, gp(L.O, d, L.emb, c.vocab, B * kh, c.vocab, d), keys2, nullptr);
   hipLaunchKernelGGL(assemble_keys_kernel, dim3(B), dim3(256), 0, ctx->stream, (const unsigned long long*)L.keys_h1,
-                     (const unsigned long long*)L.keys2, (const int*)L.sel, k, L.keys);
+                     (const unsigned long long*)keys2, (const int*)L.sel, k, L.keys);
   LAUNCHCHK();
   if (ctx->pend_slices) return fail(ctx, BPD_E_STATE, "split-K slices were left unreduced");
   return BPD_OK;
@@ -1002,6 +1005,16 @@ bool is_host_ptr(const void* p) {
   return a.type != hipMemoryTypeDevice && a.type != hipMemoryTypeManaged;
 }
 
+// is_host_ptr with the answers for the last four distinct pointers remembered in the context
+bool is_host_ptr_cached(bpd_ctx* ctx, const void* p) {
+  for (int i = 0; i < 4; ++i)
+    if (ctx->kind_ptr[i] == p) return ctx->kind_host[i];
+  const bool h = is_host_ptr(p);
+  ctx->kind_ptr[ctx->kind_next] = p; ctx->kind_host[ctx->kind_next] = h;
+  ctx->kind_next = (ctx->kind_next + 1) & 3;
+  return h;
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------------------- C ABI
@@ -1070,6 +1083,10 @@ int bpd_load_weights(bpd_ctx* ctx, const bpd_tensor* tensors, int n) {
     bool ok = T.ndim == e.nd;
     for (int i = 0; ok && i < e.nd; ++i) ok = T.shape[i] == e.shape[i];
     if (!ok) return fail(ctx, BPD_E_WEIGHTS, std::string("wrong shape for ") + T.name);
+    size_t count = 1;
+    for (int i = 0; i < e.nd; ++i) count *= (size_t)e.shape[i];
+    if (!T.on_device && count * (T.dtype == BPD_F32 ? 4 : 2) > ctx->lay.staging_bytes)
+      return fail(ctx, BPD_E_CAPACITY, std::string("staging area too small for ") + T.name);
   }
   for (int t = 0; t < n; ++t) {
     const bpd_tensor& T = tensors[t];
@@ -1078,8 +1095,7 @@ int bpd_load_weights(bpd_ctx* ctx, const bpd_tensor* tensors, int n) {
     for (int i = 0; i < e.nd; ++i) count *= (size_t)e.shape[i];
     const size_t esz = T.dtype == BPD_F32 ? 4 : 2;
     const void* src = T.data;
-    if (!T.on_device) {
-      if (count * esz > ctx->lay.staging_bytes) return fail(ctx, BPD_E_CAPACITY, "staging area too small");
+    if (!T.on_device) {                          // (fits the staging area: checked above)
       HIPCHK(hipMemcpyAsync(ctx->lay.staging, T.data, count * esz, hipMemcpyHostToDevice, ctx->stream));
       src = ctx->lay.staging;
     }
@@ -1193,10 +1209,10 @@ static int step_impl(bpd_ctx* ctx, int k, const int* imposed_dev, int imposed_st
       const bool sp = stats_path(ctx, ctx->B * k);
       hipLaunchKernelGGL(accept_embed_kernel, dim3(ctx->B), dim3(1024), 0, ctx->stream, s, L.keys, k, ctx->B, imposed_step, accepted_dev,
                          c.d_model, (const bf16_t*)L.emb, c.vocab, (const float*)L.pos_tgt, sqrtf((float)c.d_model), L.x,
-                         sp ? L.stats_ln : L.stats_big, sp ? 16 : ctx->B * k, sp ? (bf16_t*)nullptr : (bf16_t*)L.xn);
+                         sp ? L.stats_ln : L.stats_big, sp ? 16 : ctx->B * k, sp ? (bf16_t*)nullptr : (bf16_t*)L.xn, (int)ctx->steps);
       ctx->x_ready_k = k;
     } else {
-      hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(64), 0, ctx->stream, s, L.keys, k, ctx->B, 1, imposed_step, accepted_dev);
+      hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(64), 0, ctx->stream, s, L.keys, k, ctx->B, 1, imposed_step, accepted_dev, (int)ctx->steps);
       ctx->x_ready_k = 0;
     }
   }
@@ -1213,14 +1229,14 @@ int bpd_step(bpd_ctx* ctx, int k, const int32_t* imposed_accept, int32_t* accept
   // device pointers are used in place by the accept kernel; host arrays go through a copy
   const int* imp = nullptr;
   if (imposed_accept) {
-    if (is_host_ptr(imposed_accept)) {
+    if (is_host_ptr_cached(ctx, imposed_accept)) {
       HIPCHK(hipMemcpyAsync(L.imposed1, imposed_accept, (size_t)ctx->B * 4, hipMemcpyHostToDevice, ctx->stream));
       imp = L.imposed1;
     } else {
       imp = imposed_accept;
     }
   }
-  const bool out_host = accepted_len && is_host_ptr(accepted_len);
+  const bool out_host = accepted_len && is_host_ptr_cached(ctx, accepted_len);
   int rc = step_impl(ctx, k, imp, 0, 0, out_host ? nullptr : accepted_len);
   if (rc) return rc;
   if (out_host) HIPCHK(hipMemcpyAsync(accepted_len, L.accepted, (size_t)ctx->B * 4, hipMemcpyDeviceToHost, ctx->stream));
@@ -1337,7 +1353,7 @@ int bpd_debug_step_logits(bpd_ctx* ctx, int k, float* logits) {
   if (k < 1 || k > ctx->cfg.k_max) return fail(ctx, BPD_E_ARG, "bpd_debug_step_logits: k outside 1..k_max");
   int rc = forward(ctx, k, k, 0, logits);
   if (rc) return rc;
-  hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(64), 0, ctx->stream, state_params(ctx), ctx->lay.keys, k, ctx->B, 0, 0, nullptr);
+  hipLaunchKernelGGL(accept_kernel, dim3(ctx->B), dim3(64), 0, ctx->stream, state_params(ctx), ctx->lay.keys, k, ctx->B, 0, 0, nullptr, 0);
   LAUNCHCHK();
   return BPD_OK;
 }

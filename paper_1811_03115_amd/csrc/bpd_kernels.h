@@ -1324,8 +1324,9 @@ __global__ __launch_bounds__(256) void assemble_keys_kernel(const unsigned long 
 //   value; then cut at the first EOS (inclusive) and at max_len; append; L += k-hat commits
 //   the cache rows of the accepted tokens (rejected rows are simply overwritten next step);
 //   P <- row k-hat of the table.
+//   step: row of the imposed schedule; live_step: steps made since the last bpd_encode (for the step counter).
 __global__ __launch_bounds__(64) void accept_kernel(StateP s, const unsigned long long* keys, int k, int B,
-                                                    int commit, int step, int* accepted_out) {
+                                                    int commit, int step, int* accepted_out, int live_step) {
   const int b = blockIdx.x, lane = threadIdx.x;
   if (b >= B) return;
   for (int e = lane; e < k * k; e += 64) {
@@ -1357,7 +1358,7 @@ __global__ __launch_bounds__(64) void accept_kernel(StateP s, const unsigned lon
     atomicAdd((unsigned long long*)&s.stats[1], (unsigned long long)khat);
     if (fin) atomicAdd((unsigned long long*)&s.stats[2], 1ull);
     atomicAdd((unsigned long long*)&s.stats[3 + khat], 1ull);
-    atomicMax((unsigned long long*)&s.stats[20], (unsigned long long)(step + 1));   // steps with a live sequence
+    atomicMax((unsigned long long*)&s.stats[20], (unsigned long long)(live_step + 1));   // steps with a live sequence
   }
 }
 
@@ -1373,7 +1374,7 @@ __global__ __launch_bounds__(64) void accept_kernel(StateP s, const unsigned lon
 __global__ __launch_bounds__(1024) void accept_embed_kernel(StateP s, unsigned long long* keys, int k, int B, int step,
                                                             int* accepted_out, int d, const bf16_t* E, int V,
                                                             const float* pos, float scale, float* x, float* stats,
-                                                            int srows, bf16_t* xb) {
+                                                            int srows, bf16_t* xb, int live_step) {
   __shared__ int tok_s[16];
   __shared__ int L_s;
   __shared__ int A_s[256];                       // the sequence's k x k arg-max table
@@ -1426,7 +1427,7 @@ __global__ __launch_bounds__(1024) void accept_embed_kernel(StateP s, unsigned l
         atomicAdd((unsigned long long*)&s.stats[1], (unsigned long long)khat);
         if (fin) atomicAdd((unsigned long long*)&s.stats[2], 1ull);
         atomicAdd((unsigned long long*)&s.stats[3 + khat], 1ull);
-        atomicMax((unsigned long long*)&s.stats[20], (unsigned long long)(step + 1));   // steps with a live sequence
+        atomicMax((unsigned long long*)&s.stats[20], (unsigned long long)(live_step + 1));   // steps with a live sequence
       }
     }
   }

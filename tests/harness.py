@@ -79,8 +79,16 @@ class LockStep:
         self.ctx.bpd_set_proposals(P)
         self.P_all = P
 
-    def step(self, imposed=None, check_logits=True):
-        """One step on both sides; returns the accepted lengths."""
+    def step(self, imposed=None, check_logits=True, two_phase=False, top_n=1):
+        """One step on both sides; returns the accepted lengths.
+
+        two_phase: the step runs with bpd_set_two_phase(True).  Where that mode is active (bf16, more than 16 block
+        rows, k > 1) the table holds head 1 of every row and row k-hat only: those entries are checked against the
+        oracle's logits and all the others must read -1.
+        top_n > 1: top-n verification (Section 5.1) with bpd_set_top_n(top_n).  Proposal P_{i+1} has to be accepted
+        where the oracle's p_1 logit of it at row i is at least 2*tol above the n-th best, and must not be where it is
+        more than 2*tol below; between the two either decision is correct at this precision.
+        """
         k, ctx, cfg = self.k, self.ctx, self.cfg
         zs = {}
         for b in self.sample:
@@ -92,36 +100,64 @@ class LockStep:
                 err = np.abs(lg[b] - z).max()
                 assert err <= self.tol, f"logits b={b}: max abs err {err} > {self.tol}"
                 self.max_logit_err = max(getattr(self, "max_logit_err", 0.0), float(err))
-        acc = np.zeros(self.B, dtype=np.int32)
         import torch
         acc_t = torch.zeros(self.B, dtype=torch.int32, device="cuda")
-        ctx.bpd_step(k, imposed, acc_t)
+        ctx.bpd_set_two_phase(two_phase)
+        ctx.bpd_set_top_n(top_n)
+        try:
+            ctx.bpd_step(k, imposed, acc_t)
+        finally:
+            ctx.bpd_set_two_phase(False)
+            ctx.bpd_set_top_n(1)
         acc = acc_t.cpu().numpy()
         P_gpu, A_gpu, j_gpu, fin_gpu = ctx.bpd_get_state()
         out_ids, out_len = ctx.bpd_get_output()
+        partial_table = two_phase and cfg.dtype == "bf16" and self.B * k > 16 and k > 1
         for b in self.sample:
             if self.done[b]:
                 assert acc[b] == 0 and fin_gpu[b] == 1
                 continue
             z = zs[b]
-            self.match.append(check_argmax(A_gpu[b, :k, :k], z, self.tol, f"A table b={b}"))
-            A = z.argmax(-1)
             P = [int(t) for t in self.P[b][:k]]
             j = len(self.prefix[b])
+            room = int(self.max_len[b]) - j
+
+            def cut(kv):
+                if cfg.eos_id >= 0 and cfg.eos_id in P[:kv]:
+                    kv = P.index(cfg.eos_id) + 1
+                return min(kv, room)
+
+            # head 1 of every row is always there: it is what verification reads
+            self.match.append(check_argmax(A_gpu[b, :k, 0], z[:, 0], self.tol, f"A column 1 b={b}"))
             if imposed is not None:
-                k_ver = int(np.clip(imposed[b], 1, k))
+                lo = hi = int(np.clip(imposed[b], 1, k))
+            elif top_n > 1:
+                nth = np.sort(z[:, 0], axis=-1)[:, -top_n]                       # n-th best logit of p_1 per row
+                zp = np.array([z[i - 1, 0, P[i]] for i in range(1, k)])         # p_1's logit of proposal i+1 at row i
+                must = zp >= nth[:k - 1] + 2 * self.tol
+                may = zp >= nth[:k - 1] - 2 * self.tol
+                lo = 1 + (int(np.argmin(must)) if not must.all() else k - 1)
+                hi = 1 + (int(np.argmin(may)) if not may.all() else k - 1)
             else:
                 # exact verification against the GPU's own head-1 choices where those are
                 # within tolerance, so that the integer decision is compared like with like
-                k_ver = 1
-                while k_ver < k and P[k_ver] == int(A_gpu[b, k_ver - 1, 0]):
-                    k_ver += 1
-            k_hat = k_ver
-            if cfg.eos_id >= 0 and cfg.eos_id in P[:k_hat]:
-                k_hat = P.index(cfg.eos_id) + 1
-            k_hat = min(k_hat, int(self.max_len[b]) - j)
+                lo = 1
+                while lo < k and P[lo] == int(A_gpu[b, lo - 1, 0]):
+                    lo += 1
+                hi = lo
+            assert cut(lo) <= acc[b] <= cut(hi), f"accepted length b={b}: gpu {acc[b]}, oracle {cut(lo)}..{cut(hi)}"
+            k_hat = int(acc[b])
+            assert k_hat >= 1
+            if partial_table:
+                self.match.append(check_argmax(A_gpu[b, k_hat - 1, :k], z[k_hat - 1], self.tol, f"A row k-hat b={b}"))
+                rest = np.ones((k, k), bool)
+                rest[:, 0] = False
+                rest[k_hat - 1, :] = False
+                assert (A_gpu[b, :k, :k][rest] == -1).all(), f"two-phase table b={b}: entries outside column 1 / row k-hat"
+            else:
+                self.match.append(check_argmax(A_gpu[b, :k, :k], z, self.tol, f"A table b={b}"))
+            A = z.argmax(-1)
             eos = cfg.eos_id >= 0 and cfg.eos_id in P[:k_hat]
-            assert acc[b] == k_hat, f"accepted length b={b}: gpu {acc[b]} oracle {k_hat}"
             self.prefix[b].extend(P[:k_hat])
             assert j_gpu[b] == len(self.prefix[b]) == out_len[b]
             assert out_ids[b, :out_len[b]].tolist() == self.prefix[b]

@@ -288,6 +288,68 @@ def test_two_phase_scoring_on_gpu(which):
     np.testing.assert_array_equal(ids0, ids1)
 
 
+@pytest.mark.parametrize("which,max_batch,k", [("M-bf16", None, None), ("M-bf16", 9, 4), ("odd-fold153", None, None),
+                                               ("odd-fold153", 20, 5)])
+def test_two_phase_scoring_against_oracle(which, max_batch, k):
+    """Two-phase scoring teacher-forced against the oracle: head 1 of every block row and all heads of row k-hat lie
+    within tolerance of the oracle's logits (Section 4 fixes what one invocation must yield: the verification of the
+    block and the next proposals), every other table entry is empty, accepted lengths / appended tokens / next
+    proposals follow.  Also with fewer sequences than max_batch and fewer heads than k_max (the second-phase keys then
+    do not start where a full-size step would put them)."""
+    cfg = {c.name: c for c in [MID_BF16] + ODD_SHAPES}[which]
+    weights = wl.make_weights(cfg)
+    ctx = gpu_context(cfg, weights, max_batch=max_batch)
+    src, n = ragged_sources(cfg, 8)
+    rng = np.random.default_rng(5)
+    sample = sorted(set([0, cfg.batch - 1] + rng.integers(0, cfg.batch, size=2).tolist()))
+    ls = LockStep(cfg, weights, ctx, src, n, np.full(cfg.batch, cfg.max_out, np.int32), k=k, sample=sample)
+    sched = wl.make_schedule(cfg, 2.5, 16, seed=6, k=ls.k)
+    for s in range(4):
+        ls.step(imposed=sched[s], two_phase=True, check_logits=(s == 0))
+    ls.step(imposed=None, two_phase=False, check_logits=False)          # modes may alternate between steps
+    for s in range(3):
+        ls.step(imposed=None, two_phase=True, check_logits=False)
+    ls.step(imposed=np.full(cfg.batch, ls.k, np.int32), two_phase=True, check_logits=False)
+
+
+def test_top_n_bf16_against_oracle():
+    """Top-n verification (Section 5.1) in bf16 over several row tiles, teacher-forced: every accepted proposal's
+    oracle logit under p_1 is within 2*tol of the oracle's n-th best at its row, and the first rejected one is not
+    more than 2*tol above it (LockStep.step states the rule); with and without two-phase scoring."""
+    cfg = MID_BF16
+    weights = wl.make_weights(cfg)
+    ctx = gpu_context(cfg, weights)
+    src, n = ragged_sources(cfg, 6)
+    ls = LockStep(cfg, weights, ctx, src, n, np.full(cfg.batch, cfg.max_out, np.int32), sample=[0, 2, 6])
+    lens = []
+    for top in (2, 50, 400, 50, 2):
+        lens.append(ls.step(top_n=top, check_logits=False).copy())
+        lens.append(ls.step(top_n=top, two_phase=True, check_logits=False).copy())
+    assert max(int(a.max()) for a in lens) > 1                          # some proposal beyond the first was accepted
+
+
+def test_step_counters_run_on_over_calls():
+    """steps / invocations count the steps made since bpd_encode, whether they came from bpd_step calls, from one
+    bpd_decode or from a decode resumed by a second call (Section 4: one invocation per step plus one)."""
+    cfg = SMALL_F32
+    weights = wl.make_weights(cfg, std=0.08)
+    ctx = gpu_context(cfg, weights)
+    src, n = ragged_sources(cfg, 4)
+    ones = np.ones(cfg.batch, np.int32)
+    ctx.bpd_encode(src, n)
+    for s in range(5):
+        ctx.bpd_step(cfg.k, ones)
+    st = ctx.bpd_get_stats()
+    assert st.steps == 5 and st.invocations == 6 and st.seq_steps == 5 * cfg.batch
+    sched = np.ones((cfg.max_out, cfg.batch), np.int32)
+    _, out_len, st = ctx.bpd_decode(cfg.k, schedule=sched, max_steps=3)     # resumed: three more steps
+    assert st.steps == 8 and st.invocations == 9 and (out_len == 8).all()
+    _, out_len, st = ctx.bpd_decode(cfg.k, schedule=sched)                  # to the end, one token per step
+    assert (out_len == cfg.max_out).all() and st.steps == cfg.max_out and st.invocations == cfg.max_out + 1
+    ctx.bpd_step(cfg.k, ones)                                               # nothing is alive: not a step
+    assert ctx.bpd_get_stats().steps == cfg.max_out
+
+
 def test_error_codes_on_gpu():
     from paper_1811_03115_amd import binding
     cfg = SMALL_F32

@@ -104,7 +104,8 @@ def test_c3_big_batch32_ragged():
     weights, ctx = big()
     src, n = wl.make_sources(cfg)
     max_len = wl.make_max_len(cfg, n)
-    sample = [0, 13, 31]
+    # the shortest and the longest source of the batch and one more, drawn with a seed
+    sample = sorted({int(np.argmin(n)), int(np.argmax(n)), int(np.random.default_rng(7).integers(cfg.batch))})
     ls = LockStep(cfg, weights, ctx, src, n, max_len, sample=sample)
     sched = wl.make_schedule(cfg, 3, cfg.max_out)
     for s in range(3):
@@ -210,6 +211,25 @@ def test_c3_two_phase_equals_full_table():
         np.testing.assert_array_equal(out, out_ref)
     finally:
         ctx.bpd_set_two_phase(False)
+
+
+def test_c3_two_phase_against_oracle():
+    """Batch 32 at full size with two-phase scoring, teacher-forced against the oracle on three sequences, among them
+    a one-token source and one of the maximum length (the lengths of sequences 0 and 31 are overwritten)."""
+    w, ctx = big()
+    cfg = wl.C3
+    src, n = wl.make_sources(cfg)
+    src, n = src.copy(), n.copy()
+    src[0, 1:] = cfg.pad_id
+    src[31] = np.resize(src[31, :n[31]], cfg.max_src)                   # its own tokens repeated up to the maximum length
+    n[0], n[31] = 1, cfg.max_src
+    ml = wl.make_max_len(cfg, n)
+    ls = LockStep(cfg, w, ctx, src, n, ml, sample=[0, 17, 31])
+    sched = wl.make_schedule(cfg, 3, cfg.max_out)
+    ls.step(imposed=sched[0], two_phase=True)
+    ls.step(imposed=sched[1], two_phase=True, check_logits=False)
+    ls.step(imposed=None, two_phase=True, check_logits=False)
+    print("C3 two-phase max logit err", ls.max_logit_err, "identical argmax fraction", np.mean(ls.match))
 
 
 def test_c2_top_n_and_profile_samples():
