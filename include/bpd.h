@@ -150,6 +150,18 @@ int bpd_encode(bpd_ctx* ctx, const int32_t* src_ids, const int32_t* src_len,
  * Errors: BPD_E_STATE (no bpd_encode yet), BPD_E_ARG. */
 int bpd_step(bpd_ctx* ctx, int k, const int32_t* imposed_accept, int32_t* accepted_len);
 
+/* bpd_step for callers that cannot allocate device memory and cannot spare workspace for a step's scratch: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results (the
+ * same kernels in the same order) and the same state transition as bpd_step; the scratch of the step (arg-max keys
+ * merged by atomic max, split-KV attention partials, split-K slices) lives in an 8 MiB array inside the library's
+ * device image instead of the workspace.  The call allocates nothing (no hipMalloc / hipFree, no allocating library
+ * routine) and clears what must start at zero with a fill kernel.  Every context on a GPU shares that GPU's array and
+ * it keeps the last call's contents: calls that overlap on one GPU (other streams, other threads) race.
+ * Errors: as bpd_step, and BPD_E_CAPACITY when the step's scratch exceeds the array (e.g. 64-wide heads: about
+ * 2.2 MB + 8 k^2 B bytes + the K slices of blocks of more than 16 rows; Transformer-big at batch 32, k = 10 needs
+ * 7.4 MB), with the byte counts in bpd_last_error(). */
+int bpd_step_static(bpd_ctx* ctx, int k, const int32_t* imposed_accept, int32_t* accepted_len);
+
 /* Relaxed verification (Section 5), applies to later bpd_step / bpd_decode calls with
  * imposed_accept == NULL:  a proposal is accepted if |P - argmax p_1| <= distance_eps
  * (Section 5.2; 0 = exact match) and at least min_block tokens are taken (Section 5.3;

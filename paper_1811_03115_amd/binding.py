@@ -41,7 +41,7 @@ class bpd_stats(C.Structure):
                 ("accepted_total", C.c_int64), ("hist", C.c_int64 * 17), ("finished", C.c_int32)]
 
 
-EXPORTS = ["bpd_workspace_bytes", "bpd_create", "bpd_destroy", "bpd_load_weights", "bpd_encode", "bpd_step",
+EXPORTS = ["bpd_workspace_bytes", "bpd_create", "bpd_destroy", "bpd_load_weights", "bpd_encode", "bpd_step", "bpd_step_static",
            "bpd_set_acceptance", "bpd_set_top_n", "bpd_set_two_phase", "bpd_set_local_attention", "bpd_decode", "bpd_get_state", "bpd_get_output", "bpd_get_stats",
            "bpd_set_proposals", "bpd_debug_step_logits", "bpd_profile_enable", "bpd_profile_read",
            "bpd_profile_samples", "bpd_measure_hbm_read", "bpd_measure_mfma_bf16", "bpd_last_error"]
@@ -65,6 +65,7 @@ def lib() -> C.CDLL:
         L.bpd_load_weights.argtypes = [vp, C.POINTER(bpd_tensor), C.c_int]
         L.bpd_encode.argtypes = [vp, i32p, i32p, i32p, C.c_int, C.c_int]
         L.bpd_step.argtypes = [vp, C.c_int, i32p, i32p]
+        L.bpd_step_static.argtypes = [vp, C.c_int, i32p, i32p]
         L.bpd_set_acceptance.argtypes = [vp, C.c_int, C.c_int]
         L.bpd_set_top_n.argtypes = [vp, C.c_int]
         L.bpd_set_two_phase.argtypes = [vp, C.c_int]
@@ -198,6 +199,10 @@ class Context:
     def bpd_step(self, k: int, imposed_accept=None, accepted_len=None):
         imposed_accept = _i32(imposed_accept)
         self._check(self.L.bpd_step(self.h, k, _ptr(imposed_accept), _ptr(accepted_len)))
+
+    def bpd_step_static(self, k: int, imposed_accept=None, accepted_len=None):
+        imposed_accept = _i32(imposed_accept)
+        self._check(self.L.bpd_step_static(self.h, k, _ptr(imposed_accept), _ptr(accepted_len)))
 
     def bpd_set_acceptance(self, distance_eps: int = 0, min_block: int = 1):
         self._check(self.L.bpd_set_acceptance(self.h, distance_eps, min_block))

@@ -14,9 +14,22 @@
 namespace {
 
 constexpr size_t ALIGN = 256;
+
+// Scratch of bpd_step_static: the device memory of a step that is neither input nor output nor decode state (arg-max
+// keys that the vocabulary projection merges with atomic max, split-KV attention partials, split-K slices), for callers
+// that may not allocate and hand over no workspace for it.  One copy per GPU, held until the process ends; every call
+// on a GPU shares it, so calls that overlap on one GPU race.  In host code `scratch` is only a handle: the address on
+// the current device comes from hipGetSymbolAddress (bpd_create keeps it per device).
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)8 << 20;
+constexpr int MAX_DEVICES = 64;
 constexpr int KSPLIT_MAX = 16;          // K slices of a split-K GEMM
 constexpr int ATTN_LIMF_MIN_WGS = 256;  // attention launches of at least this many workgroups clamp their K/V loads to the length
 constexpr int ATTN_PART_SLOTS = 512;   // workgroups of one split attention launch (partial-result slots)
+
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+namespace {
+void* g_scratch_ptr[MAX_DEVICES] = {};     // address of `scratch` on each device that has created a context
 
 struct Arena {
   char* base;
@@ -170,6 +183,7 @@ struct bpd_ctx {
   int distance_eps = 0, min_block = 1, top_n = 1, two_phase = 0;
   int local_q = 0, local_m = 0;   // 1D local self-attention in the decoder (0: full causal), bpd_set_local_attention
   int num_cus = 256;                   // compute units of the device the context was created on
+  int device = 0;                      // that device's index
   int x_ready_k = 0;                   // > 0: the last step's accept kernel already embedded the next block of that many rows
   bool weights_exceed_llc = false;     // decoder-side weights read per step > 192 MB (the Infinity Cache holds 256 MB)
   const int* cur_imposed = nullptr; int cur_imposed_stride = 0, cur_imposed_step = 0;   // of the step being run
@@ -1038,8 +1052,14 @@ int bpd_create(const bpd_config* cfg, void* workspace, size_t workspace_bytes, v
   ctx->stream = (hipStream_t)hip_stream;
   {
     int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
-      ctx->num_cus = cus;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) { delete ctx; return BPD_E_HIP; }
+    ctx->device = dev;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0) ctx->num_cus = cus;
+    if (!g_scratch_ptr[dev]) {               // once per device, with that device current
+      void* sp = nullptr;
+      if (hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch)) != hipSuccess || !sp) { (void)hipGetLastError(); delete ctx; return BPD_E_HIP; }
+      g_scratch_ptr[dev] = sp;
+    }
   }
   build_layout(*cfg, (char*)workspace, ctx->lay);
   build_table(ctx);
@@ -1238,6 +1258,60 @@ int bpd_step(bpd_ctx* ctx, int k, const int32_t* imposed_accept, int32_t* accept
   }
   const bool out_host = accepted_len && is_host_ptr_cached(ctx, accepted_len);
   int rc = step_impl(ctx, k, imp, 0, 0, out_host ? nullptr : accepted_len);
+  if (rc) return rc;
+  if (out_host) HIPCHK(hipMemcpyAsync(accepted_len, L.accepted, (size_t)ctx->B * 4, hipMemcpyDeviceToHost, ctx->stream));
+  return BPD_OK;
+}
+
+int bpd_step_static(bpd_ctx* ctx, int k, const int32_t* imposed_accept, int32_t* accepted_len) {
+  if (!ctx) return BPD_E_ARG;
+  if (!ctx->encoded) return fail(ctx, BPD_E_STATE, "bpd_step_static: call bpd_encode first");
+  if (k < 1 || k > ctx->cfg.k_max) return fail(ctx, BPD_E_ARG, "bpd_step_static: k outside 1..k_max");
+  Layout& L = ctx->lay;
+  const bpd_config& c = ctx->cfg;
+  char* sp = (char*)g_scratch_ptr[ctx->device];
+  if (!sp) return fail(ctx, BPD_E_STATE, "bpd_step_static: no scratch address for this device");
+  // what this step needs: its k x k keys per sequence, the head-1 / second-phase keys, the attention partials, and as
+  // many K slices as bpd_step would use for the same block (so that both sum in the same order)
+  const size_t M = (size_t)ctx->B * k, d = c.d_model;
+  auto up = [](size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; };
+  const size_t keys_b = up(M * k * 8), keys_h1_b = up(2 * M * 8);
+  const size_t attn_b = up((size_t)ATTN_PART_SLOTS * 16 * (d / c.n_heads + 2) * 4);
+  size_t slices = 1;
+  if (c.dtype == BPD_BF16 && M > 16)
+    for (int K : {c.d_model, c.d_ff}) {
+      const int ns = residual_k_slices(ctx, gp(nullptr, K, nullptr, c.d_model, (int)M, c.d_model, K));
+      if ((size_t)ns > slices) slices = ns;
+    }
+  const size_t kpart_b = slices > 1 ? up(slices * M * d * 4) : 0;
+  if (keys_b + keys_h1_b + attn_b + kpart_b > STATIC_SCRATCH_BYTES)
+    return fail(ctx, BPD_E_CAPACITY, "bpd_step_static: this step needs " + std::to_string(keys_b + keys_h1_b + attn_b + kpart_b) +
+                                     " bytes of scratch, the static array holds " + std::to_string(STATIC_SCRATCH_BYTES));
+  const int* imp = nullptr;
+  if (imposed_accept) {
+    if (is_host_ptr_cached(ctx, imposed_accept)) {
+      HIPCHK(hipMemcpyAsync(L.imposed1, imposed_accept, (size_t)ctx->B * 4, hipMemcpyHostToDevice, ctx->stream));
+      imp = L.imposed1;
+    } else {
+      imp = imposed_accept;
+    }
+  }
+  const bool out_host = accepted_len && is_host_ptr_cached(ctx, accepted_len);
+  // the step's kernels take their scratch from the layout: point it at the static array for this call
+  unsigned long long* const keys0 = L.keys; unsigned long long* const keys_h10 = L.keys_h1;
+  float* const attn0 = L.attn_part; float* const kpart0 = L.kpart;
+  L.keys = (unsigned long long*)sp;
+  L.keys_h1 = (unsigned long long*)(sp + keys_b);
+  L.attn_part = (float*)(sp + keys_b + keys_h1_b);
+  L.kpart = (float*)(sp + keys_b + keys_h1_b + attn_b);
+  // the array keeps the last call's contents and the keys are merged with atomic max: they start at zero
+  // (a fill kernel, not a memset node: callers may be capturing the stream)
+  fill_i32(ctx, (int*)L.keys, (long)(2 * M * k), 0);
+  int rc = step_impl(ctx, k, imp, 0, 0, out_host ? nullptr : accepted_len);
+  L.keys = keys0; L.keys_h1 = keys_h10; L.attn_part = attn0; L.kpart = kpart0;
+  // (this step's accept kernel cleared the static keys, not the workspace's: the next step embeds its block and clears
+  // its keys itself)
+  ctx->x_ready_k = 0;
   if (rc) return rc;
   if (out_host) HIPCHK(hipMemcpyAsync(accepted_len, L.accepted, (size_t)ctx->B * 4, hipMemcpyDeviceToHost, ctx->stream));
   return BPD_OK;
