@@ -3,9 +3,11 @@
 // bpd_kernels.h; this file only orders them on the caller's stream.
 #include "../../include/bpd.h"
 #include "bpd_kernels.h"
+#include "bpd_stack.h"
 
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <string>
@@ -61,6 +63,9 @@ struct Layout {
   float *x, *q, *h, *stats_ln, *stats_big, *zeros, *attn_part, *kpart; size_t n_zeros, n_kpart; void *xn, *attn, *ffh, *hn, *H, *O;
   unsigned long long* keys; unsigned long long* keys_h1; float* logits_h1; int* topn_ok;
   void* hn2; float* h2; int* sel;
+  // decoder stack kernel (blocks of at most 16 rows): exchange buffers, flags, error word, probe output
+  unsigned char* stack_ex = nullptr; unsigned* stack_flags = nullptr; unsigned* stack_err = nullptr; unsigned* xcc_map = nullptr;
+  unsigned long long* stack_trace = nullptr; StackLayerP* stack_layers = nullptr;
   // encoder activations (max_batch * max_src rows)
   float *xe, *qe; void *xen, *ke, *ve, *attne, *ffhe, *mem;
   // state
@@ -92,6 +97,14 @@ bool config_ok(const bpd_config& c) {
 bool fold_kept(const bpd_config& c) {
   return c.dtype == BPD_BF16 && (long)c.max_batch * c.k_max > 128 && c.d_model % 64 == 0 && c.d_model <= 1024;
 }
+
+// Shapes the decoder stack kernel is built for (what a step additionally needs is checked per launch)
+bool stack_shape_ok(const bpd_config& c) {
+  const int d = c.d_model;
+  return c.dtype == BPD_BF16 && d == 64 * c.n_heads && (d == 128 || d == 256 || d == 512 || d == 768 || d == 1024) &&
+         c.d_ff % 128 == 0 && c.n_dec_layers <= STACK_MAX_LAYERS;
+}
+constexpr int XCC_MAP_MAX = 1024;          // compute units the placement probe can record
 
 size_t build_layout(const bpd_config& c, char* base, Layout& L) {
   Arena a(base);
@@ -148,6 +161,14 @@ size_t build_layout(const bpd_config& c, char* base, Layout& L) {
   L.out_ids = ints(B * (size_t)c.max_out_len); L.step_counter = ints(1); L.imposed1 = ints(B);
   L.sched = ints(B * (size_t)c.max_out_len);
   L.stats = (long long*)a.take(32 * 8);
+  L.xcc_map = (unsigned*)a.take(XCC_MAP_MAX * 4);
+  L.stack_err = (unsigned*)a.take(256);
+  if (stack_shape_ok(c)) {
+    L.stack_ex = (unsigned char*)a.take((size_t)c.n_dec_layers * stack_ex(c.d_model, c.d_ff).total);
+    L.stack_flags = (unsigned*)a.take((size_t)c.n_dec_layers * STACK_OPS * STACK_FLAG_STRIDE * 4);
+    L.stack_trace = (unsigned long long*)a.take((size_t)STACK_FLAG_STRIDE * c.n_dec_layers * STACK_OPS * 8 * 8);
+    L.stack_layers = (StackLayerP*)a.take(sizeof(StackLayerP) * STACK_MAX_LAYERS);
+  }
   size_t biggest = V * d;                    // largest tensor a bpd_load_weights call may stage (elements)
   if (k * d * F > biggest) biggest = k * d * F;
   if (slots * d > biggest) biggest = slots * d;
@@ -184,6 +205,11 @@ struct bpd_ctx {
   int local_q = 0, local_m = 0;   // 1D local self-attention in the decoder (0: full causal), bpd_set_local_attention
   int num_cus = 256;                   // compute units of the device the context was created on
   int device = 0;                      // that device's index
+  // decoder stack kernel: placement of workgroups on XCDs as probed at creation (workers = 0: not usable), the value
+  // its flags take next, and whether a launch has reported a timeout (then the per-operator kernels take over)
+  int stack_xcc = 0, stack_nx = 0, stack_workers = 0;
+  unsigned stack_epoch = 0;
+  bool stack_off = false;
   int x_ready_k = 0;                   // > 0: the last step's accept kernel already embedded the next block of that many rows
   bool weights_exceed_llc = false;     // decoder-side weights read per step > 192 MB (the Infinity Cache holds 256 MB)
   const int* cur_imposed = nullptr; int cur_imposed_stride = 0, cur_imposed_step = 0;   // of the step being run
@@ -774,6 +800,71 @@ void fill_i32(bpd_ctx* ctx, int* p, long n, int v) {
   hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, p, n, v);
 }
 
+// ------------------------------------------------------------------------------- decoder stack kernel
+// The decoder layers of a block of at most 16 rows as one kernel on one XCD (bpd_stack.h).  Usable when the workgroup
+// placement probe of bpd_create found the regular round-robin, the model has a shape the kernel is built for, both
+// attentions run unsplit (short caches), and the largest operator's LDS fits.
+StackShape stack_shape_of(const bpd_ctx* ctx, int B, int R) {
+  const bpd_config& c = ctx->cfg;
+  StackShape s;
+  s.n_layers = c.n_dec_layers; s.d = c.d_model; s.F = c.d_ff; s.heads = c.n_heads; s.B = B; s.M = B * R;
+  s.workers = ctx->stack_workers; s.KU = c.d_model / 128;
+  return s;
+}
+int stack_lds_bytes(const bpd_ctx* ctx, int B, int R) { return stack_lds_need(stack_shape_of(ctx, B, R), (int)AttnLds::BYTES); }
+bool stack_usable(const bpd_ctx* ctx, int B, int R) {
+  const bpd_config& c = ctx->cfg;
+  const int M = B * R;
+  return ctx->stack_workers > 0 && !ctx->stack_off && ctx->lay.stack_ex != nullptr && M >= 1 && M <= 16 && ctx->local_q == 0 &&
+         attention_nsplit(ctx, c.max_out_len + c.k_max + 1, B, R, 1) == 1 && attention_nsplit(ctx, c.max_src_len, B, R, 0) == 1 &&
+         stack_lds_bytes(ctx, B, R) <= 160 * 1024 &&
+         (std::max(3 * c.d_model, c.d_ff) / 16 + ctx->stack_workers - 1) / ctx->stack_workers <= 8;     // tiles a helper wave finishes: two
+}
+template <int KU>
+void launch_stack_ku(bpd_ctx* ctx, const StackP& p) {
+  auto k = decoder_stack_kernel<KU>;
+  static int attr = 0;                            // per instantiation: allow more than 64 KiB of LDS
+  if (attr < p.lds_bytes) { (void)hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, p.lds_bytes); attr = p.lds_bytes; }
+  hipLaunchKernelGGL(k, dim3(p.nx * p.workers), dim3(512), p.lds_bytes, ctx->stream, p);
+}
+void launch_stack(bpd_ctx* ctx, int R) {
+  const bpd_config& c = ctx->cfg;
+  Layout& L = ctx->lay;
+  const int d = c.d_model, slots = c.max_out_len + c.k_max + 1;
+  StackP p{};
+  p.L = L.stack_layers;
+  p.n_layers = c.n_dec_layers; p.d = d; p.F = c.d_ff; p.heads = c.n_heads; p.B = ctx->B; p.R = R; p.M = ctx->B * R;
+  p.slots = slots; p.max_src = c.max_src_len;
+  p.Lbase = L.L; p.src_len = L.src_len; p.x_in = L.x; p.x_out = L.x; p.stats_out = L.stats_ln;
+  p.ex = L.stack_ex; p.flags = L.stack_flags; p.err = L.stack_err;
+  if (++ctx->stack_epoch == 0) ctx->stack_epoch = 1;
+  p.epoch = ctx->stack_epoch;
+  p.spin_limit = 1 << 21;
+  p.xcc = ctx->stack_xcc; p.nx = ctx->stack_nx; p.workers = ctx->stack_workers;
+  p.eps = c.ln_eps; p.scale = 1.0f / sqrtf(64.f);
+  p.lds_bytes = stack_lds_bytes(ctx, ctx->B, R);
+  p.trace = getenv("BPD_STACK_TRACE") ? L.stack_trace : nullptr;
+  switch (d / 128) {
+    case 1: launch_stack_ku<1>(ctx, p); break;
+    case 2: launch_stack_ku<2>(ctx, p); break;
+    case 4: launch_stack_ku<4>(ctx, p); break;
+    case 6: launch_stack_ku<6>(ctx, p); break;
+    default: launch_stack_ku<8>(ctx, p); break;
+  }
+}
+// After a synchronisation: has a stack launch reported a wait that ran out?  Then the per-operator kernels take over
+// for the rest of the context's life and the caller learns that results since the last check cannot be trusted.
+int stack_check(bpd_ctx* ctx) {
+  if (ctx->stack_workers == 0 || ctx->stack_off || ctx->stack_epoch == 0) return BPD_OK;
+  unsigned e = 0;
+  HIPCHK(hipMemcpy(&e, ctx->lay.stack_err, 4, hipMemcpyDeviceToHost));
+  if (e == 0) return BPD_OK;
+  ctx->stack_off = true;
+  HIPCHK(hipMemsetAsync(ctx->lay.stack_err, 0, 4, ctx->stream));
+  return fail(ctx, BPD_E_HIP, "decoder stack kernel: a bounded wait ran out (code " + std::to_string(e) +
+                              "); the results of this decode are invalid, later steps use the per-operator kernels");
+}
+
 // ------------------------------------------------------------------------------- profiling
 
 hipEvent_t prof_event(bpd_ctx* ctx) {
@@ -890,7 +981,9 @@ int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
     ctx->x_ready_k = 0;
     xs = have_x && !sp;
     if (!have_x) embed(ctx, L.P, c.k_max, L.L, R, M, L.pos_tgt, L.x, zero_input, L.keys, (int)nk);
-    for (int l = 0; l < c.n_dec_layers; ++l) {
+    const bool stack = sp && stack_usable(ctx, B, R);
+    if (stack) launch_stack(ctx, R);
+    for (int l = 0; l < (stack ? 0 : c.n_dec_layers); ++l) {
       DecL& w = L.dec[l];
       char* Kl = (char*)L.selfK + (size_t)l * c.max_batch * slots * d * as;
       char* Vl = (char*)L.selfV + (size_t)l * c.max_batch * slots * d * as;
@@ -1068,6 +1161,44 @@ int bpd_create(const bpd_config* cfg, void* workspace, size_t workspace_bytes, v
     const size_t step_weights = ((size_t)cfg->n_dec_layers * (6 * d * d + 2 * d * F) + 2 * k * d * F + V * d) * act_size(*cfg);
     ctx->weights_exceed_llc = step_weights > ((size_t)192 << 20);
   }
+  (void)hipMemsetAsync(ctx->lay.stack_err, 0, 256, ctx->stream);
+  if (ctx->lay.stack_ex && ctx->num_cus <= XCC_MAP_MAX) {
+    // placement probe: which XCD does workgroup i of a one-workgroup-per-CU grid land on?  The stack kernel needs the
+    // regular round-robin (workgroup i on XCD i mod nx, every XCD equally often) and at most 64 workers per XCD.
+    const char* env = getenv("BPD_DECODER_STACK");
+    std::vector<StackLayerP> table(STACK_MAX_LAYERS);        // the layers' weights and caches: fixed addresses in the workspace
+    {
+      const bpd_config& c = *cfg;
+      Layout& L = ctx->lay;
+      const size_t d = c.d_model, slots = (size_t)c.max_out_len + c.k_max + 1, as = 2;
+      for (int l = 0; l < c.n_dec_layers; ++l) {
+        const DecL& w = L.dec[l];
+        StackLayerP& q = table[l];
+        q.wqkv = w.wqkv; q.wo = w.wo; q.cq = w.cq; q.co = w.co; q.w1 = w.w1; q.w2 = w.w2;
+        q.ln1g = w.ln1.g; q.ln1b = w.ln1.b; q.ln2g = w.ln2.g; q.ln2b = w.ln2.b; q.ln3g = w.ln3.g; q.ln3b = w.ln3.b;
+        q.b1 = w.b1; q.b2 = w.b2;
+        q.selfK = (char*)L.selfK + (size_t)l * c.max_batch * slots * d * as;
+        q.selfV = (char*)L.selfV + (size_t)l * c.max_batch * slots * d * as;
+        q.crossK = (char*)L.crossK + (size_t)l * c.max_batch * c.max_src_len * d * as;
+        q.crossV = (char*)L.crossV + (size_t)l * c.max_batch * c.max_src_len * d * as;
+      }
+      (void)hipMemcpyAsync(ctx->lay.stack_layers, table.data(), sizeof(StackLayerP) * STACK_MAX_LAYERS, hipMemcpyHostToDevice, ctx->stream);
+    }
+    (void)hipMemsetAsync(ctx->lay.stack_flags, 0, (size_t)cfg->n_dec_layers * STACK_OPS * STACK_FLAG_STRIDE * 4, ctx->stream);
+    hipLaunchKernelGGL(xcc_map_kernel, dim3(ctx->num_cus), dim3(64), 0, ctx->stream, ctx->lay.xcc_map);
+    std::vector<unsigned> map(ctx->num_cus);
+    if (hipMemcpyAsync(map.data(), ctx->lay.xcc_map, map.size() * 4, hipMemcpyDeviceToHost, ctx->stream) == hipSuccess &&
+        hipStreamSynchronize(ctx->stream) == hipSuccess && env && env[0] == '1') {      // opt-in: slower than the kernel chain so far
+      int nx = 1;
+      while (nx < ctx->num_cus && map[nx] != map[0]) ++nx;
+      bool ok = ctx->num_cus % nx == 0 && ctx->num_cus / nx <= STACK_FLAG_STRIDE;
+      for (int i = 0; ok && i < ctx->num_cus; ++i) ok = map[i] == map[i % nx];
+      for (int i = 0; ok && i < nx; ++i)
+        for (int j = 0; ok && j < i; ++j) ok = map[i] != map[j];
+      if (ok) { ctx->stack_nx = nx; ctx->stack_xcc = (int)map[0]; ctx->stack_workers = ctx->num_cus / nx; }
+    }
+    (void)hipGetLastError();
+  }
   (void)hipMemsetAsync(ctx->lay.zeros, 0, ctx->lay.n_zeros * 4, ctx->stream);
   (void)hipMemsetAsync(ctx->lay.stats_ln, 0, 64 * 16 * 2 * 4, ctx->stream);
   if (hipHostMalloc((void**)&ctx->pinned, 64 * sizeof(int), hipHostMallocDefault) != hipSuccess) {
@@ -1081,6 +1212,14 @@ int bpd_create(const bpd_config* cfg, void* workspace, size_t workspace_bytes, v
 int bpd_destroy(bpd_ctx* ctx) {
   if (!ctx) return BPD_E_ARG;
   (void)hipStreamSynchronize(ctx->stream);
+  if (const char* path = getenv("BPD_STACK_TRACE")) {      // debugging aid: the last stack launch's timestamps, raw
+    if (ctx->lay.stack_trace && ctx->stack_workers > 0) {
+      const size_t n = (size_t)ctx->stack_workers * ctx->cfg.n_dec_layers * STACK_OPS * 8;
+      std::vector<unsigned long long> t(n);
+      if (hipMemcpy(t.data(), ctx->lay.stack_trace, n * 8, hipMemcpyDeviceToHost) == hipSuccess)
+        if (FILE* f = fopen(path, "wb")) { fwrite(t.data(), 8, n, f); fclose(f); }
+    }
+  }
   for (auto e : ctx->prof_ev) (void)hipEventDestroy(e);
   if (ctx->pinned) (void)hipHostFree(ctx->pinned);
   delete ctx;
@@ -1363,7 +1502,7 @@ int bpd_get_output(bpd_ctx* ctx, int32_t* out_ids, int32_t* out_len) {
   if (out_ids) HIPCHK(hipMemcpyAsync(out_ids, L.out_ids, (size_t)ctx->B * ctx->cfg.max_out_len * 4, hipMemcpyDefault, ctx->stream));
   if (out_len) HIPCHK(hipMemcpyAsync(out_len, L.j, (size_t)ctx->B * 4, hipMemcpyDefault, ctx->stream));
   HIPCHK(hipStreamSynchronize(ctx->stream));
-  return BPD_OK;
+  return stack_check(ctx);
 }
 
 int bpd_decode(bpd_ctx* ctx, int k, const int32_t* schedule, int max_steps, int32_t* out_ids, int32_t* out_len, bpd_stats* stats) {
@@ -1405,7 +1544,7 @@ int bpd_get_state(bpd_ctx* ctx, int32_t* P, int32_t* A, int32_t* j, int32_t* fin
   if (j) HIPCHK(hipMemcpyAsync(j, L.j, B * 4, hipMemcpyDefault, ctx->stream));
   if (finished) HIPCHK(hipMemcpyAsync(finished, L.finished, B * 4, hipMemcpyDefault, ctx->stream));
   HIPCHK(hipStreamSynchronize(ctx->stream));
-  return BPD_OK;
+  return stack_check(ctx);
 }
 
 int bpd_set_proposals(bpd_ctx* ctx, const int32_t* P) {

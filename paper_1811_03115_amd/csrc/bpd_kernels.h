@@ -863,17 +863,44 @@ struct QProjP {
   const void* W;        // packed [d/16 column tiles][d/32 k-steps][64 lanes][8]
   float eps;
 };
+// LDS of one attention workgroup (4 waves): the kernel below declares it; a caller that runs the body from inside
+// another kernel carves it out of its own LDS.
+struct AttnLds {
+  static constexpr int RT = 16, DH = 64, WK = 64, VLD = DH + 4;
+  bf16_t (*vs)[WK][VLD];      // [4][WK][VLD] per wave: its 64 V rows of the chunk
+  f32x4 (*o_s)[4][64];        // [4][4][64]   per wave and output tile: un-normalised out^T
+  float (*m_s)[RT];           // [4][RT]      per wave: running maximum per query row
+  float (*l_s)[RT];           // [4][RT]      ... and sum
+  float* q_s;                 // QU > 0: [RT * (DH + 4)] projected queries
+  static constexpr size_t VS_BYTES = (size_t)4 * WK * VLD * 2, OS_BYTES = (size_t)4 * 4 * 64 * 16, ML_BYTES = (size_t)4 * RT * 4;
+  static constexpr size_t BYTES = VS_BYTES + OS_BYTES + 2 * ML_BYTES;        // without q_s
+  // carve (16-byte aligned base), QU == 0 layout
+  __device__ static AttnLds carve(unsigned char* base) {
+    AttnLds s;
+    s.vs = (bf16_t (*)[WK][VLD])base;
+    s.o_s = (f32x4 (*)[4][64])(base + VS_BYTES);
+    s.m_s = (float (*)[RT])(base + VS_BYTES + OS_BYTES);
+    s.l_s = (float (*)[RT])(base + VS_BYTES + OS_BYTES + ML_BYTES);
+    s.q_s = nullptr;
+    return s;
+  }
+};
+// One (head h, sequence b, z = row tile * nsplit + split) item of the attention, run by 256 threads (tid 0..255, four
+// whole waves) that share `sm`; nheads / nz: the extents the partial-result layout is indexed with.  Every
+// __syncthreads() inside is reached by all 256 threads; a caller whose workgroup has more waves makes those arrive at
+// as many barriers (one with QU == 0, three with QU > 0).
 template <bool KVNT, bool LIMF, int QU>
-__global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p, QProjP qp) {
+__device__ __forceinline__ void attention_mfma_body(const AttnP& p, const QProjP& qp, const AttnLds& sm, int h, int b, int z,
+                                                    int nheads, int nz, int tid) {
   constexpr int RT = 16, CH = 256, DH = 64, WK = 64, VLD = DH + 4;
-  __shared__ __attribute__((aligned(16))) bf16_t vs[4][WK][VLD];     // per wave: its 64 V rows of the chunk
-  __shared__ f32x4 o_s[4][4][64];                                    // per wave and output tile: un-normalised out^T
-  __shared__ float m_s[4][RT], l_s[4][RT];                           // per wave: running maximum and sum per query row
-  __shared__ __attribute__((aligned(16))) float q_s[QU > 0 ? RT * (DH + 4) : 4];   // projected queries
-  const int h = blockIdx.x, b = blockIdx.y;
-  const int split = blockIdx.z % p.nsplit, tile = blockIdx.z / p.nsplit, r0 = tile * RT;
+  bf16_t (*vs)[WK][VLD] = sm.vs;
+  f32x4 (*o_s)[4][64] = sm.o_s;
+  float (*m_s)[RT] = sm.m_s;
+  float (*l_s)[RT] = sm.l_s;
+  float* q_s = sm.q_s;
+  const int split = z % p.nsplit, tile = z / p.nsplit, r0 = tile * RT;
   const int nrows = min(RT, p.R - r0);
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 15, lq = lane >> 4;
   const bf16_t* Kb = (const bf16_t*)p.Kc + b * p.kv_seq_stride + h * DH;
   const bf16_t* Vb = (const bf16_t*)p.Vc + b * p.kv_seq_stride + h * DH;
@@ -918,7 +945,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p, QProjP qp)
     float* st_s = (float*)&vs[0][0][0];          // [K/16][16][2]   (<= 8 KB)
     float* gb_s = st_s + 2048;                   // gain at 0, bias at 1024   (8 KB)
     f32x4* red = &o_s[0][0][0];                  // [wave][column tile][lane]
-    static_assert(sizeof(vs) >= 4 * 4096, "prologue operands fit the V staging area");
+    static_assert(AttnLds::VS_BYTES >= 4 * 4096, "prologue operands fit the V staging area");
     // every global load of the kernel is issued before the first wait: small operands, x, weights, then K / V
     // (named registers: indexed arrays of these were placed in LDS by the compiler)
     const int i0 = tid < NV4 ? tid : 0, i1 = tid + 256 < NV4 ? tid + 256 : 0;
@@ -1132,11 +1159,22 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p, QProjP qp)
                                (unsigned)f2bf(o[2] * inv) | ((unsigned)f2bf(o[3] * inv) << 16));
     }
   } else {
-    const int tiles = gridDim.z / p.nsplit;
-    float* part = p.part + ((((long)b * gridDim.x + h) * tiles + tile) * p.nsplit + split) * (RT * (DH + 2));
+    const int tiles = nz / p.nsplit;
+    float* part = p.part + ((((long)b * nheads + h) * tiles + tile) * p.nsplit + split) * (RT * (DH + 2));
     *(float4*)(part + lr * DH + dim) = make_float4(o[0], o[1], o[2], o[3]);
     if (tid < RT) { part[RT * DH + tid] = M; part[RT * DH + RT + tid] = L; }
   }
+}
+template <bool KVNT, bool LIMF, int QU>
+__global__ __launch_bounds__(256) void attention_mfma_kernel(AttnP p, QProjP qp) {
+  constexpr int RT = 16, DH = 64, WK = 64, VLD = DH + 4;
+  __shared__ __attribute__((aligned(16))) bf16_t vs[4][WK][VLD];
+  __shared__ f32x4 o_s[4][4][64];
+  __shared__ float m_s[4][RT], l_s[4][RT];
+  __shared__ __attribute__((aligned(16))) float q_s[QU > 0 ? RT * (DH + 4) : 4];
+  AttnLds sm;
+  sm.vs = vs; sm.o_s = o_s; sm.m_s = m_s; sm.l_s = l_s; sm.q_s = q_s;
+  attention_mfma_body<KVNT, LIMF, QU>(p, qp, sm, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.x, gridDim.z, threadIdx.x);
 }
 
 // Merge of the nsplit partial results of attention_kernel: with M the largest of the partial

@@ -580,3 +580,34 @@ def test_reloaded_layernorm_weights_reach_the_folded_copies():
     ctx.bpd_load_weights(new_ln)
     for a, b in zip(run(ctx), want):
         np.testing.assert_array_equal(a, b)
+
+
+@pytest.mark.parametrize("which", ["S-bf16", "odd-q256", "odd-stream9", "odd-vocab25"])
+def test_decoder_stack_kernel_against_oracle(which, monkeypatch, tmp_path):
+    """The decoder layers of a block of at most 16 rows as one kernel on one XCD (opt-in, BPD_DECODER_STACK=1 when the
+    context is created): teacher-forced against the oracle like the default path, d = 128 / 256 / 768 / 1024, one and
+    two sequences per row tile; its state equals the per-operator kernels' wherever no near-tie decides."""
+    monkeypatch.setenv("BPD_DECODER_STACK", "1")
+    trace = tmp_path / "stack_trace.bin"
+    monkeypatch.setenv("BPD_STACK_TRACE", str(trace))             # (its time stamps show that the kernel did run)
+    cfg = {c.name: c for c in [SMALL_BF16] + ODD_SHAPES}[which]
+    weights = wl.make_weights(cfg, std=0.02)
+    ctx = gpu_context(cfg, weights)
+    monkeypatch.delenv("BPD_DECODER_STACK")
+    src, n = ragged_sources(cfg, 9)
+    max_len = np.array([max(1, cfg.max_out - 2 * b) for b in range(cfg.batch)], dtype=np.int32)
+    ls = LockStep(cfg, weights, ctx, src, n, max_len)
+    sched = wl.make_schedule(cfg, min(2.0, cfg.k), 16, seed=4)
+    for s in range(4):
+        ls.step(imposed=sched[s])
+    for s in range(3):
+        ls.step(imposed=None)
+    for s in range(cfg.max_out):
+        if all(ls.done.values()):
+            break
+        ls.step(imposed=np.full(cfg.batch, cfg.k, dtype=np.int32), check_logits=False)
+    assert all(ls.done.values())
+    ctx.close()
+    stamps = np.fromfile(str(trace), dtype=np.uint64)
+    assert stamps.size > 0 and (stamps != 0).any(), "the decoder stack kernel was not launched"
+    print(cfg.name, "decoder stack kernel: max logit err", ls.max_logit_err)
