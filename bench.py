@@ -113,13 +113,15 @@ def k_sweep(ctx, cfg, src, n, max_len, torch, steps=100):
     return res
 
 
-def other_configs(torch, binding):
+def other_configs(torch, binding, names=("C0", "C1", "C4", "C4L")):
     """bpd_step latency of the remaining workloads (parity-test configurations, reported for context):
     C0 and C1 over a decode session, C4 at three cache lengths (accepting one token per step so
     that the cache length stays put while timing), and C4L (C4 with 1D local self-attention in the decoder,
-    Section 7.2) at the same lengths."""
+    Section 7.2) at the same lengths.  C4 is bound by the K/V cache it reads: each entry carries the step's algorithmic
+    HBM bytes (weights once, the self-attention K/V rows of every sequence and layer up to the cache length, the
+    cross-attention K/V) against the time of the whole step."""
     res = {}
-    for name in ("C0", "C1", "C4", "C4L"):
+    for name in names:
         cfg = wl.CONFIGS[name]
         ctx = binding.Context(binding.config_from_workload(cfg))
         ctx.bpd_load_weights(wl.make_weights(cfg))
@@ -150,8 +152,19 @@ def other_configs(torch, binding):
                     ctx.bpd_step(cfg.k, one)
                 torch.cuda.synchronize()
                 L += 23
-                res[f"{name}@L{target}"] = {"ms_per_step": 1e3 * (time.perf_counter() - t0) / 20, "batch": cfg.batch, "k": cfg.k,
-                                        "scored_positions_per_s": cfg.batch * cfg.k * 20 / (time.perf_counter() - t0)}
+                dt = time.perf_counter() - t0
+                ms = 1e3 * dt / 20
+                entry = {"ms_per_step": ms, "batch": cfg.batch, "k": cfg.k, "scored_positions_per_s": cfg.batch * cfg.k * 20 / dt}
+                if name == "C4":
+                    wbytes = sum(step_bytes(cfg).values())
+                    kv = cfg.n_dec * 2 * cfg.batch * target * cfg.d_model * 2          # K and V rows 0..L of every layer and sequence
+                    cross = cfg.n_dec * 2 * cfg.batch * int(n.mean()) * cfg.d_model * 2
+                    total = wbytes + kv + cross
+                    entry["roofline"] = {"bound": "hbm", "kernel": "whole step (self-attention over the cache dominates the bytes)",
+                                         "bytes": {"weights": wbytes, "self_kv": kv, "cross_kv": cross},
+                                         "achieved": total / (ms * 1e6), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                         "frac": total / (ms * 1e6) / HBM_PEAK_GBS}
+                res[f"{name}@L{target}"] = entry
         ctx.close()
     return res
 
@@ -186,6 +199,9 @@ def main():
     ap.add_argument("--no-other-configs", action="store_true")
     ap.add_argument("--no-k-sweep", action="store_true")
     ap.add_argument("--no-peaks", action="store_true")
+    ap.add_argument("--only", default=None,
+                    help="comma-separated names among C0, C1, C4, C4L: time just these workloads and print their entries "
+                         "(for profiler runs of one workload)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also launch a plain 256 MiB copy kernel a few times (reference for rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE scaling)")
@@ -209,6 +225,10 @@ def main():
             torch.mul(a, 1.0, out=b)          # one elementwise kernel: reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del a, b
+
+    if args.only:
+        print(json.dumps({"other_configs": other_configs(torch, binding, tuple(args.only.split(",")))}))
+        return
 
     cfg1, cfg32 = wl.C2, wl.C3
     weights = wl.make_weights(cfg1)
@@ -235,9 +255,11 @@ def main():
     bracket_ms = profile_phase(ctx, binding.PHASE_EMPTY, cfg1, src, n, max_len, sched, k, min(args.steps, 60), torch)
     for name in ("head_hidden", "head_out", "vocab"):
         kern[name]["ms_minus_empty_bracket"] = kern[name]["ms"] - bracket_ms
-    dom = max(("head_hidden", "head_out", "vocab"), key=lambda q: kern[q]["ms"])
-    # HBM bytes per launch of that kernel measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by
-    # a copy kernel of known size); recorded by hand from the runs summarised under profiles/
+    # the roofline entry is for the phase that takes most of the step: the decoder layers (42 kernels, each a small
+    # weight stream), not for the best-behaved kernel; the three big single-kernel streams stay under "kernels"
+    dom = max(("layers", "head_hidden", "head_out", "vocab"), key=lambda q: kern[q]["ms"])
+    # HBM bytes per step of that phase measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of
+    # known size), written by `python -m paper_1811_03115_amd.profsum` from the runs named in profiles/
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
@@ -269,7 +291,9 @@ def main():
     if not args.no_peaks:
         peaks = {"hbm_read_GBps": binding.Context.bpd_measure_hbm_read(1 << 30, 4),
                  "mfma_bf16_TFLOPs": binding.Context.bpd_measure_mfma_bf16(20000)}
-    roofline = {"bound": "hbm", "kernel": dom, "achieved": kern[dom]["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+    roofline = {"bound": "hbm", "kernel": dom if dom != "layers" else "layers (the 42 kernels of the 6 decoder layers)",
+                "share_of_step": kern[dom]["ms"] / ms_step,
+                "achieved": kern[dom]["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": kern[dom]["GBps"] / HBM_PEAK_GBS, "traffic": traffic,
                 "frac_of_measured_peak": (kern[dom]["GBps"] / peaks["hbm_read_GBps"]) if peaks else None,
                 "step_achieved": total_bytes / (ms_step * 1e6), "step_frac": total_bytes / (ms_step * 1e6) / HBM_PEAK_GBS,

@@ -57,15 +57,7 @@ struct StackP {
   unsigned long long* trace;                              // debugging aid, may be null: [worker][op instance][8] timestamps
 };
 
-// exchange buffers of one layer (16 rows each): q, attn, x1, q2, attn2, x2, ffh, x3
-struct StackEx { long q, attn, x1, q2, attn2, x2, ffh, x3, total; };
-__host__ __device__ inline StackEx stack_ex(int d, int F) {
-  StackEx e;
-  const long f = 16L * d * 4, h = 16L * d * 2;
-  e.q = 0; e.attn = e.q + f; e.x1 = e.attn + h; e.q2 = e.x1 + f; e.attn2 = e.q2 + f; e.x2 = e.attn2 + h;
-  e.ffh = e.x2 + f; e.x3 = e.ffh + 16L * F * 2; e.total = e.x3 + f;
-  return e;
-}
+static_assert(sizeof(StackLayerP) * STACK_MAX_LAYERS == STACK_LAYER_TABLE_BYTES, "layer table size");
 
 __device__ __forceinline__ unsigned stack_xcc_id() {
   unsigned v;

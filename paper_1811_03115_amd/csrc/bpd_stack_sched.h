@@ -19,6 +19,17 @@ constexpr int STACK_BAR_A = 0;             // a GEMM operator's input block is s
 constexpr int STACK_BAR_B = 1;             // the worker's partial sums of a GEMM operator are in LDS
 constexpr int STACK_BAR_ATT = 2;           // the barrier inside one attention item
 
+// exchange buffers of one layer (16 rows each): q, attn, x1, q2, attn2, x2, ffh, x3 (byte offsets)
+struct StackEx { long q, attn, x1, q2, attn2, x2, ffh, x3, total; };
+BPD_HD inline StackEx stack_ex(int d, int F) {
+  StackEx e;
+  const long f = 16L * d * 4, h = 16L * d * 2;
+  e.q = 0; e.attn = e.q + f; e.x1 = e.attn + h; e.q2 = e.x1 + f; e.attn2 = e.q2 + f; e.x2 = e.attn2 + h;
+  e.ffh = e.x2 + f; e.x3 = e.ffh + 16L * F * 2; e.total = e.x3 + f;
+  return e;
+}
+constexpr int STACK_LAYER_TABLE_BYTES = STACK_MAX_LAYERS * 18 * 8;     // 18 pointers per layer (StackLayerP)
+
 struct StackShape {
   int n_layers, d, F, heads, B, M;         // M = block rows (<= 16)
   int workers;                              // workgroups of the working XCD

@@ -1,0 +1,115 @@
+// Host check of libbpd's sizing and dispatch logic (paper_1811_03115_amd/csrc/bpd_host_logic.h) on many random
+// configurations inside what bpd_create accepts: workspace regions are aligned, disjoint and inside the reported size;
+// the staging area holds the largest tensor bpd_load_weights may stage; key / slice / partial-result buffers hold what
+// the launches write into them; the tile rule only returns tiles the library instantiates.
+// Built by tests/test_host_logic.py with the system compiler under -fsanitize=address,undefined.
+#include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+#include <random>
+#include <set>
+#include <utility>
+
+#include "../../paper_1811_03115_amd/csrc/bpd_host_logic.h"
+
+static long bad = 0;
+#define EXPECT(cond, ...) do { if (!(cond)) { ++bad; if (bad < 20) { fprintf(stderr, "violated: %s  [", #cond); fprintf(stderr, __VA_ARGS__); fprintf(stderr, "]\n"); } } } while (0)
+
+// tiles (rows / 16, columns / 64) the LDS-staged GEMM is instantiated for (the dispatch lists in bpd.hip)
+static const std::set<std::pair<int, int>> TILES = {{3, 1}, {2, 1}, {1, 1}, {8, 2}, {7, 2}, {5, 2}, {4, 2}, {3, 2}, {2, 2}, {1, 2},
+                                                    {8, 4}, {7, 4}, {5, 4}, {4, 4}, {3, 4}, {2, 4}, {1, 4}};
+
+static void check_config(const bpd_config& c) {
+  Layout L;
+  std::vector<std::pair<size_t, size_t>> log;
+  const size_t total = build_layout(c, nullptr, L, &log);
+  Layout L2;
+  EXPECT(build_layout(c, nullptr, L2) == total, "size is a pure function of the configuration");
+  size_t end = 0;
+  for (auto& r : log) {
+    EXPECT(r.first % ALIGN == 0, "aligned region at %zu", r.first);
+    EXPECT(r.first >= end, "regions overlap at %zu", r.first);
+    end = r.first + r.second;
+  }
+  EXPECT(end <= total && total % ALIGN == 0, "last region ends at %zu of %zu", end, total);
+  const size_t d = c.d_model, F = c.d_ff, V = c.vocab, k = c.k_max, S = c.max_src_len, slots = (size_t)c.max_out_len + c.k_max + 1;
+  const size_t B = c.max_batch, M = B * k;
+  // every tensor bpd_load_weights accepts (include/bpd.h), as fp32 from the host
+  const size_t tensors[] = {V * d, S * d, slots * d, d * d, d * F, F * d, F, d, k * d * F, k * F, k * F * d, k * d};
+  for (size_t t : tensors) EXPECT(t * 4 <= L.staging_bytes, "staging %zu < tensor %zu", L.staging_bytes, t * 4);
+  // distances between neighbouring regions that launches rely on
+  EXPECT((char*)L.kpart - (char*)L.attn_part >= (long)((size_t)ATTN_PART_SLOTS * 16 * (d / c.n_heads + 2) * 4), "attention partials");
+  EXPECT((size_t)((char*)L.xn - (char*)L.kpart) >= L.n_kpart * 4, "K slices");
+  EXPECT((size_t)((char*)L.keys_h1 - (char*)L.keys) >= M * k * 8, "keys");
+  EXPECT((size_t)((char*)L.hn2 - (char*)L.keys_h1) >= 2 * M * 8, "head-1 and second-phase keys");
+  EXPECT(L.n_zeros >= std::max({k * F, V, 3 * d}), "zero vector");
+  // split factors stay inside their buffers for every block the context may see
+  for (int b = 1; b <= c.max_batch; b += (c.max_batch > 8 ? 3 : 1))
+    for (int kk = 1; kk <= c.k_max; kk += (c.k_max > 6 ? 2 : 1)) {
+      const int Mb = b * kk;
+      for (int K : {c.d_model, c.d_ff}) {
+        const int ns = residual_k_slices_of(c.d_model, L.n_kpart, Mb, c.d_model, K);
+        EXPECT(ns >= 1 && ns <= KSPLIT_MAX && (ns == 1 || ((size_t)ns * Mb * c.d_model <= L.n_kpart && K % (ns * 512) == 0)), "K slices %d", ns);
+      }
+      for (long steps : {0L, 3L, 50L, 400L})
+        for (int causal : {0, 1}) {
+          const int cap = causal ? (int)slots : c.max_src_len;
+          const int ns = attention_nsplit_of(c, steps, 0, 0, cap, b, kk, causal);
+          const int wgs = c.n_heads * b * ((kk + 15) / 16);
+          EXPECT(ns >= 1 && ns <= 16 && (ns == 1 || ns * wgs <= ATTN_PART_SLOTS), "attention split %d x %d", ns, wgs);
+        }
+    }
+  if (stack_shape_ok(c)) {
+    EXPECT(L.stack_ex && L.stack_flags && L.stack_layers, "decoder stack buffers");
+    EXPECT((size_t)((char*)L.stack_flags - (char*)L.stack_ex) >= (size_t)c.n_dec_layers * stack_ex(c.d_model, c.d_ff).total, "exchange buffers");
+  }
+}
+
+int main() {
+  std::mt19937 rng(1811);
+  auto U = [&](int lo, int hi) { return (int)(lo + rng() % (unsigned)(hi - lo + 1)); };
+  long configs = 0;
+  for (int it = 0; it < 3000; ++it) {
+    bpd_config c{};
+    c.dtype = U(0, 3) == 0 ? BPD_F32 : BPD_BF16;
+    const int dh = (c.dtype == BPD_F32 || U(0, 2) == 0) ? 16 : 64;
+    c.n_heads = U(1, dh == 16 ? 16 : 32);
+    c.d_model = dh * c.n_heads;
+    c.d_ff = 32 * U(1, 160);
+    c.vocab = 16 * U(1, 2200);
+    c.k_max = U(1, 16);
+    c.n_enc_layers = U(1, 6); c.n_dec_layers = U(1, 8);
+    c.max_batch = U(1, 40); c.max_src_len = U(1, 200); c.max_out_len = U(1, 3100);
+    c.eos_id = U(-1, 15); c.pad_id = 0; c.ln_eps = 1e-6f;
+    if (!config_ok(c)) continue;
+    check_config(c);
+    ++configs;
+  }
+  // the five workloads' shapes
+  const int W[5][9] = {{2, 2, 64, 4, 256, 256, 4, 1, 32}, {6, 6, 512, 8, 2048, 32000, 8, 1, 64}, {6, 6, 1024, 16, 4096, 32768, 10, 32, 128},
+                       {6, 6, 1024, 16, 4096, 32768, 10, 1, 128}, {6, 6, 512, 8, 2048, 256, 10, 8, 3072}};
+  for (auto& w : W) {
+    bpd_config c{};
+    c.n_enc_layers = w[0]; c.n_dec_layers = w[1]; c.d_model = w[2]; c.n_heads = w[3]; c.d_ff = w[4]; c.vocab = w[5]; c.k_max = w[6];
+    c.max_batch = w[7]; c.max_out_len = w[8]; c.max_src_len = w[8] == 3072 ? 192 : 128;
+    c.dtype = w[2] == 64 ? BPD_F32 : BPD_BF16; c.eos_id = 2; c.ln_eps = 1e-6f;
+    EXPECT(config_ok(c), "workload shape accepted");
+    check_config(c);
+    ++configs;
+  }
+  // the tile rule: every answer is a tile the library has, K is a multiple of the chunk depth, the cap on rows is kept
+  long tiles = 0;
+  for (int M : {17, 20, 33, 48, 64, 80, 100, 128, 153, 252, 320, 512, 1000, 3200, 4096})
+    for (int N : {64, 256, 528, 1024, 3072, 4096, 32768, 40960})
+      for (int K : {64, 128, 192, 256, 320, 512, 1024, 2048, 4096})
+        for (long z : {1L, 2L, 4L, 10L, 16L})
+          for (int cap : {8, 3}) {
+            int mt = 0, nt = 0;
+            pick_tile(M, N, K, z, mt, nt, cap);
+            EXPECT(TILES.count({mt, nt}) == 1, "tile %d x %d for M=%d N=%d K=%d", mt, nt, M, N, K);
+            EXPECT(mt <= cap && K % (256 / nt) == 0, "tile %d x %d cap %d K %d", mt, nt, cap, K);
+            ++tiles;
+          }
+  printf("%ld configurations, %ld tile choices checked, %ld violations\n", configs, tiles, bad);
+  return bad ? 1 : 0;
+}

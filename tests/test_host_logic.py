@@ -24,3 +24,10 @@ def test_decoder_stack_schedule(tmp_path):
     every worker of many shapes; the compute waves consume exactly the worker's tiles; LDS regions fit."""
     out = build_and_run(os.path.join(HERE, "host", "stack_sched_check.cpp"), str(tmp_path))
     assert "0 violations" in out, out
+
+
+def test_layout_and_dispatch_rules(tmp_path):
+    """Workspace layout, staging size, split factors and the tile rule on thousands of random configurations
+    (bpd_host_logic.h compiled for the host)."""
+    out = build_and_run(os.path.join(HERE, "host", "host_logic_check.cpp"), str(tmp_path))
+    assert " 0 violations" in out, out
