@@ -157,9 +157,9 @@ int bpd_step(bpd_ctx* ctx, int k, const int32_t* imposed_accept, int32_t* accept
  * device image instead of the workspace.  The call allocates nothing (no hipMalloc / hipFree, no allocating library
  * routine) and clears what must start at zero with a fill kernel.  Every context on a GPU shares that GPU's array and
  * it keeps the last call's contents: calls that overlap on one GPU (other streams, other threads) race.
- * Errors: as bpd_step, and BPD_E_CAPACITY when the step's scratch exceeds the array (e.g. 64-wide heads: about
- * 2.2 MB + 8 k^2 B bytes + the K slices of blocks of more than 16 rows; Transformer-big at batch 32, k = 10 needs
- * 7.4 MB), with the byte counts in bpd_last_error(). */
+ * Errors: as bpd_step, and BPD_E_CAPACITY when the step's scratch exceeds the array (8 k^2 B bytes of keys, up to
+ * 2.2 MB of attention partials once a cache is long enough to be split, the K slices of blocks of more than 16 rows;
+ * Transformer-big at batch 32, k = 10 needs 5.3 MB), with the byte counts in bpd_last_error(). */
 int bpd_step_static(bpd_ctx* ctx, int k, const int32_t* imposed_accept, int32_t* accepted_len);
 
 /* Relaxed verification (Section 5), applies to later bpd_step / bpd_decode calls with

@@ -1203,7 +1203,12 @@ int bpd_step_static(bpd_ctx* ctx, int k, const int32_t* imposed_accept, int32_t*
   const size_t M = (size_t)ctx->B * k, d = c.d_model;
   auto up = [](size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; };
   const size_t keys_b = up(M * k * 8), keys_h1_b = up(2 * M * 8);
-  const size_t attn_b = up((size_t)ATTN_PART_SLOTS * 16 * (d / c.n_heads + 2) * 4);
+  size_t attn_b = 0;                       // partial results of a split attention launch: splits x (head, sequence, row tile)
+  for (int causal : {1, 0}) {
+    const int ns = attention_nsplit(ctx, causal ? c.max_out_len + c.k_max + 1 : c.max_src_len, ctx->B, k, causal);
+    const size_t wgs = (size_t)c.n_heads * ctx->B * ((k + 15) / 16);
+    if (ns > 1) attn_b = std::max(attn_b, up(ns * wgs * 16 * (d / c.n_heads + 2) * 4));
+  }
   size_t slices = 1;
   if (c.dtype == BPD_BF16 && M > 16)
     for (int K : {c.d_model, c.d_ff}) {

@@ -24,7 +24,8 @@ constexpr size_t STATIC_SCRATCH_BYTES = (size_t)8 << 20;
 constexpr int MAX_DEVICES = 64;
 constexpr int KSPLIT_MAX = 16;          // K slices of a split-K GEMM
 constexpr int ATTN_LIMF_MIN_WGS = 256;  // attention launches of at least this many workgroups clamp their K/V loads to the length
-constexpr int ATTN_PART_SLOTS = 512;   // workgroups of one split attention launch (partial-result slots)
+constexpr int ATTN_PART_SLOTS = 512;   // workgroups of one split attention launch (partial-result slots); 1024 (one 256-key chunk per
+                                       // workgroup up to 16 chunks) measured slower: C4 step at 3000 cached rows 0.383 vs 0.362 ms
 
 
 struct Arena {
