@@ -118,8 +118,8 @@ def main():
         hdr = [
             "# rocprofv3 kernel trace of bench.py (C2 batch-1 run and its per-phase timing passes, then the C3 batch-32 run in both",
             "# scoring modes; encoder runs and weight loading included)",
-            f"# command: rocprofv3 --kernel-trace --stats -d gpurun_out/prof_trace -o bench -- {BENCH_TRACE}",
-            "# summarised by: python -m paper_1811_03115_amd.profsum --trace gpurun_out/prof_trace",
+            f"# command: rocprofv3 --kernel-trace --stats -d prof_out/prof_trace -o bench -- {BENCH_TRACE}",
+            "# summarised by: python -m paper_1811_03115_amd.profsum --trace prof_out/prof_trace",
             "# durations in microseconds, grouped by kernel and grid (grid = threads in x)",
             "# C2 step (batch 1, 10 block rows), average kernel durations x launches per step:",
         ] + [f"#   {ph:12s} {us:8.2f} us" for ph, us in per_step.items()] + [
@@ -146,9 +146,9 @@ def main():
         hdr = [
             "# rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE (KiB per dispatch) for the kernels of the C2 batch-1 step",
             "# commands (one counter per run):",
-            f"#   rocprofv3 --pmc FETCH_SIZE -d gpurun_out/pmc_fetch -o c2 -- {BENCH_PMC}",
-            f"#   rocprofv3 --pmc WRITE_SIZE -d gpurun_out/pmc_write -o c2 -- {BENCH_PMC}",
-            "#   python -m paper_1811_03115_amd.profsum --fetch gpurun_out/pmc_fetch --write gpurun_out/pmc_write",
+            f"#   rocprofv3 --pmc FETCH_SIZE -d prof_out/pmc_fetch -o c2 -- {BENCH_PMC}",
+            f"#   rocprofv3 --pmc WRITE_SIZE -d prof_out/pmc_write -o c2 -- {BENCH_PMC}",
+            "#   python -m paper_1811_03115_amd.profsum --fetch prof_out/pmc_fetch --write prof_out/pmc_write",
             f"# calibration: the 256 MiB elementwise copy kernel (reads 262144 KiB, writes 262144 KiB) shows FETCH_SIZE {copy_f:.0f} and",
             f"# WRITE_SIZE {copy_w:.0f}, so FETCH_SIZE is scaled by {fs:.2f} and WRITE_SIZE by {ws:.2f} to get bytes.",
             "# per step (bytes = 1024 * (fetch scale * FETCH_SIZE + write scale * WRITE_SIZE), summed over the phase's launches),",
@@ -172,9 +172,9 @@ def main():
             "# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE for the super-resolution workload C4 (batch 8, k = 10, 6 layers, d = 512):",
             "# bpd_step at cache lengths 256, 1536 and 3000 (bench.py --only C4 steps the decode to each length, then times 20 steps",
             "# that accept one token each)",
-            f"#   rocprofv3 --pmc FETCH_SIZE -d gpurun_out/pmc_c4_fetch -o c4 -- {BENCH_C4}",
-            f"#   rocprofv3 --pmc WRITE_SIZE -d gpurun_out/pmc_c4_write -o c4 -- {BENCH_C4}",
-            "#   python -m paper_1811_03115_amd.profsum --c4-fetch gpurun_out/pmc_c4_fetch --c4-write gpurun_out/pmc_c4_write",
+            f"#   rocprofv3 --pmc FETCH_SIZE -d prof_out/pmc_c4_fetch -o c4 -- {BENCH_C4}",
+            f"#   rocprofv3 --pmc WRITE_SIZE -d prof_out/pmc_c4_write -o c4 -- {BENCH_C4}",
+            "#   python -m paper_1811_03115_amd.profsum --c4-fetch prof_out/pmc_c4_fetch --c4-write prof_out/pmc_c4_write",
             f"# copy kernel: FETCH_SIZE {copy_f:.0f}, WRITE_SIZE {copy_w:.0f} for 262144 KiB each way: scales {fs:.2f} / {ws:.2f}",
             "# self-attention over the cache = attention_mfma_kernel<true, *, 0> (K/V fetched with non-temporal loads: the 303 MB of",
             "# caches would evict the weights from the Infinity Cache), its split-KV merge = attention_combine_kernel.",
@@ -206,8 +206,8 @@ def main():
                  "SQ_ACTIVE_INST_VMEM", "SQ_VALU_MFMA_BUSY_CYCLES"]
         hdr = [
             "# rocprofv3 SQ counters per dispatch (averages) of the bench workloads: C2 step (batch 1) and C3 step (batch 32)",
-            "# command: rocprofv3 --pmc " + " ".join(names) + f" -d gpurun_out/pmc_sq -o b -- {BENCH_SQ}",
-            "# summarised by: python -m paper_1811_03115_amd.profsum --sq gpurun_out/pmc_sq",
+            "# command: rocprofv3 --pmc " + " ".join(names) + f" -d prof_out/pmc_sq -o b -- {BENCH_SQ}",
+            "# summarised by: python -m paper_1811_03115_amd.profsum --sq prof_out/pmc_sq",
             "# mfma_util = SQ_VALU_MFMA_BUSY_CYCLES / (kernel duration x 2.4 GHz x 1024 SIMDs): the share of the chip's matrix-pipe cycles",
             "# in use (the counter adds, over all SIMDs, the cycles an MFMA occupies its pipe: 16 per v_mfma_f32_16x16x32_bf16, which at",
             "# 16384 flop each is the published 2.5 PFLOP/s when every SIMD issues back to back; padded rows count as work here).",
