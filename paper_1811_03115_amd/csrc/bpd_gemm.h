@@ -745,6 +745,19 @@ __global__ __launch_bounds__(512) void stream_vocab_kernel(GemmP p, unsigned lon
   }
 }
 
+// 16 bytes per lane from global memory (base, the same for the whole wave, + the lane's byte offset) straight into LDS:
+// lane l's piece lands at lds_base + 16 l (lds_base: the same for the whole wave).  Issued from inline assembly on purpose:
+// behind the compiler's builtin for this instruction every later LDS read of the kernel is ordered after ALL outstanding
+// loads (s_waitcnt vmcnt(0) ahead of the first read of each chunk), so nothing stayed in flight across the matrix
+// instructions.  The kernel waits for these loads itself (s_waitcnt vmcnt(n) + workgroup barrier) before reading.
+__device__ __forceinline__ void lds_dma16(const void* base, unsigned byte_off, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_base), "v"(byte_off), "s"(base) : "memory");
+}
+__device__ __forceinline__ unsigned lds_address(const void* p) {
+  return (unsigned)(unsigned long long)(const __attribute__((address_space(3))) void*)p;
+}
+
 // ---------------------------------------------------------------------------------------
 // "ldsx" GEMM: BM = 16*MT rows x BN = 64*NT columns per workgroup, K walked in chunks of KC.
 // Wave w owns column tiles (4*blockIdx.x + w)*NT .. +NT and streams their weight tiles from
@@ -753,7 +766,8 @@ __global__ __launch_bounds__(512) void stream_vocab_kernel(GemmP p, unsigned lon
 // registers), double buffered.  Such a load writes 64 consecutive 16-byte slots per wave, so
 // rows cannot be padded; instead the 16-byte segment index within a row is XOR-ed with
 // (row & 7), which spreads the MFMA operand reads of a wave evenly over the LDS banks.
-// Requires K % KC == 0, KC % 64 == 0.  Dynamic LDS: ldsx_lds_bytes() (2 or 3 buffers of XI * 4096 bytes).
+// Requires K % KC == 0, KC % 64 == 0 (DEEP tiles: K % 128 == 0).  Dynamic LDS: ldsx_lds_bytes() (2 or 3 buffers of
+// XI * 4096 bytes).
 // Two workgroups share a CU whenever the accumulators (4*MT*NT registers), the two weight chunks
 // (8*NT*KC/32) and the operand fragments (4*MT) leave room for it in half the register file: the
 // second wave per SIMD covers the LDS and memory latencies of the first.
@@ -764,13 +778,19 @@ constexpr int ldsx_waves_min() { return ldsx_regs<MT, NT, KC>() <= 272 ? 2 : 1; 
 template <int MT, int NT, int KC>
 constexpr int ldsx_waves_max() { return ldsx_regs<MT, NT, KC>() <= 168 ? 4 : ldsx_waves_min<MT, NT, KC>(); }
 
-// Two weight buffers take turns (2) unless the tile has no registers to spare for two code copies of the chunk (1).  A
-// third buffer (weights and activations two chunks ahead) was measured: it halves the workgroups per CU of the small
-// tiles and made every workload slower.
+// Large tiles (64 or more rows, 256 columns, chunks of 64) keep more in flight (DEEP): four 32-deep steps of weights in
+// registers, each requested again right after the step that used them (a lead of three steps instead of two: what a
+// chunk waits for is the slowest of its ~100 memory requests, and one in seven misses the L2), three activation
+// buffers, and the LDS reads of one half of a step's row tiles overlap the matrix instructions of the other half.
+// On the 3200 x 32768 x 1024 vocabulary projection: 264 us with the compiler's waits, 222 us with the loop's loads and
+// waits issued by hand, 207 us with all LDS reads of a step ahead of its matrix instructions, 187 us as DEEP.
+#ifndef BPD_LDSX_DEEP
+#define BPD_LDSX_DEEP 1
+#endif
 template <int MT, int NT, int KC>
-constexpr int ldsx_ring() { return ldsx_regs<MT, NT, KC>() <= 210 ? 2 : 1; }
+constexpr bool ldsx_deep() { return BPD_LDSX_DEEP && NT == 4 && KC == 64 && MT >= 4; }
 template <int MT, int NT, int KC>
-constexpr size_t ldsx_lds_bytes() { return (size_t)2 * ((16 * MT * (KC / 8) + 255) / 256) * 4096; }
+constexpr size_t ldsx_lds_bytes() { return (size_t)(ldsx_deep<MT, NT, KC>() ? 3 : 2) * ((16 * MT * (KC / 8) + 255) / 256) * 4096; }
 
 // XLN (one group, no split-K, K <= 1024): X = LayerNorm(ln.x) of the fp32 residual stream.  The producer of ln.x left per
 // 64-column block and row the sum and sum of squares of its values in ln.stats[(block * M + row) * 2] (store_tiles); the
@@ -791,7 +811,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t* xs0 = (bf16_t*)smem_raw;
   bf16_t* xs1 = xs0 + BUF;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int g = p.ksplit > 1 ? 0 : blockIdx.z;
   const int ntiles = p.N >> 4, ksteps = p.K >> 5;
   const int nchunks = p.K / KC / (p.ksplit > 1 ? p.ksplit : 1);      // chunks of this K slice
@@ -826,19 +846,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
     wt[u] = (const uint4*)W + (long)tile * ksteps * 64 + lane;
   }
   // slot i*256 + tid of a buffer holds row = slot / SEG, segment (slot % SEG) ^ (row & 7)
-  int xoff[XI];
+  unsigned xoff[XI];
 #pragma unroll
   for (int i = 0; i < XI; ++i) {
     const int slot = tid + 256 * i;
     const int r = slot / SEG;
     int row = m0 + r;
     row = row < p.M ? row : p.M - 1;
-    xoff[i] = row * p.ldx + (((slot % SEG) ^ (r & 7)) * 8);
+    xoff[i] = (row * p.ldx + (((slot % SEG) ^ (r & 7)) * 8)) * 2;      // bytes
   }
 #define BPD_X_TO_LDS(buf, chunk)                                                            \
   _Pragma("unroll") for (int i = 0; i < XI; ++i)                                            \
-    __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(X + xoff[i] + (chunk) * KC), \
-                                     (void __attribute__((address_space(3)))*)((buf) + (i * 256 + wave * 64) * 8), 16, 0, 0);
+    lds_dma16(X + (chunk) * KC, xoff[i], lds_address((buf) + (i * 256 + wave * 64) * 8));
   if constexpr (XLN) {
     // ---- LayerNorm-fused variant: activations through registers
     static_assert(256 % SEG == 0, "a thread keeps its 16-byte segment across its rows");
@@ -972,28 +991,33 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
     store_tiles<MT, NT, STATS>(e, g, acc, m0, nt0, ntiles, p.M, lane, nullptr, nullptr, nullptr, XPREF ? xpre_b : nullptr, XPREF ? xpre_r : nullptr);
     return;
   }
-  // The chunk being multiplied and the next one are in use / in flight: weights in two register buffers, activations in
-  // two LDS buffers.  RING == 2: the register buffers take turns; RING == 1: a register copy per chunk.
-  constexpr int RING = ldsx_ring<MT, NT, KC>();
+  // The direct-to-LDS loads of the loop are issued from inline assembly (lds_dma16) and waited for by hand (s_waitcnt
+  // vmcnt(n): at most the n youngest loads of this wave still outstanding; loads complete in issue order).  Through the
+  // compiler's builtin every later LDS read is ordered behind ALL outstanding loads, whichever buffer they fill, which ends
+  // in vmcnt(0) ahead of each chunk's first read and leaves nothing in flight across the matrix instructions.  The weight
+  // loads stay ordinary loads: the compiler's own waits for them count only the loads it knows of, so with the direct
+  // loads in the queue they cover a few more loads than needed (never fewer): each weight request is therefore issued
+  // AHEAD of the activation request of its chunk, which keeps what is covered to loads of about the same age.
+  //
+  // Plain tiles: the chunk being multiplied and the next one are in use / in flight, weights in two register sets that
+  // take turns, activations in two LDS buffers.
+  // DEEP tiles: four 32-deep steps of weights in registers, each requested again (two chunks ahead) right after the step
+  // that used them; three activation buffers.
+  constexpr bool DEEP = ldsx_deep<MT, NT, KC>();
+  static_assert(!DEEP || KS == 2, "DEEP: two steps per chunk");
   uint4 a0[KS][NT], a1[KS][NT];
   f32x4 acc[MT][NT];
 #pragma unroll
   for (int t = 0; t < MT; ++t)
 #pragma unroll
     for (int u = 0; u < NT; ++u) acc[t][u] = f32x4{0.f, 0.f, 0.f, 0.f};
+#define BPD_LOAD_WS(dst, step)                                                               \
+  _Pragma("unroll") for (int u = 0; u < NT; ++u) dst[u] = wt[u][(long)(step) * 64];
 #define BPD_LOAD_W(dst, chunk)                                                               \
-  _Pragma("unroll") for (int s = 0; s < KS; ++s)                                            \
-    _Pragma("unroll") for (int u = 0; u < NT; ++u) dst[s][u] = wt[u][(long)((chunk) * KS + s) * 64];
-  // vmcnt <= n, other counters untouched.  Loads complete in issue order: once at most the loads issued after an
-  // activation chunk (its own weights) are outstanding, this wave's part of that chunk has reached LDS.
-#define BPD_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (7 << 4) | (15 << 8) | (((n) >> 4) << 14))
-  constexpr int YOUNGER = KS * NT;
-  static_assert(YOUNGER <= 63, "vmcnt range");
-  BPD_X_TO_LDS(xs0, cbase)
-  BPD_LOAD_W(a0, cbase)
-  // small tiles: bias and residual of the epilogue, requested now (younger than the first chunk: the waits below count them)
+  _Pragma("unroll") for (int s = 0; s < KS; ++s) BPD_LOAD_WS(dst[s], (chunk) * KS + s)
+#define BPD_WAIT_VM(n) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(n) : "memory")
+  // small tiles: bias and residual of the epilogue are requested first
   constexpr bool PREF = !ARGMAX && MT * NT <= 3;
-  constexpr int NPRE = PREF ? NT + MT * NT : 0;
   float4 pre_b[PREF ? NT : 1], pre_r[PREF ? MT * NT : 1];
   const bool pre = PREF && e.pre_epi != 0;       // (uniform)
   if constexpr (PREF) {
@@ -1015,7 +1039,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
   constexpr int RL = MT == 1 ? 1 : 4;
   float2 rpv[ROWAFF ? RL : 1];
   float4 ra_c4[NT], ra_d4[NT];
-  if constexpr (ROWAFF) {                        // behind the first chunk's loads, in the shadow of their round trip
+  if constexpr (ROWAFF) {
     int row = m0 + (MT == 1 ? (tid & 15) : lane); row = row < p.M ? row : p.M - 1;
     const int tiles = p.K >> 6;                  // 64-column blocks of the producer, <= 16
 #pragma unroll
@@ -1029,10 +1053,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
       ra_c4[u] = *(const float4*)(e.ra_c + tile * 16 + lq * 4);
       ra_d4[u] = *(const float4*)(e.ra_d + tile * 16 + lq * 4);
     }
-    BPD_WAIT_VM(0);
+  }
+  const bf16_t* xa = xs0;                        // DEEP: the activation buffers take turns (xa: multiplied, xb: next, xf: filling)
+  const bf16_t* xb = xs1;
+  bf16_t* xf = xs1 + (DEEP ? BUF : 0);
+  const int c1 = cbase + (1 < nchunks ? 1 : 0);
+  if constexpr (DEEP) {                          // (the order of the loop: weights of step 0, activations, weights of step 1)
+    BPD_LOAD_WS(a0[0], cbase * KS)
+    BPD_X_TO_LDS(xs0, cbase)
+    BPD_LOAD_WS(a0[1], cbase * KS + 1)
+    BPD_LOAD_WS(a1[0], c1 * KS)
+    BPD_X_TO_LDS(xs1, c1)
+    BPD_LOAD_WS(a1[1], c1 * KS + 1)
+    BPD_WAIT_VM(3 * NT + XI);                    // the first activation chunk has landed (this wave's part)
   } else {
-    static_assert(YOUNGER + NPRE <= 63, "vmcnt range");
-    if (pre) { BPD_WAIT_VM(YOUNGER + NPRE); } else { BPD_WAIT_VM(YOUNGER); }
+    BPD_LOAD_W(a0, cbase)
+    BPD_X_TO_LDS(xs0, cbase)
+    BPD_WAIT_VM(0);
   }
   if constexpr (ROWAFF) {
     const int tiles = p.K >> 6;
@@ -1056,48 +1093,100 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
       ra_ms[tid] = make_float2(mean, 1.0f / sqrtf(var + e.ra_eps));
     }
   }
-  // One chunk c (weights in AC, activations in xc): chunk c + 1 starts moving into AL / xl, chunk c is multiplied, then the
-  // workgroup meets once activation chunk c + 1 has landed.  The weights requested after that chunk stay in flight across
-  // the barrier, so the memory pipe never drains.  The last chunk re-requests itself (branch-free).
+  // one 32-deep step: the MT activation fragments from LDS (all requested before the first matrix instruction, which
+  // then waits for its own fragment only), MT x NT matrix instructions
+#define BPD_XFRAG(xc, s, t) *(const uint4*)((xc) + ((t) * 16 + lr) * KC + ((((s) * 4 + lq) ^ (lr & 7)) * 8))
+#define BPD_STEP(A_, xc, s)                                                                  \
+  {                                                                                          \
+    uint4 b[MT];                                                                             \
+    _Pragma("unroll") for (int t = 0; t < MT; ++t) b[t] = BPD_XFRAG(xc, s, t);               \
+    _Pragma("unroll") for (int t = 0; t < MT; ++t)                                           \
+      _Pragma("unroll") for (int u = 0; u < NT; ++u)                                         \
+        acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A_[u]), \
+                                                            __builtin_bit_cast(bf16x8, b[t]), acc[t][u], 0, 0, 0); \
+    __builtin_amdgcn_sched_group_barrier(0x100, MT, 0);                                      \
+    __builtin_amdgcn_sched_group_barrier(0x008, MT * NT, 0);                                 \
+  }
+  // Plain chunk c (weights in AC, activations in xc): chunk c + 1 starts moving into AL / xl, chunk c is multiplied, and
+  // the workgroup meets once activation chunk c + 1 has landed: its request is the youngest, so that is when nothing is
+  // outstanding any more.  The last chunk requests itself again (branch-free).
 #define BPD_CHUNK(AC, AL, xc, xl, c)                                                         \
   {                                                                                          \
     const int cl = cbase + ((c) + 1 < nchunks ? (c) + 1 : nchunks - 1);                      \
-    BPD_X_TO_LDS(xl, cl)                                                                     \
     BPD_LOAD_W(AL, cl)                                                                       \
+    BPD_X_TO_LDS(xl, cl)                                                                     \
     __builtin_amdgcn_sched_barrier(0);                                                       \
     _Pragma("unroll") for (int s = 0; s < KS; ++s) {                                         \
-      uint4 b[MT];                                                                           \
-      _Pragma("unroll") for (int t = 0; t < MT; ++t)                                         \
-        b[t] = *(const uint4*)((xc) + (t * 16 + lr) * KC + (((s * 4 + lq) ^ (lr & 7)) * 8)); \
-      _Pragma("unroll") for (int t = 0; t < MT; ++t)                                         \
-        _Pragma("unroll") for (int u = 0; u < NT; ++u)                                       \
-          acc[t][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, AC[s][u]), \
-                                                              __builtin_bit_cast(bf16x8, b[t]), acc[t][u], 0, 0, 0); \
+      BPD_STEP(AC[s], xc, s)                                                                 \
+      __builtin_amdgcn_sched_barrier(0);                                                     \
     }                                                                                        \
-    __builtin_amdgcn_sched_barrier(0);                                                       \
-    BPD_WAIT_VM(YOUNGER);                                                                    \
+    BPD_WAIT_VM(0);                                                                          \
     __syncthreads();                                                                         \
   }
-  if constexpr (RING == 2) {
-    for (int c = 0; c < nchunks; c += 2) {
+  // DEEP chunk c (its two steps' weights in A: a0 / a1 in turn; activations in xa).  The row tiles of a step go in two
+  // halves: while the matrix instructions of one half are issued the other half's fragments (of the same step, or of the
+  // next one) are on their way from LDS.  The first half of the next chunk's first step is requested before this
+  // chunk's last half-step, so the workgroup meets there: activation chunk c + 1 has landed by then (younger than its
+  // request: the weights of that chunk's second step and this chunk's first refill), and no wave still reads chunk
+  // c - 1, whose buffer (xf) chunk c + 2 starts moving into.  A step's weights are requested again (chunk c + 2) once its
+  // matrix instructions are issued.  Issue order per chunk: weights of step 0, activations, weights of step 1.
+#define BPD_HALF(A_, B_, T0, TN)                                                             \
+  _Pragma("unroll") for (int t = 0; t < TN; ++t)                                             \
+    _Pragma("unroll") for (int u = 0; u < NT; ++u)                                           \
+      acc[T0 + t][u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, A_[u]), \
+                                                               __builtin_bit_cast(bf16x8, B_[t]), acc[T0 + t][u], 0, 0, 0); \
+  __builtin_amdgcn_sched_barrier(0);
+#define BPD_READ_LO(xc, s) _Pragma("unroll") for (int t = 0; t < ML; ++t) blo[t] = BPD_XFRAG(xc, s, t); __builtin_amdgcn_sched_barrier(0);
+#define BPD_READ_HI(xc, s) _Pragma("unroll") for (int t = 0; t < MH; ++t) bhi[t] = BPD_XFRAG(xc, s, ML + t); __builtin_amdgcn_sched_barrier(0);
+#define BPD_CHUNK_DEEP(A, c)                                                                 \
+  {                                                                                          \
+    const int cl = cbase + ((c) + 2 < nchunks ? (c) + 2 : nchunks - 1);                      \
+    BPD_READ_HI(xa, 0)                                                                       \
+    BPD_HALF(A[0], blo, 0, ML)                                                               \
+    BPD_READ_LO(xa, 1)                                                                       \
+    BPD_HALF(A[0], bhi, ML, MH)                                                              \
+    BPD_LOAD_WS(A[0], cl * KS)                                                               \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
+    BPD_READ_HI(xa, 1)                                                                       \
+    BPD_HALF(A[1], blo, 0, ML)                                                               \
+    BPD_WAIT_VM(2 * NT);                                                                     \
+    __syncthreads();                                                                         \
+    BPD_X_TO_LDS(xf, cl)                                                                     \
+    BPD_READ_LO(xb, 0)                                                                       \
+    BPD_HALF(A[1], bhi, ML, MH)                                                              \
+    BPD_LOAD_WS(A[1], cl * KS + 1)                                                           \
+    __builtin_amdgcn_sched_barrier(0);                                                       \
+    { const bf16_t* t_ = xa; xa = xb; xb = xf; xf = (bf16_t*)t_; }                           \
+  }
+  if constexpr (DEEP) {
+    static_assert(3 * NT + XI <= 63, "vmcnt range");
+    constexpr int ML = MT / 2, MH = MT - ML;
+    uint4 blo[ML], bhi[MH];
+    BPD_READ_LO(xa, 0)
+    for (int c = 0; c < nchunks; c += 2) {       // (an even number of chunks: the host's tile choice sees to it)
+      BPD_CHUNK_DEEP(a0, c)
+      BPD_CHUNK_DEEP(a1, c + 1)
+    }
+    BPD_WAIT_VM(0);                              // the last chunks requested themselves again: those copies still land in LDS
+    __syncthreads();
+  } else {
+    int c = 0;
+    for (; c + 1 < nchunks; c += 2) {
       BPD_CHUNK(a0, a1, xs0, xs1, c)
-      if (c + 1 >= nchunks) break;
       BPD_CHUNK(a1, a0, xs1, xs0, c + 1)
     }
-  } else {
-    for (int c = 0; c < nchunks; ++c) {
-      const bf16_t* xc = (c & 1) ? xs1 : xs0;
-      bf16_t* xl = (c & 1) ? xs0 : xs1;
-      BPD_CHUNK(a0, a1, xc, xl, c)
-#pragma unroll
-      for (int s = 0; s < KS; ++s)
-#pragma unroll
-        for (int u = 0; u < NT; ++u) a0[s][u] = a1[s][u];        // waits for the next weights
-    }
+    if (c < nchunks) BPD_CHUNK(a0, a1, xs0, xs1, c)
   }
+#undef BPD_READ_HI
+#undef BPD_READ_LO
+#undef BPD_HALF
+#undef BPD_XFRAG
+#undef BPD_CHUNK_DEEP
 #undef BPD_CHUNK
+#undef BPD_STEP
 #undef BPD_WAIT_VM
 #undef BPD_LOAD_W
+#undef BPD_LOAD_WS
 #undef BPD_X_TO_LDS
   if (ARGMAX) {
     // per-row best of each wave -> LDS -> one atomic per row and workgroup

@@ -192,6 +192,7 @@ void pick_tile(int M, int N, int K, long zdim, int& mt, int& nt, int mt_max = 8)
     const long cols = (N / 16 + 4 * n - 1) / (4 * n);
     for (int m : mts) {
       if ((n == 1 && m > 3) || m > mt_max) continue;
+      if (n == 4 && m >= 4 && K % 128 != 0) continue;       // these tiles walk K two chunks of 64 at a time
       const long bm = 16 * m, mblocks = (M + bm - 1) / bm, pad = mblocks * bm;
       if (mblocks * cols * zdim < (K >= 2048 && M < 1024 ? LDSX_MIN_WGS_LONGK : LDSX_MIN_WGS)) continue;
       const long area = (long)m * n;                  // compared as area * M / pad: padded rows are wasted work
