@@ -779,16 +779,16 @@ template <int MT, int NT, int KC>
 constexpr int ldsx_waves_max() { return ldsx_regs<MT, NT, KC>() <= 168 ? 4 : ldsx_waves_min<MT, NT, KC>(); }
 
 // Large tiles (64 or more rows, 256 columns, chunks of 64) keep more in flight (DEEP): four 32-deep steps of weights in
-// registers, each requested again right after the step that used them (a lead of three steps instead of two: what a
-// chunk waits for is the slowest of its ~100 memory requests, and one in seven misses the L2), three activation
-// buffers, and the LDS reads of one half of a step's row tiles overlap the matrix instructions of the other half.
-// On the 3200 x 32768 x 1024 vocabulary projection: 264 us with the compiler's waits, 222 us with the loop's loads and
-// waits issued by hand, 207 us with all LDS reads of a step ahead of its matrix instructions, 187 us as DEEP.
-#ifndef BPD_LDSX_DEEP
-#define BPD_LDSX_DEEP 1
-#endif
+// registers, each requested again right after the step that used them (what a chunk waits for is the slowest of its ~100
+// memory requests, and one in seven misses the L2), three activation buffers, and the LDS reads of one half of a step's
+// row tiles overlap the matrix instructions of the other half.  An even number of chunks (K % 128 == 0; the host's tile
+// rule sees to it: a third copy of the chunk for an odd tail spilled registers).
+// On the 3200 x 32768 x 1024 vocabulary projection: 264 us with the compiler's builtin for the direct loads, 216 us with
+// those loads and their waits issued by hand and all LDS reads of a step ahead of its matrix instructions, 196 us as
+// DEEP.  Smaller tiles measured no faster as DEEP (the batch-32 step 0.780 ms against 0.760 ms: they lose a workgroup
+// per CU to the third buffer), the 64 x 128 tiles of the heads' output layers the same (0.759 ms).
 template <int MT, int NT, int KC>
-constexpr bool ldsx_deep() { return BPD_LDSX_DEEP && NT == 4 && KC == 64 && MT >= 4; }
+constexpr bool ldsx_deep() { return NT == 4 && KC == 64 && MT >= 4; }
 template <int MT, int NT, int KC>
 constexpr size_t ldsx_lds_bytes() { return (size_t)(ldsx_deep<MT, NT, KC>() ? 3 : 2) * ((16 * MT * (KC / 8) + 255) / 256) * 4096; }
 
@@ -1004,7 +1004,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
   // DEEP tiles: four 32-deep steps of weights in registers, each requested again (two chunks ahead) right after the step
   // that used them; three activation buffers.
   constexpr bool DEEP = ldsx_deep<MT, NT, KC>();
-  static_assert(!DEEP || KS == 2, "DEEP: two steps per chunk");
   uint4 a0[KS][NT], a1[KS][NT];
   f32x4 acc[MT][NT];
 #pragma unroll
@@ -1058,14 +1057,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
   const bf16_t* xb = xs1;
   bf16_t* xf = xs1 + (DEEP ? BUF : 0);
   const int c1 = cbase + (1 < nchunks ? 1 : 0);
-  if constexpr (DEEP) {                          // (the order of the loop: weights of step 0, activations, weights of step 1)
-    BPD_LOAD_WS(a0[0], cbase * KS)
+  if constexpr (DEEP) {                          // two chunks up front; both have landed when the loop starts
     BPD_X_TO_LDS(xs0, cbase)
-    BPD_LOAD_WS(a0[1], cbase * KS + 1)
-    BPD_LOAD_WS(a1[0], c1 * KS)
+    BPD_LOAD_W(a0, cbase)
     BPD_X_TO_LDS(xs1, c1)
-    BPD_LOAD_WS(a1[1], c1 * KS + 1)
-    BPD_WAIT_VM(3 * NT + XI);                    // the first activation chunk has landed (this wave's part)
+    BPD_LOAD_W(a1, c1)
+    BPD_WAIT_VM(0);
   } else {
     BPD_LOAD_W(a0, cbase)
     BPD_X_TO_LDS(xs0, cbase)
@@ -1141,27 +1138,29 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
 #define BPD_CHUNK_DEEP(A, c)                                                                 \
   {                                                                                          \
     const int cl = cbase + ((c) + 2 < nchunks ? (c) + 2 : nchunks - 1);                      \
-    BPD_READ_HI(xa, 0)                                                                       \
-    BPD_HALF(A[0], blo, 0, ML)                                                               \
-    BPD_READ_LO(xa, 1)                                                                       \
-    BPD_HALF(A[0], bhi, ML, MH)                                                              \
-    BPD_LOAD_WS(A[0], cl * KS)                                                               \
-    __builtin_amdgcn_sched_barrier(0);                                                       \
-    BPD_READ_HI(xa, 1)                                                                       \
-    BPD_HALF(A[1], blo, 0, ML)                                                               \
-    BPD_WAIT_VM(2 * NT);                                                                     \
+    _Pragma("unroll") for (int s = 0; s < KS - 1; ++s) {                                     \
+      BPD_READ_HI(xa, s)                                                                     \
+      BPD_HALF(A[s], blo, 0, ML)                                                             \
+      BPD_READ_LO(xa, s + 1)                                                                 \
+      BPD_HALF(A[s], bhi, ML, MH)                                                            \
+      BPD_LOAD_WS(A[s], cl * KS + s)                                                         \
+      __builtin_amdgcn_sched_barrier(0);                                                     \
+    }                                                                                        \
+    BPD_READ_HI(xa, KS - 1)                                                                  \
+    BPD_HALF(A[KS - 1], blo, 0, ML)                                                          \
+    BPD_WAIT_VM(KS * NT);                                                                    \
     __syncthreads();                                                                         \
     BPD_X_TO_LDS(xf, cl)                                                                     \
     BPD_READ_LO(xb, 0)                                                                       \
-    BPD_HALF(A[1], bhi, ML, MH)                                                              \
-    BPD_LOAD_WS(A[1], cl * KS + 1)                                                           \
+    BPD_HALF(A[KS - 1], bhi, ML, MH)                                                         \
+    BPD_LOAD_WS(A[KS - 1], cl * KS + KS - 1)                                                 \
     __builtin_amdgcn_sched_barrier(0);                                                       \
     { const bf16_t* t_ = xa; xa = xb; xb = xf; xf = (bf16_t*)t_; }                           \
   }
   if constexpr (DEEP) {
-    static_assert(3 * NT + XI <= 63, "vmcnt range");
+    static_assert(KS * NT <= 63, "vmcnt range");
     constexpr int ML = MT / 2, MH = MT - ML;
-    uint4 blo[ML], bhi[MH];
+    uint4 blo[ML > 0 ? ML : 1], bhi[MH];
     BPD_READ_LO(xa, 0)
     for (int c = 0; c < nchunks; c += 2) {       // (an even number of chunks: the host's tile choice sees to it)
       BPD_CHUNK_DEEP(a0, c)
