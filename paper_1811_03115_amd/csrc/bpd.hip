@@ -252,7 +252,9 @@ void launch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* 
     (void)hipFuncSetAttribute((const void*)gemm_ldsx_kernel<MT, NT, KC, ARGMAX, XLN, STATS, ROWAFF>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_set = true;
   }
-  hipLaunchKernelGGL((gemm_ldsx_kernel<MT, NT, KC, ARGMAX, XLN, STATS, ROWAFF>), grid, dim3(256), lds, s, p, e, keys, logits, ln);
+  GemmP q = p;
+  ldsx_remap(q, KC, grid.x, grid.y);            // (grid.x * grid.y * grid.y * 4 < 2^32 by far: at most a few thousand blocks each way)
+  hipLaunchKernelGGL((gemm_ldsx_kernel<MT, NT, KC, ARGMAX, XLN, STATS, ROWAFF>), grid, dim3(256), lds, s, q, e, keys, logits, ln);
 }
 
 // Tile of the LDS-staged GEMM: 16*mt rows x 64*nt columns per workgroup, K walked in chunks of
