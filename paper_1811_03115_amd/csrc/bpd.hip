@@ -253,7 +253,7 @@ void launch_ldsx(const GemmP& p, const Epi& e, unsigned long long* keys, float* 
     attr_set = true;
   }
   GemmP q = p;
-  ldsx_remap(q, KC, grid.x, grid.y);            // (grid.x * grid.y * grid.y * 4 < 2^32 by far: at most a few thousand blocks each way)
+  q.lx = ldsx_map_of(p.K, KC, p.ksplit, grid.x, grid.y, grid.z);            // (grid.x * grid.y * grid.y * 4 < 2^32 by far: at most a few thousand blocks each way)
   hipLaunchKernelGGL((gemm_ldsx_kernel<MT, NT, KC, ARGMAX, XLN, STATS, ROWAFF>), grid, dim3(256), lds, s, q, e, keys, logits, ln);
 }
 

@@ -812,28 +812,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
   bf16_t* xs0 = (bf16_t*)smem_raw;
   bf16_t* xs1 = xs0 + BUF;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int g = p.ksplit > 1 ? 0 : blockIdx.z;
+  int g = p.ksplit > 1 ? 0 : blockIdx.z;
   const int ntiles = p.N >> 4, ksteps = p.K >> 5;
-  const int nchunks = p.lx_nchunks;                                   // chunks of this K slice (K / KC / slices, from the host)
+  const int nchunks = p.lx.nchunks;                                   // chunks of this K slice (K / KC / slices, from the host)
   const int cbase = p.ksplit > 1 ? blockIdx.z * nchunks : 0;
-  // Workgroups are handed to the 8 XCDs round-robin in launch order and each XCD has its own L2.
-  // Remap so that an XCD owns column blocks (weights) congruent to its index and sweeps the row
-  // blocks fastest: a weight block is then fetched from memory once instead of once per row block.
-  // (the divisions are by numbers the host knows: it passes log2 G and multipliers (ldsx_remap()); spelled out as
-  // integer divisions this map was a hundred instructions in front of the kernel's first load)
-  int bx = blockIdx.x, by = blockIdx.y;
-  {
-    const unsigned NB = gridDim.x, MB = gridDim.y, L = blockIdx.x + NB * blockIdx.y;
-    if ((NB & 7) == 0) {
-      // within an XCD: groups of G column blocks, row blocks next, the G column blocks of a group fastest, so that a
-      // row block of activations is fetched once per G column blocks while their G weight blocks stay in L2
-      const unsigned j = L >> 3, lg = p.lx_log2g;
-      const unsigned grp = __umulhi(j, p.lx_magic_mbg), within = j - grp * (MB << lg);
-      by = within >> lg;
-      bx = (L & 7) + 8 * ((grp << lg) + (within & ((1u << lg) - 1)));
-    }
-    else { bx = __umulhi(L, p.lx_magic_mb); by = L - bx * MB; }
-  }
+  int bx, by;                                    // (the map: bpd_tile_map.h)
+  ldsx_tile_of(p.lx, gridDim.x, gridDim.y, blockIdx.x, blockIdx.y, blockIdx.z, g, by, bx);
   const int m0 = by * BM;
   const int nt0 = (bx * 4 + wave) * NT;
   const int lr = lane & 15, lq = lane >> 4;

@@ -14,6 +14,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include "bpd_tile_map.h"
 
 typedef unsigned short bf16_t;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -150,19 +151,8 @@ struct GemmP {
   // split-K (gemm_ldsx_kernel, one group): blockIdx.z = slice of K; the raw fp32 product of slice z
   // goes to part + z*M*N and the consumer (layernorm_kernel) adds the slices in index order
   int ksplit; float* part;
-  // gemm_ldsx_kernel: what its workgroup -> tile map and K walk would otherwise divide for (set by ldsx_remap())
-  int lx_nchunks, lx_log2g; unsigned lx_magic_mbg, lx_magic_mb;
+  LdsxMap lx;          // gemm_ldsx_kernel: its workgroup -> tile map and K walk (bpd_tile_map.h; set by the launcher)
 };
-// Multiplier m with n / d == umulhi(n, m) for all n with n * d < 2^32 (m = ceil(2^32 / d))
-inline unsigned magic_div(unsigned d) { return (unsigned)((0x100000000ull + d - 1) / d); }
-// Fills the lx_ fields of p for a launch of gemm_ldsx_kernel with chunks of KC on a grid of NB x MB column / row blocks
-inline void ldsx_remap(GemmP& p, int KC, unsigned NB, unsigned MB) {
-  p.lx_nchunks = p.K / KC / (p.ksplit > 1 ? p.ksplit : 1);
-  const unsigned per = NB >> 3;
-  p.lx_log2g = (per & 3) == 0 ? 2 : ((per & 1) == 0 ? 1 : 0);
-  p.lx_magic_mbg = magic_div(MB << p.lx_log2g);
-  p.lx_magic_mb = magic_div(MB);
-}
 
 // ---------------------------------------------------------------------------------------
 // bf16 MFMA GEMM.  One workgroup = 4 wavefronts.

@@ -11,6 +11,7 @@
 #include <utility>
 
 #include "../../paper_1811_03115_amd/csrc/bpd_host_logic.h"
+#include "../../paper_1811_03115_amd/csrc/bpd_tile_map.h"
 
 static long bad = 0;
 #define EXPECT(cond, ...) do { if (!(cond)) { ++bad; if (bad < 20) { fprintf(stderr, "violated: %s  [", #cond); fprintf(stderr, __VA_ARGS__); fprintf(stderr, "]\n"); } } } while (0)
@@ -112,6 +113,28 @@ int main() {
             EXPECT(!(nt == 4 && mt >= 4) || K % 128 == 0, "deep tile %d x %d with K = %d", mt, nt, K);
             ++tiles;
           }
-  printf("%ld configurations, %ld tile choices checked, %ld violations\n", configs, tiles, bad);
+  // the workgroup -> tile map of the LDS-staged GEMM: every (group, row block, column block) of a grid exactly once,
+  // for one group, K slices in z, and several groups (with and without the grouped map)
+  long grids = 0;
+  for (unsigned NB : {1u, 2u, 3u, 4u, 6u, 8u, 10u, 16u, 20u, 24u, 40u, 128u, 160u})
+    for (unsigned MB : {1u, 2u, 3u, 5u, 7u, 20u, 25u})
+      for (unsigned Z : {1u, 2u, 4u, 8u, 9u, 10u, 16u})
+        for (int ksplit : {1, 4}) {
+          if (ksplit > 1 && Z != 4) continue;
+          const LdsxMap m = ldsx_map_of(1024, 64, ksplit, NB, MB, Z);
+          EXPECT(m.nchunks == 16 / ksplit, "chunks %d", m.nchunks);
+          std::vector<char> seen((size_t)NB * MB * Z, 0);
+          for (unsigned z = 0; z < Z; ++z)
+            for (unsigned y = 0; y < MB; ++y)
+              for (unsigned x = 0; x < NB; ++x) {
+                int g = (int)z, by = -1, bx = -1;
+                ldsx_tile_of(m, NB, MB, x, y, z, g, by, bx);
+                const bool ok = g >= 0 && g < (int)Z && by >= 0 && by < (int)MB && bx >= 0 && bx < (int)NB;
+                EXPECT(ok, "map NB=%u MB=%u Z=%u (%u,%u,%u) -> g %d by %d bx %d", NB, MB, Z, x, y, z, g, by, bx);
+                if (ok) { char& c = seen[((size_t)g * MB + by) * NB + bx]; EXPECT(c == 0, "tile twice NB=%u MB=%u Z=%u", NB, MB, Z); c = 1; }
+              }
+          ++grids;
+        }
+  printf("%ld configurations, %ld tile choices, %ld grids checked, %ld violations\n", configs, tiles, grids, bad);
   return bad ? 1 : 0;
 }
