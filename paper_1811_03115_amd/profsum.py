@@ -128,7 +128,7 @@ def main():
             "#   the partial statistics), stream_gemm_kernel<16,true> = heads' output layers, attention_mfma_kernel<..,0> self-attention,",
             "#   <..,8> cross-attention with its query projection, stream_vocab_kernel = vocabulary projection + arg-max (100 rows)",
             "# C3 step (batch 32, 320 block rows): gemm_ldsx_kernel<8,4,64,true,..> = vocabulary projection + arg-max (3200 rows),",
-            "#   <7,4,64,false,..> = heads' hidden layers, <3,2,128,false> = heads' output layers (10 groups), <3,1,256> / <2,1,256> /",
+            "#   <7,4,64,false,..> = heads' hidden layers, <4,2,128,false> = heads' output layers (10 groups), <3,1,256> / <2,1,256> /",
             "#   <1,1,256> = layer GEMMs (the 4096-deep FFN output split 4 ways over K, summed by layernorm_kernel); two-phase mode adds",
             "#   gemm_ldsx_kernel<5,4,64,true> (320 and 288 rows), select_row_kernel, assemble_keys_kernel",
         ]
