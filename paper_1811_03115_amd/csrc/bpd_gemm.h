@@ -19,11 +19,22 @@
 // Epi); ms: (mu, rstd) of the workgroup's rows, in LDS.
 // pre_b / pre_r (with e.pre_epi): bias of the NT column tiles and residual of the MT x NT tiles, fetched at kernel entry.
 template <int MT, int NT, bool STATS, bool ROWAFF = false>
-__device__ __forceinline__ void store_tiles(const Epi& e, int g, const f32x4 (&acc)[MT][NT], int m0, int nt0,
+__device__ __forceinline__ void store_tiles(const Epi& e_in, int g, const f32x4 (&acc)[MT][NT], int m0, int nt0,
                                             int ntiles, int M, int lane, const float2* ms = nullptr,
                                             const float4* rc = nullptr, const float4* rd = nullptr,
-                                            const float4* pre_b = nullptr, const float4* pre_r = nullptr) {
-  const bool stats = STATS && e.mode == 0 && e.stats_out != nullptr;
+                                            const float4* pre_b = nullptr, const float4* pre_r = nullptr,
+                                            unsigned char* stage = nullptr) {
+  const bool stats = STATS && e_in.mode == 0 && e_in.stats_out != nullptr;
+  // bf16 output of four whole column tiles per wave (64 columns: 128 bytes per row), `stage`: 2 KB of LDS of this wave's
+  // own.  Stored straight from the accumulator layout a lane holds 4 columns (8 bytes) of a row and a store instruction
+  // touches 16 rows x 32 bytes; the 27 MB that the heads' hidden layers write at batch 32 went out at 1.4 TB/s that way
+  // (6.7 of the kernel's 33 us with one row block).  Instead the row tile's 16 x 64 values pass through LDS (16-byte
+  // segments XOR-ed with the row, conflict-free both ways) and leave as 16 bytes per lane: 8 rows x 128 bytes per store.
+  const bool wide = NT == 4 && stage != nullptr && e_in.mode == 0 && e_in.Ya != nullptr && nt0 + NT <= ntiles &&
+                    (e_in.ldya & 7) == 0 && (e_in.ya_g & 7) == 0 && ((size_t)e_in.Ya & 15) == 0;
+  bf16_t* ya = (bf16_t*)e_in.Ya;
+  Epi e = e_in;
+  if (wide) e.Ya = nullptr;                      // the per-tile stores below then skip the bf16 output
   float2 wsum[MT];
 #pragma unroll
   for (int t = 0; t < MT; ++t) wsum[t] = make_float2(0.f, 0.f);
@@ -55,12 +66,26 @@ __device__ __forceinline__ void store_tiles(const Epi& e, int g, const f32x4 (&a
           fin[0] = v[0]; fin[1] = v[1]; fin[2] = v[2]; fin[3] = v[3];
         }
       } else if (m < M) epi_store4f(e, g, m, n, v, fin);
+      if (wide) {                                 // (the direct stores above saw e.Ya == nullptr: see the copy of e below)
+        const int lr_ = lane & 15, sg = (u * 2 + (lane >> 5)) ^ (lr_ & 7);
+        *(uint2*)(stage + lr_ * 128 + sg * 16 + ((lane >> 4) & 1) * 8) =
+            make_uint2((unsigned)f2bf(fin[0]) | ((unsigned)f2bf(fin[1]) << 16), (unsigned)f2bf(fin[2]) | ((unsigned)f2bf(fin[3]) << 16));
+      }
       if (stats) {
         float sv = (fin[0] + fin[1]) + (fin[2] + fin[3]);
         float qv = (fin[0] * fin[0] + fin[1] * fin[1]) + (fin[2] * fin[2] + fin[3] * fin[3]);
         sv += __shfl_xor(sv, 16, 64); sv += __shfl_xor(sv, 32, 64);
         qv += __shfl_xor(qv, 16, 64); qv += __shfl_xor(qv, 32, 64);
         wsum[t].x += sv; wsum[t].y += qv;        // this wave's NT tiles lie in one 64-column block
+      }
+    }
+    if (wide) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int r = h * 8 + (lane >> 3), sgr = lane & 7;
+        const uint4 w = *(const uint4*)(stage + r * 128 + ((sgr ^ (r & 7)) * 16));
+        const int mm = m0 + t * 16 + r;
+        if (mm < M) *(uint4*)(ya + g * e.ya_g + (long)mm * e.ldya + nt0 * 16 + sgr * 8) = w;
       }
     }
   }
@@ -973,7 +998,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
 #undef BPD_NORM1
 #undef BPD_LOAD_X
     if (nt0 >= ntiles) return;
-    store_tiles<MT, NT, STATS>(e, g, acc, m0, nt0, ntiles, p.M, lane, nullptr, nullptr, nullptr, XPREF ? xpre_b : nullptr, XPREF ? xpre_r : nullptr);
+    store_tiles<MT, NT, STATS>(e, g, acc, m0, nt0, ntiles, p.M, lane, nullptr, nullptr, nullptr, XPREF ? xpre_b : nullptr, XPREF ? xpre_r : nullptr, smem_raw + wave * 2048);
     return;
   }
   // The direct-to-LDS loads of the loop are issued from inline assembly (lds_dma16) and waited for by hand (s_waitcnt
@@ -1219,5 +1244,5 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(ldsx_waves_
     }
     return;
   }
-  store_tiles<MT, NT, STATS, ROWAFF>(e, g, acc, m0, nt0, ntiles, p.M, lane, ra_ms, ra_c4, ra_d4, PREF ? pre_b : nullptr, PREF ? pre_r : nullptr);
+  store_tiles<MT, NT, STATS, ROWAFF>(e, g, acc, m0, nt0, ntiles, p.M, lane, ra_ms, ra_c4, ra_d4, PREF ? pre_b : nullptr, PREF ? pre_r : nullptr, smem_raw + wave * 2048);
 }
