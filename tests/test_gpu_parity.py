@@ -456,6 +456,13 @@ ODD_SHAPES = [
     # the raw bf16 copy of the residual stream); 153 rows = nine 16-row tiles and a ragged one
     wl.Config("odd-fold153", 37, 1, 3, 256, 4, 512, 528, 9, 17, 6, 24, "bf16", 2, src_len_kind="lognormal"),
     wl.Config("loc-b20", 35, 1, 1, 128, 2, 256, 528, 4, 20, 7, 30, "bf16", 2, src_len_kind="lognormal", local_q=5, local_m=0),
+    # the widest model bpd_create accepts (d = 2048) on one row tile, and d = 1536 on 30 rows with a 2048-deep FFN
+    # output: beyond d = 1024 LayerNorm is a kernel of its own (a row of up to 2048 floats per wavefront), the accept
+    # kernel does not embed the next block and the cross-attention queries come from a GEMM
+    wl.Config("odd-d2048", 38, 1, 1, 2048, 32, 1024, 528, 4, 2, 6, 16, "bf16", 2, src_len_kind="lognormal"),
+    wl.Config("odd-d1536", 39, 1, 1, 1536, 24, 2048, 528, 5, 6, 7, 15, "bf16", 2, src_len_kind="lognormal"),
+    # many sequences: 96 x 10 = 960 block rows (seven and a half 128-row blocks in every GEMM, 96 accept workgroups)
+    wl.Config("odd-b96", 40, 1, 1, 128, 2, 256, 528, 10, 96, 5, 12, "bf16", 2, src_len_kind="lognormal"),
 ]
 
 
