@@ -235,9 +235,10 @@ void launch_stream(const bpd_ctx* ctx, const GemmP& p, const Epi& e, int groups)
 bool embed_in_accept(const bpd_ctx* ctx) {
   return ctx->cfg.dtype == BPD_BF16 && ctx->cfg.d_model <= 1024;
 }
-// LayerNorm statistics ride along with the residual stream when the whole block is one MFMA row tile
+// LayerNorm statistics ride along with the residual stream when the whole block is one MFMA row tile and every GEMM
+// that updates the stream is one the skinny kernel takes (it is the one that writes them: K = d_ff must fit it)
 bool stats_path(const bpd_ctx* ctx, int M) {
-  return ctx->cfg.dtype == BPD_BF16 && M <= 16 && ctx->cfg.d_model <= 1024;
+  return ctx->cfg.dtype == BPD_BF16 && M <= 16 && ctx->cfg.d_model <= 1024 && ctx->cfg.d_ff <= 4096;
 }
 
 // ---- ldsx path: many rows ---------------------------------------------------------------
@@ -798,7 +799,7 @@ int forward(bpd_ctx* ctx, int R, int k, int zero_input, float* logits) {
     }
   }
   { PhaseTimer t(ctx, BPD_PHASE_EMPTY); }       // calibration of the event bracketing itself
-  if (ctx->two_phase && R == k && k > 1 && !sp && !logits && c.dtype == BPD_BF16) return heads_two_phase(ctx, k);
+  if (ctx->two_phase && R == k && k > 1 && M > 16 && !logits && c.dtype == BPD_BF16) return heads_two_phase(ctx, k);
   // the k residual FFN heads: final LayerNorm + hidden layers side by side (h kept in fp32
   // for the residual), then one output layer per head
   {

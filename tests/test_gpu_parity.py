@@ -289,13 +289,14 @@ def test_two_phase_scoring_on_gpu(which):
 
 
 @pytest.mark.parametrize("which,max_batch,k", [("M-bf16", None, None), ("M-bf16", 9, 4), ("odd-fold153", None, None),
-                                               ("odd-fold153", 20, 5)])
+                                               ("odd-fold153", 20, 5), ("odd-d2048", None, None), ("odd-d1536", None, None)])
 def test_two_phase_scoring_against_oracle(which, max_batch, k):
     """Two-phase scoring teacher-forced against the oracle: head 1 of every block row and all heads of row k-hat lie
     within tolerance of the oracle's logits (Section 4 fixes what one invocation must yield: the verification of the
     block and the next proposals), every other table entry is empty, accepted lengths / appended tokens / next
     proposals follow.  Also with fewer sequences than max_batch and fewer heads than k_max (the second-phase keys then
-    do not start where a full-size step would put them)."""
+    do not start where a full-size step would put them), and beyond d = 1024: 8 block rows (the mode is ignored up to
+    16 rows, whatever the width: the table is full) and 30 block rows."""
     cfg = {c.name: c for c in [MID_BF16] + ODD_SHAPES}[which]
     weights = wl.make_weights(cfg)
     ctx = gpu_context(cfg, weights, max_batch=max_batch)
@@ -462,6 +463,10 @@ ODD_SHAPES = [
     wl.Config("odd-d2048", 38, 1, 1, 2048, 32, 1024, 528, 4, 2, 6, 16, "bf16", 2, src_len_kind="lognormal"),
     wl.Config("odd-d1536", 39, 1, 1, 1536, 24, 2048, 528, 5, 6, 7, 15, "bf16", 2, src_len_kind="lognormal"),
     # many sequences: 96 x 10 = 960 block rows (seven and a half 128-row blocks in every GEMM, 96 accept workgroups)
+    # a feed-forward layer deeper than the one-tile kernels take (K = d_ff > 4096) under a block of at most 16 rows:
+    # 4128 is no multiple of 64 either (plain MFMA kernel), 4160 is (LDS-staged kernel on a single ragged row tile)
+    wl.Config("odd-F4128", 41, 1, 2, 128, 8, 4128, 528, 4, 3, 6, 14, "bf16", 2, src_len_kind="lognormal"),
+    wl.Config("odd-F4160", 42, 1, 1, 256, 4, 4160, 528, 5, 2, 6, 14, "bf16", 2, src_len_kind="lognormal"),
     wl.Config("odd-b96", 40, 1, 1, 128, 2, 256, 528, 10, 96, 5, 12, "bf16", 2, src_len_kind="lognormal"),
 ]
 
