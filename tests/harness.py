@@ -4,7 +4,10 @@ the CPU oracle side by side on the same seeded inputs.
 Comparison rules (stated once here, used by every test):
   * integers that do not depend on floating point (accepted lengths under an imposed
     schedule, appended tokens given the proposals, counters) must be bit-identical;
-  * logits: |gpu - oracle| <= TOL[dtype]  (1e-4 in fp32 mode, 2e-2 in bf16 mode);
+  * logits: |gpu - oracle| <= TOL[dtype]  (1e-4 in fp32 mode, 2e-2 in bf16 mode) at every width the paper uses
+    (d <= 1024).  bf16 models wider than that: 2e-2 * sqrt(d / 1024) (tol_of): the error is the rounding of the GEMM
+    inputs to bf16, a sum over d terms of independent roundings, and grows like sqrt(d) as the logits themselves do
+    with weights of fixed variance;
   * an argmax entry is right iff oracle_logit[gpu_choice] >= max(oracle_logit) - 2*TOL:
     where the oracle's top-1/top-2 margin is at least 2*TOL this forces equality, inside
     the margin either token is a correct answer at that precision;
@@ -20,6 +23,12 @@ import workloads as wl
 from oracle import CombinedModel, scorers
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def tol_of(cfg):
+    if cfg.dtype == "bf16" and cfg.d_model > 1024:
+        return TOL["bf16"] * (cfg.d_model / 1024.0) ** 0.5
+    return TOL[cfg.dtype]
 
 
 def oracle_model(cfg, weights):
@@ -53,7 +62,7 @@ class LockStep:
         self.cfg, self.ctx = cfg, ctx
         self.k = cfg.k if k is None else k
         self.B = src.shape[0]
-        self.tol = TOL[cfg.dtype]
+        self.tol = tol_of(cfg)
         self.model = oracle_model(cfg, weights)
         self.sample = list(range(self.B)) if sample is None else list(sample)
         self.max_len = np.asarray(max_len)

@@ -534,6 +534,59 @@ def test_lockstep_random_shapes(seed):
     print(cfg.name, "max logit err", ls.max_logit_err, "bit-identical argmax fraction", np.mean(ls.match))
 
 
+def random_wide_config(seed):
+    """Dimensions drawn from the whole range bpd_create accepts: up to 32 heads of 64 (d = 2048), d_ff up to 4128 (past
+    what the one-tile kernels take), vocabularies up to 9600, up to 48 sequences, k up to 16."""
+    rng = np.random.default_rng(7000 + seed)
+    dtype = "f32" if seed % 7 == 3 else "bf16"
+    dh = 16 if (dtype == "f32" or rng.random() < 0.2) else 64
+    heads = int(rng.integers(1, 9)) if dtype == "f32" else int(rng.integers(1, 17 if dh == 16 else 33))
+    d = dh * heads
+    if d % 32:
+        heads += 1
+        d = dh * heads
+    F = 32 * int(rng.integers(1, 130))
+    V = 16 * int(rng.integers(2, 600))
+    k = int(rng.integers(1, 17))
+    B = int(rng.integers(1, 49))
+    if dtype == "f32":                               # one thread per output: keep the scalar kernels' share of the run small
+        B, F, V = min(B, 8), min(F, 512), min(V, 2048)
+    cfg = wl.Config(f"wide{seed}-{dtype}-d{d}-h{heads}-F{F}-V{V}-k{k}-B{B}", 140 + seed, int(rng.integers(1, 3)), int(rng.integers(1, 3)),
+                    d, heads, F, V, k, B, int(rng.integers(1, 41)), int(rng.integers(5, 41)), dtype, 2,
+                    src_kind="uniform3", src_len_kind="lognormal")
+    if seed % 3 == 1:
+        lq, lm = int(rng.integers(1, 9)), int(rng.integers(0, 9))
+        cfg = wl.scaled(cfg, name=cfg.name + f"-loc{lq}+{lm}", local_q=lq, local_m=lm)
+    return cfg
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("seed", range(24))
+def test_lockstep_random_wide_shapes(seed):
+    """Random shapes over the whole accepted range, teacher-forced against the oracle on two sequences; every fifth
+    context is larger than its batch, every fifth decodes with fewer heads than k_max, every second bf16 case scores in
+    two phases, every third ends with a top-n step."""
+    cfg = random_wide_config(seed)
+    rng = np.random.default_rng(99 + seed)
+    weights = wl.make_weights(cfg, std=0.08 if cfg.dtype == "f32" else 0.02)
+    max_batch = cfg.batch + int(rng.integers(0, 9)) if seed % 5 == 0 else None
+    k = int(rng.integers(1, cfg.k + 1)) if seed % 5 == 1 else None
+    ctx = gpu_context(cfg, weights, max_batch=max_batch)
+    src, n = ragged_sources(cfg, 11 + seed)
+    max_len = rng.integers(1, cfg.max_out + 1, size=cfg.batch).astype(np.int32)
+    sample = sorted(set(rng.integers(0, cfg.batch, size=2).tolist()))
+    ls = LockStep(cfg, weights, ctx, src, n, max_len, sample=sample, k=k)
+    sched = wl.make_schedule(cfg, min(2.0, ls.k), 8, seed=seed, k=ls.k)
+    for s in range(2):
+        ls.step(imposed=sched[s])
+    two_phase = cfg.dtype == "bf16" and seed % 2 == 0
+    for s in range(2):
+        ls.step(imposed=None, two_phase=two_phase, check_logits=not two_phase)
+    if cfg.dtype == "bf16" and seed % 3 == 0:
+        ls.step(top_n=int(rng.integers(2, 40)), two_phase=two_phase, check_logits=False)
+    print(cfg.name, "max logit err", ls.max_logit_err, "bit-identical argmax fraction", np.mean(ls.match))
+
+
 @pytest.mark.gpu
 @pytest.mark.parametrize("which", ["S-bf16", "odd-dh16", "odd-stream9"])
 def test_accept_kernel_embedding_next_block_changes_nothing(which):
